@@ -1,0 +1,170 @@
+"""Python face of the CPU oracle (``ralm_oracle.c``).  TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It imports nothing from the HIP package
+and shares no code with it.  All arrays are numpy, on the host.
+
+What each function computes is stated in the C file; this wrapper only checks
+shapes, builds the shared object with gcc when it is missing, and provides the
+chunk-streaming form of the same brute-force retrieval for datastores that do
+not fit in host memory at once (scores of every row of every chunk, then a full
+sort of carry + chunk by (score descending, id ascending)).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Iterable, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ralm_oracle.c")
+_LIB = os.path.join(_HERE, "libralm_oracle.so")
+
+F32, BF16, F16 = 0, 1, 2
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP for row-level threads)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-shared", "-fPIC",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        L.ralm_oracle_threads.restype = ctypes.c_int
+        L.ralm_oracle_scores.argtypes = [vp, vp, ctypes.c_int, i64, i32, i64, vp]
+        L.ralm_oracle_scores.restype = None
+        L.ralm_oracle_retrieve_topk.argtypes = [vp, i64, vp, ctypes.c_int, i64, i32, i64, i32, vp, vp]
+        L.ralm_oracle_retrieve_topk.restype = ctypes.c_int
+        L.ralm_oracle_cache_lookup.argtypes = [vp, vp, i32, i64, vp, vp, vp, ctypes.c_int, i64, i32,
+                                               i64, vp, vp]
+        L.ralm_oracle_cache_lookup.restype = ctypes.c_int
+        L.ralm_oracle_verify.argtypes = [vp, vp, i64, vp, i64, vp]
+        L.ralm_oracle_verify.restype = None
+        _lib = L
+    return _lib
+
+
+def threads() -> int:
+    return int(_load().ralm_oracle_threads())
+
+
+def _store(X: np.ndarray) -> Tuple[np.ndarray, int]:
+    """Accept fp32, fp16, or bf16-as-uint16 (pass dtype tag explicitly for bf16)."""
+    if X.dtype == np.float32:
+        return np.ascontiguousarray(X), F32
+    if X.dtype == np.float16:
+        return np.ascontiguousarray(X), F16
+    raise TypeError(f"datastore dtype {X.dtype} not supported (use float32/float16, or bf16_store())")
+
+
+class bf16_store:
+    """Wrap a uint16 array holding bf16 bit patterns."""
+
+    def __init__(self, bits: np.ndarray):
+        assert bits.dtype == np.uint16
+        self.bits = np.ascontiguousarray(bits)
+
+
+def _store_any(X):
+    if isinstance(X, bf16_store):
+        return X.bits, BF16
+    return _store(X)
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def scores(q: np.ndarray, X) -> np.ndarray:
+    """All inner products of ONE query with the rows of X; fp32 [n]."""
+    Xa, tag = _store_any(X)
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    n, d = Xa.shape
+    assert q.shape == (d,)
+    out = np.empty(n, dtype=np.float32)
+    _load().ralm_oracle_scores(_ptr(q), _ptr(Xa), tag, n, d, d, _ptr(out))
+    return out
+
+
+def retrieve_topk(queries: np.ndarray, X, k: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Exact top-k of every query over the whole datastore: (ids int32 [Q,k], scores fp32 [Q,k])."""
+    Xa, tag = _store_any(X)
+    queries = np.ascontiguousarray(queries, dtype=np.float32)
+    Q, d = queries.shape
+    N, d2 = Xa.shape
+    assert d == d2
+    ids = np.empty((Q, k), dtype=np.int32)
+    sc = np.empty((Q, k), dtype=np.float32)
+    rc = _load().ralm_oracle_retrieve_topk(_ptr(queries), Q, _ptr(Xa), tag, N, d, d, k, _ptr(ids), _ptr(sc))
+    if rc != 0:
+        raise ValueError("oracle retrieve_topk: bad arguments")
+    return ids, sc
+
+
+def retrieve_topk_stream(queries: np.ndarray, chunks: Iterable[Tuple[int, object]], k: int
+                         ) -> Tuple[np.ndarray, np.ndarray]:
+    """Same result as ``retrieve_topk`` for a datastore delivered as (base_row, rows) chunks.
+
+    Per query a carry list of the best k (score, id) pairs so far is kept; for
+    each chunk all of its scores are computed, carry + chunk is fully sorted by
+    (score descending, id ascending) and cut to k.
+    """
+    queries = np.ascontiguousarray(queries, dtype=np.float32)
+    Q = queries.shape[0]
+    carry_s = [np.empty(0, np.float32) for _ in range(Q)]
+    carry_i = [np.empty(0, np.int64) for _ in range(Q)]
+    for base, rows in chunks:
+        n = (rows.bits if isinstance(rows, bf16_store) else rows).shape[0]
+        ids_here = np.arange(base, base + n, dtype=np.int64)
+        for i in range(Q):
+            s = np.concatenate([carry_s[i], scores(queries[i], rows)])
+            j = np.concatenate([carry_i[i], ids_here])
+            order = np.lexsort((j, -s.astype(np.float64)))[:k]
+            carry_s[i], carry_i[i] = s[order], j[order]
+    ids = np.stack([c.astype(np.int32) for c in carry_i])
+    sc = np.stack(carry_s)
+    return ids, sc
+
+
+def cache_lookup(cache_ids: np.ndarray, cache_len: np.ndarray, queries: np.ndarray,
+                 q_offsets: np.ndarray, X) -> Tuple[np.ndarray, np.ndarray]:
+    """Speculative top-1 of each query over its request's cached row ids."""
+    Xa, tag = _store_any(X)
+    cache_ids = np.ascontiguousarray(cache_ids, dtype=np.int32)
+    cache_len = np.ascontiguousarray(cache_len, dtype=np.int32)
+    queries = np.ascontiguousarray(queries, dtype=np.float32)
+    q_offsets = np.ascontiguousarray(q_offsets, dtype=np.int64)
+    R, C = cache_ids.shape
+    N, d = Xa.shape
+    Qt = int(q_offsets[-1]) if R > 0 else 0
+    assert queries.shape == (Qt, d) and q_offsets.shape == (R + 1,)
+    ids = np.empty(Qt, dtype=np.int32)
+    sc = np.empty(Qt, dtype=np.float32)
+    rc = _load().ralm_oracle_cache_lookup(_ptr(cache_ids), _ptr(cache_len), C, R, _ptr(queries),
+                                          _ptr(q_offsets), _ptr(Xa), tag, N, d, d, _ptr(ids), _ptr(sc))
+    if rc != 0:
+        raise ValueError("oracle cache_lookup: bad arguments")
+    return ids, sc
+
+
+def verify(spec_ids: np.ndarray, true_ids: np.ndarray, q_offsets: np.ndarray,
+           true_stride: int = 1) -> np.ndarray:
+    """First mismatch per request (0-based; the stride itself when all match)."""
+    spec_ids = np.ascontiguousarray(spec_ids, dtype=np.int32)
+    true_ids = np.ascontiguousarray(true_ids, dtype=np.int32)
+    q_offsets = np.ascontiguousarray(q_offsets, dtype=np.int64)
+    R = q_offsets.shape[0] - 1
+    out = np.empty(R, dtype=np.int32)
+    _load().ralm_oracle_verify(_ptr(spec_ids), _ptr(true_ids), true_stride, _ptr(q_offsets), R, _ptr(out))
+    return out

@@ -1,0 +1,207 @@
+/*
+ * CPU oracle for the RaLMSpec retrieval hot path.  TEST INFRASTRUCTURE ONLY:
+ * it exists so that tests, the smoke check and the benchmark's CPU-baseline leg
+ * can say what the right answer is.  It shares no code with the HIP library
+ * and the product never calls it.
+ *
+ * Everything here is the plain definition written out, slow and obvious:
+ *
+ *  - knowledge-base retrieval C.retrieve(q_1..q_s) of Alg. 1 (the batched
+ *    verification step) with the exact dense retriever of Section 5.1
+ *    ("Retrievers"): score every datastore row against every query by inner
+ *    product, sort ALL rows by (score descending, row id ascending), return the
+ *    first k.  Batched retrieval is by definition the same as retrieving for
+ *    each query on its own (Section 1: the method preserves the outputs).
+ *  - speculative retrieval Q.retrieve(q) of Alg. 1: the same ranking with the
+ *    same metric, restricted to the entries of the request's local cache
+ *    (Section 3, "Speculative retrieval", and the caption of Fig. 2), top-1.
+ *  - the verification compare m = argmin_i (d^_i != d_i) of Alg. 1, per request.
+ *
+ * Readings where the paper is silent:
+ *  - metric: inner product (dense passage retrieval scores, raw inner product
+ *    for KNN-LM keys);
+ *  - ties: equal scores are ordered by the lower row id, everywhere;
+ *  - precision: inputs are fp32 (or fp16/bf16 keys widened exactly); each
+ *    product is formed in double, the d products are added left to right in
+ *    double, and the sum is rounded once to fp32.  Comparisons are made on
+ *    that fp32 value;
+ *  - first mismatch is reported 0-based, and equals the request's stride when
+ *    every speculated id matches.
+ *
+ * Threads (OpenMP, if compiled in) only split independent rows between cores;
+ * no blocking, no reordering of any sum.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
+
+typedef struct {
+    float score;
+    int32_t id;
+} scored_t;
+
+/* widen one stored element to fp32 exactly */
+static float widen_f16(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h >> 15) << 31;
+    int exp = (h >> 10) & 0x1F;
+    uint32_t man = h & 0x3FF;
+    float mag;
+    if (exp == 0)
+        mag = ldexpf((float)man, -24); /* subnormal or zero */
+    else if (exp == 31)
+        mag = man ? NAN : INFINITY;
+    else
+        mag = ldexpf((float)(man | 0x400), exp - 25);
+    uint32_t bits;
+    memcpy(&bits, &mag, 4);
+    bits |= sign;
+    memcpy(&mag, &bits, 4);
+    return mag;
+}
+
+static float widen_bf16(uint16_t b)
+{
+    uint32_t bits = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &bits, 4);
+    return f;
+}
+
+static float element(const void *X, int dtype, int64_t index)
+{
+    if (dtype == ORACLE_F32)
+        return ((const float *)X)[index];
+    if (dtype == ORACLE_F16)
+        return widen_f16(((const uint16_t *)X)[index]);
+    return widen_bf16(((const uint16_t *)X)[index]);
+}
+
+/* <q, x_row>: products and sum in double, one rounding to fp32 */
+static float inner_product(const float *q, const void *X, int dtype, int64_t row, int64_t ld,
+                           int32_t d)
+{
+    double sum = 0.0;
+    for (int32_t c = 0; c < d; ++c)
+        sum += (double)q[c] * (double)element(X, dtype, row * ld + c);
+    return (float)sum;
+}
+
+/* (score descending, id ascending) */
+static int by_score_then_id(const void *pa, const void *pb)
+{
+    const scored_t *a = (const scored_t *)pa, *b = (const scored_t *)pb;
+    if (a->score > b->score) return -1;
+    if (a->score < b->score) return 1;
+    if (a->id < b->id) return -1;
+    if (a->id > b->id) return 1;
+    return 0;
+}
+
+int ralm_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* scores[j] = <q, X[j]> for j in [0, n): one query against a block of rows */
+void ralm_oracle_scores(const float *q, const void *X, int dtype, int64_t n, int32_t d,
+                        int64_t ld, float *scores)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n; ++j)
+        scores[j] = inner_product(q, X, dtype, j, ld, d);
+}
+
+/*
+ * Exact dense retrieval: for each of Q queries, all N scores, a full sort,
+ * the first k.  out_ids/out_scores are [Q, k] row-major.  Returns 0, or -1 on
+ * bad arguments / allocation failure.
+ */
+int ralm_oracle_retrieve_topk(const float *queries, int64_t Q, const void *X, int dtype,
+                              int64_t N, int32_t d, int64_t ld, int32_t k, int32_t *out_ids,
+                              float *out_scores)
+{
+    if (Q < 0 || N < 1 || d < 1 || k < 1 || k > N || ld < d) return -1;
+    scored_t *all = (scored_t *)malloc((size_t)N * sizeof(scored_t));
+    if (!all) return -1;
+    for (int64_t i = 0; i < Q; ++i) {
+        const float *q = queries + i * (int64_t)d;
+#pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < N; ++j) {
+            all[j].score = inner_product(q, X, dtype, j, ld, d);
+            all[j].id = (int32_t)j;
+        }
+        qsort(all, (size_t)N, sizeof(scored_t), by_score_then_id);
+        for (int32_t r = 0; r < k; ++r) {
+            out_ids[i * k + r] = all[r].id;
+            out_scores[i * k + r] = all[r].score;
+        }
+    }
+    free(all);
+    return 0;
+}
+
+/*
+ * Speculative retrieval from the per-request local cache.  Request r owns the
+ * row ids cache_ids[r*C .. r*C + cache_len[r]) and the queries
+ * q_offsets[r] .. q_offsets[r+1].  For each query: rank the cached rows with
+ * the retriever's own metric and take the first.  An empty cache gives id -1
+ * and score -inf.
+ */
+int ralm_oracle_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C,
+                             int64_t R, const float *queries, const int64_t *q_offsets,
+                             const void *X, int dtype, int64_t N, int32_t d, int64_t ld,
+                             int32_t *spec_ids, float *spec_scores)
+{
+    if (R < 0 || C < 0 || d < 1 || ld < d) return -1;
+    scored_t *ranked = (scored_t *)malloc((size_t)(C > 0 ? C : 1) * sizeof(scored_t));
+    if (!ranked) return -1;
+    for (int64_t r = 0; r < R; ++r) {
+        int32_t len = cache_len[r];
+        if (len < 0 || len > C) { free(ranked); return -1; }
+        for (int64_t i = q_offsets[r]; i < q_offsets[r + 1]; ++i) {
+            const float *q = queries + i * (int64_t)d;
+            for (int32_t e = 0; e < len; ++e) {
+                int32_t id = cache_ids[r * (int64_t)C + e];
+                if (id < 0 || id >= N) { free(ranked); return -1; }
+                ranked[e].score = inner_product(q, X, dtype, id, ld, d);
+                ranked[e].id = id;
+            }
+            qsort(ranked, (size_t)len, sizeof(scored_t), by_score_then_id);
+            spec_ids[i] = len ? ranked[0].id : -1;
+            spec_scores[i] = len ? ranked[0].score : -INFINITY;
+        }
+    }
+    free(ranked);
+    return 0;
+}
+
+/*
+ * Verification compare.  Request r speculated ids spec[q_offsets[r] + i] for
+ * its steps i = 0 .. s_r - 1; the knowledge base returned
+ * truth[(q_offsets[r] + i) * true_stride] for the same steps.  first_mismatch[r]
+ * is the smallest i where they differ, or s_r when none does.
+ */
+void ralm_oracle_verify(const int32_t *spec, const int32_t *truth, int64_t true_stride,
+                        const int64_t *q_offsets, int64_t R, int32_t *first_mismatch)
+{
+    for (int64_t r = 0; r < R; ++r) {
+        int64_t s = q_offsets[r + 1] - q_offsets[r];
+        int64_t m = s;
+        for (int64_t i = 0; i < s; ++i) {
+            int64_t at = q_offsets[r] + i;
+            if (spec[at] != truth[at * true_stride]) { m = i; break; }
+        }
+        first_mismatch[r] = (int32_t)m;
+    }
+}
