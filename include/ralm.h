@@ -1,0 +1,210 @@
+/*
+ * ralm.h — C ABI of the MI355X (gfx950) retrieval hot path of RaLMSpec
+ * (arXiv 2401.14021, "Accelerating Retrieval-augmented Language Model Serving
+ * with Speculation").
+ *
+ * Three operations of the paper's serving loop (Alg. 1) are implemented:
+ *
+ *   C.retrieve(q_1..q_s)   batched exact knowledge-base retrieval, the
+ *                          verification step        -> ralm_retrieve_topk[_ex]
+ *   Q.retrieve(q_i)        speculative retrieval from the request's local
+ *                          cache, top-1             -> ralm_cache_lookup
+ *   m = argmin_i d^_i!=d_i first mis-speculated step -> ralm_verify
+ *
+ * General conventions
+ *   - Unless a parameter says "host", every data pointer is a DEVICE pointer
+ *     owned by the caller.  The library keeps no reference after the call's
+ *     work has run and never frees caller memory.
+ *   - Calls enqueue work on the given HIP stream (a hipStream_t passed as
+ *     void*; NULL = the default stream) and return without synchronising,
+ *     except where stated.  Work of one call is ordered on that stream.
+ *   - Matrices are row-major.  ids are int32 row numbers of the datastore
+ *     (N < 2^31); sizes are int64.
+ *   - The ranking is always (score descending, row id ascending): equal scores
+ *     go to the lower id.  The paper does not define ties; this is this
+ *     library's rule, at every stage.
+ *   - The score is the inner product.  Final scores (outputs) are the fp32
+ *     rounding of a sum formed in double from fp32 (or exactly widened
+ *     fp16/bf16) inputs.
+ *   - Argument errors are detected on the host before anything is launched and
+ *     are reported as a status; ralm_last_error() gives the text.  Inputs are
+ *     assumed finite (NaN/Inf: behaviour unspecified).
+ */
+#ifndef RALM_H
+#define RALM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RALM_OK = 0,
+    RALM_ERR_NULL = 1,      /* a required pointer is NULL */
+    RALM_ERR_SHAPE = 2,     /* Q, N, d, R, C or a stride is out of range */
+    RALM_ERR_K = 3,         /* k < 1, k > N, k > RALM_MAX_K, k' < k or k' > RALM_MAX_K_PRIME */
+    RALM_ERR_DTYPE = 4,     /* dtype tag unknown or not allowed in that slot */
+    RALM_ERR_ALIGN = 5,     /* base pointer or row pitch not 16-byte aligned */
+    RALM_ERR_WORKSPACE = 6, /* workspace NULL, misaligned or too small */
+    RALM_ERR_RANGE = 7,     /* a count (Qt, true_stride) is negative or does not fit */
+    RALM_ERR_DEVICE = 8,    /* a HIP call failed (text in ralm_last_error) */
+    RALM_ERR_OVERFLOW = 9   /* a candidate buffer overflowed (degenerate input); see below */
+} ralm_status;
+
+typedef enum { RALM_F32 = 0, RALM_BF16 = 1, RALM_F16 = 2 } ralm_dtype;
+
+#define RALM_MAX_K 1024
+#define RALM_MAX_K_PRIME 4096
+
+/*
+ * The knowledge base as the flat index of an exact dense retriever
+ * (Section 5.1, "Retrievers"): N key vectors of dimension d.
+ *
+ *   exact  the keys that define the right answer: fp32 [N, d], or fp16 [N, d]
+ *          (KNN-LM keys; widened exactly).  Scores returned to the caller are
+ *          computed from this copy.
+ *   scan   the copy the full scan reads: bf16 or fp16 roundings of the exact
+ *          keys (build with ralm_build_scan_copy), or the exact copy itself
+ *          (fp32 is rounded to bf16 on the fly; fp16 is used as is).
+ *          NULL means "use the exact copy".
+ *   *_stride  row pitch in ELEMENTS (0 = d).  Pitch in bytes and both base
+ *          pointers must be multiples of 16.  d must be a multiple of 8.
+ */
+typedef struct {
+    const void *exact;
+    int32_t exact_dtype;    /* RALM_F32 or RALM_F16 */
+    const void *scan;       /* may be NULL */
+    int32_t scan_dtype;     /* RALM_BF16, RALM_F16 or RALM_F32 */
+    int64_t N;
+    int32_t d;
+    int64_t exact_stride;
+    int64_t scan_stride;
+} ralm_datastore_t;
+
+/*
+ * Batched exact retrieval, simplest form (Alg. 1, the batched verification
+ * step; exact dense retriever of Section 5.1).
+ *
+ *   queries    device fp32 [Q, d]
+ *   datastore  device fp32 [N, d]; it is both the exact and the scanned copy
+ *   out_ids    device int32 [Q, k]; out_scores device fp32 [Q, k]; each row
+ *              ranked best first.
+ *
+ * Runs on the default stream, allocates and frees its own workspace, and
+ * synchronises before returning (so RALM_ERR_OVERFLOW can be reported).
+ */
+ralm_status ralm_retrieve_topk(const float *queries, int64_t Q, const float *datastore, int64_t N,
+                               int32_t d, int32_t k, int32_t *out_ids, float *out_scores);
+
+/* Bytes of workspace ralm_retrieve_topk_ex needs for (Q, ds, k, k_prime); 0 on bad arguments. */
+size_t ralm_workspace_bytes(int64_t Q, const ralm_datastore_t *ds, int32_t k, int32_t k_prime);
+
+/*
+ * Batched exact retrieval, full form.  How it gets the exact answer from a
+ * low-precision scan: every row is scored in the scan dtype on the matrix
+ * cores with fp32 accumulation; per query the k' (>= k) best scan scores are
+ * kept; those k' rows are re-scored from the exact copy and the best k of them
+ * are returned.  k_prime = 0 picks a default (64 for k <= 32, else the power
+ * of two >= 2k).
+ *
+ *   queries     device fp32 [Q, d] (host code never reads it)
+ *   ds          HOST struct of device pointers
+ *   out_ids / out_scores  device [Q, k] as above
+ *   out_margin  optional device fp32 [Q] (may be NULL): exact score of the
+ *               returned rank-k row minus the scan score of the k'-th kept
+ *               candidate.  A positive margin larger than the scan's rounding
+ *               error proves that no row outside the candidates can belong in
+ *               the top k.
+ *   workspace   device scratch, 256-byte aligned, >= ralm_workspace_bytes();
+ *               contents are undefined between calls; two calls that overlap
+ *               in time must not share it.
+ *   stream      hipStream_t
+ *
+ * Does not synchronise.  If the thresholded candidate buffer of some query
+ * overflows (only for inputs with enormous numbers of equal scores, or rows
+ * ordered adversarially), that query's outputs are set to id -1 / score NaN
+ * and the overflow is counted; read it with ralm_workspace_overflows().
+ */
+ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_datastore_t *ds,
+                                  int32_t k, int32_t k_prime, int32_t *out_ids, float *out_scores,
+                                  float *out_margin, void *workspace, size_t workspace_bytes,
+                                  void *stream);
+
+/*
+ * Number of queries of the LAST ralm_retrieve_topk_ex call on this workspace
+ * whose candidate buffer overflowed.  Synchronises `stream` and copies one
+ * int to the host (*count is a host pointer).
+ */
+ralm_status ralm_workspace_overflows(const void *workspace, void *stream, int32_t *count);
+
+/*
+ * Build the low-precision scan copy of a datastore: dst[j, c] = round-to-
+ * nearest-even(src[j, c]) in dst_dtype (RALM_BF16 or RALM_F16).  src is device
+ * fp32 [N, d] with pitch src_stride elements, dst device [N, d] with pitch
+ * dst_stride elements (0 = d for both).
+ */
+ralm_status ralm_build_scan_copy(const float *src, int64_t src_stride, void *dst, int32_t dst_dtype,
+                                 int64_t dst_stride, int64_t N, int32_t d, void *stream);
+
+/*
+ * Speculative retrieval from the per-request local caches (Alg. 1, the
+ * speculative retrieval step; Section 3 "Speculative retrieval"; Fig. 2: the
+ * cache is ranked with the retriever's own metric).  A cache holds datastore
+ * row ids; the key is re-read from the exact datastore so that a cached
+ * entry's score is the very number the knowledge-base retrieval would give it
+ * (this is what makes the cache top-1 equal the knowledge-base top-1 whenever
+ * the latter is cached).
+ *
+ *   cache_ids  device int32 [R, C]; request r owns entries [0, cache_len[r])
+ *              of row r; every owned id must be in [0, N) (ids outside are
+ *              skipped)
+ *   cache_len  device int32 [R]; values are clamped to [0, C]
+ *   queries    device fp32 [Qt, d]; request r owns rows q_offsets[r] ..
+ *              q_offsets[r+1] (its speculation steps, in order)
+ *   q_offsets  device int64 [R+1], non-decreasing, within [0, Qt].  Device
+ *              data cannot be checked on the host: the kernel clamps each
+ *              range to [0, Qt] and treats a decreasing pair as empty.
+ *   spec_ids   device int32 [Qt]: top-1 cached id per query (-1 if the cache
+ *              is empty);  spec_scores device fp32 [Qt] (-inf if empty).
+ *              Rows of [0, Qt) that no request owns are left untouched.
+ */
+ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
+                              const float *queries, int64_t Qt, const int64_t *q_offsets,
+                              const ralm_datastore_t *ds, int32_t *spec_ids, float *spec_scores,
+                              void *stream);
+
+/*
+ * Verification compare (Alg. 1: m = argmin_i d^_i != d_i).  For request r with
+ * stride s_r = q_offsets[r+1] - q_offsets[r]:
+ *   first_mismatch[r] = min { i in [0, s_r) : spec_ids[q_offsets[r] + i] !=
+ *                             true_ids[(q_offsets[r] + i) * true_stride] }
+ * or s_r when every step matches (0-based; s_r = 0 gives 0).  true_stride = k
+ * reads the rank-0 column of a [Q, k] retrieval result in place.
+ *
+ *   spec_ids   device int32 [Qt];  true_ids device int32 [Qt * true_stride];
+ *   q_offsets  device int64 [R+1] (clamped as in ralm_cache_lookup);
+ *   first_mismatch  device int32 [R]
+ */
+ralm_status ralm_verify(const int32_t *spec_ids, const int32_t *true_ids, int64_t true_stride,
+                        int64_t Qt, const int64_t *q_offsets, int64_t R, int32_t *first_mismatch,
+                        void *stream);
+
+/*
+ * Timing aid for benchmarks.  While enabled, ralm_retrieve_topk_ex brackets
+ * its full-datastore scan kernel with HIP events on the call's stream.
+ * ralm_profile_scan_ms synchronises those events and returns the total
+ * milliseconds and the number of bracketed launches since the last reset
+ * (host pointers), then resets.  Not thread-safe; off by default.
+ */
+void ralm_profile_enable(int32_t on);
+ralm_status ralm_profile_scan_ms(float *total_ms, int32_t *launches);
+
+/* Text of the calling thread's last error (static storage; never NULL). */
+const char *ralm_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RALM_H */

@@ -1,0 +1,223 @@
+"""Thin ctypes binding over ``libralm.so`` (C ABI in ``include/ralm.h``).
+
+Argument marshalling only: torch tensors supply device memory and the current
+HIP stream; every step of the path runs inside the library's kernels.  The
+functions have the names of the C entry points.  There is no CPU fallback: if
+the shared object is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libralm.so")
+
+RALM_F32, RALM_BF16, RALM_F16 = 0, 1, 2
+_DT = {torch.float32: RALM_F32, torch.bfloat16: RALM_BF16, torch.float16: RALM_F16}
+
+STATUS = {0: "RALM_OK", 1: "RALM_ERR_NULL", 2: "RALM_ERR_SHAPE", 3: "RALM_ERR_K", 4: "RALM_ERR_DTYPE",
+          5: "RALM_ERR_ALIGN", 6: "RALM_ERR_WORKSPACE", 7: "RALM_ERR_RANGE", 8: "RALM_ERR_DEVICE",
+          9: "RALM_ERR_OVERFLOW"}
+
+
+class ralm_datastore_t(ctypes.Structure):
+    _fields_ = [("exact", ctypes.c_void_p), ("exact_dtype", ctypes.c_int32),
+                ("scan", ctypes.c_void_p), ("scan_dtype", ctypes.c_int32),
+                ("N", ctypes.c_int64), ("d", ctypes.c_int32),
+                ("exact_stride", ctypes.c_int64), ("scan_stride", ctypes.c_int64)]
+
+
+class RalmError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{STATUS.get(status, status)}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libralm.so (built in-tree by ``python -m paper_2401_14021_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2401_14021_amd.build`; "
+                "there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        dsp = ctypes.POINTER(ralm_datastore_t)
+        L.ralm_last_error.restype = ctypes.c_char_p
+        L.ralm_retrieve_topk.argtypes = [vp, i64, vp, i64, i32, i32, vp, vp]
+        L.ralm_workspace_bytes.argtypes = [i64, dsp, i32, i32]
+        L.ralm_workspace_bytes.restype = ctypes.c_size_t
+        L.ralm_retrieve_topk_ex.argtypes = [vp, i64, dsp, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ralm_workspace_overflows.argtypes = [vp, vp, ctypes.POINTER(i32)]
+        L.ralm_build_scan_copy.argtypes = [vp, i64, vp, i32, i64, i64, i32, vp]
+        L.ralm_cache_lookup.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, vp, vp, vp]
+        L.ralm_verify.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp]
+        L.ralm_profile_enable.argtypes = [i32]
+        L.ralm_profile_enable.restype = None
+        L.ralm_profile_scan_ms.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+        for name in ("ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_workspace_overflows",
+                     "ralm_build_scan_copy", "ralm_cache_lookup", "ralm_verify", "ralm_profile_scan_ms"):
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise RalmError(status, lib().ralm_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+class Datastore:
+    """Holds the exact copy and (optionally) the low-precision scan copy of the keys."""
+
+    def __init__(self, exact: torch.Tensor, scan: Optional[torch.Tensor] = None):
+        assert exact.dim() == 2 and exact.stride(1) == 1
+        self.exact, self.scan = exact, scan
+        self.N, self.d = exact.shape
+        self.desc = ralm_datastore_t()
+        self.desc.exact = exact.data_ptr()
+        self.desc.exact_dtype = _DT[exact.dtype]
+        self.desc.exact_stride = exact.stride(0)
+        self.desc.N, self.desc.d = self.N, self.d
+        if scan is not None:
+            assert scan.shape == exact.shape and scan.stride(1) == 1
+            self.desc.scan = scan.data_ptr()
+            self.desc.scan_dtype = _DT[scan.dtype]
+            self.desc.scan_stride = scan.stride(0)
+        else:
+            self.desc.scan = None
+            self.desc.scan_dtype = self.desc.exact_dtype
+            self.desc.scan_stride = 0
+
+    @classmethod
+    def from_fp32(cls, exact: torch.Tensor, scan_dtype: torch.dtype = torch.bfloat16,
+                  row_chunk: int = 1 << 20) -> "Datastore":
+        """Build the scan copy with the library's own rounding kernel."""
+        scan = torch.empty(exact.shape, dtype=scan_dtype, device=exact.device)
+        ralm_build_scan_copy(exact, scan)
+        return cls(exact, scan)
+
+
+def ralm_build_scan_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    assert src.dtype == torch.float32 and src.shape == dst.shape
+    N, d = src.shape
+    _check(lib().ralm_build_scan_copy(src.data_ptr(), src.stride(0), dst.data_ptr(), _DT[dst.dtype],
+                                      dst.stride(0), N, d, _stream()))
+
+
+def ralm_workspace_bytes(Q: int, ds: Datastore, k: int, k_prime: int = 0) -> int:
+    n = lib().ralm_workspace_bytes(Q, ctypes.byref(ds.desc), k, k_prime)
+    if n == 0:
+        raise RalmError(-1, "ralm_workspace_bytes: bad arguments")
+    return int(n)
+
+
+def alloc_workspace(Q: int, ds: Datastore, k: int, k_prime: int = 0) -> torch.Tensor:
+    n = ralm_workspace_bytes(Q, ds, k, k_prime)
+    return torch.empty(n + 256, dtype=torch.uint8, device=ds.exact.device)
+
+
+def _ws_view(ws: torch.Tensor) -> Tuple[int, int]:
+    base = ws.data_ptr()
+    aligned = (base + 255) & ~255
+    return aligned, ws.numel() - (aligned - base)
+
+
+def ralm_retrieve_topk_ex(queries: torch.Tensor, ds: Datastore, k: int, k_prime: int = 0,
+                          workspace: Optional[torch.Tensor] = None,
+                          out_ids: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None,
+                          out_margin: Optional[torch.Tensor] = None
+                          ) -> Tuple[torch.Tensor, torch.Tensor]:
+    assert queries.dtype == torch.float32 and queries.is_contiguous()
+    Q = queries.shape[0]
+    dev = queries.device
+    if workspace is None:
+        workspace = alloc_workspace(Q, ds, k, k_prime)
+    if out_ids is None:
+        out_ids = torch.empty(Q, k, dtype=torch.int32, device=dev)
+    if out_scores is None:
+        out_scores = torch.empty(Q, k, dtype=torch.float32, device=dev)
+    ws_ptr, ws_bytes = _ws_view(workspace)
+    _check(lib().ralm_retrieve_topk_ex(queries.data_ptr(), Q, ctypes.byref(ds.desc), k, k_prime,
+                                       out_ids.data_ptr(), out_scores.data_ptr(), _ptr(out_margin),
+                                       ws_ptr, ws_bytes, _stream()))
+    return out_ids, out_scores
+
+
+def ralm_workspace_overflows(workspace: torch.Tensor) -> int:
+    ws_ptr, _ = _ws_view(workspace)
+    c = ctypes.c_int32(0)
+    _check(lib().ralm_workspace_overflows(ws_ptr, _stream(), ctypes.byref(c)))
+    return int(c.value)
+
+
+def ralm_retrieve_topk(queries: torch.Tensor, datastore: torch.Tensor, k: int
+                       ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Simplest form: fp32 datastore, default stream, synchronous."""
+    assert queries.dtype == torch.float32 and datastore.dtype == torch.float32
+    assert queries.is_contiguous() and datastore.is_contiguous()
+    Q, d = queries.shape
+    N = datastore.shape[0]
+    out_ids = torch.empty(Q, k, dtype=torch.int32, device=queries.device)
+    out_scores = torch.empty(Q, k, dtype=torch.float32, device=queries.device)
+    torch.cuda.synchronize()
+    _check(lib().ralm_retrieve_topk(queries.data_ptr(), Q, datastore.data_ptr(), N, d, k,
+                                    out_ids.data_ptr(), out_scores.data_ptr()))
+    return out_ids, out_scores
+
+
+def ralm_cache_lookup(cache_ids: torch.Tensor, cache_len: torch.Tensor, queries: torch.Tensor,
+                      q_offsets: torch.Tensor, ds: Datastore,
+                      spec_ids: Optional[torch.Tensor] = None, spec_scores: Optional[torch.Tensor] = None
+                      ) -> Tuple[torch.Tensor, torch.Tensor]:
+    assert cache_ids.dtype == torch.int32 and cache_len.dtype == torch.int32
+    assert q_offsets.dtype == torch.int64 and queries.dtype == torch.float32
+    assert cache_ids.is_contiguous() and queries.is_contiguous()
+    R, C = cache_ids.shape
+    Qt = queries.shape[0]
+    if spec_ids is None:
+        spec_ids = torch.full((Qt,), -1, dtype=torch.int32, device=queries.device)
+    if spec_scores is None:
+        spec_scores = torch.full((Qt,), float("-inf"), dtype=torch.float32, device=queries.device)
+    _check(lib().ralm_cache_lookup(cache_ids.data_ptr(), cache_len.data_ptr(), C, R, queries.data_ptr(), Qt,
+                                   q_offsets.data_ptr(), ctypes.byref(ds.desc), spec_ids.data_ptr(),
+                                   spec_scores.data_ptr(), _stream()))
+    return spec_ids, spec_scores
+
+
+def ralm_verify(spec_ids: torch.Tensor, true_ids: torch.Tensor, q_offsets: torch.Tensor,
+                true_stride: int = 1, first_mismatch: Optional[torch.Tensor] = None) -> torch.Tensor:
+    assert spec_ids.dtype == torch.int32 and true_ids.dtype == torch.int32 and q_offsets.dtype == torch.int64
+    R = q_offsets.shape[0] - 1
+    Qt = spec_ids.shape[0]
+    if first_mismatch is None:
+        first_mismatch = torch.empty(R, dtype=torch.int32, device=spec_ids.device)
+    _check(lib().ralm_verify(spec_ids.data_ptr(), true_ids.data_ptr(), true_stride, Qt, q_offsets.data_ptr(), R,
+                             first_mismatch.data_ptr(), _stream()))
+    return first_mismatch
+
+
+def ralm_profile_enable(on: bool) -> None:
+    lib().ralm_profile_enable(1 if on else 0)
+
+
+def ralm_profile_scan_ms() -> Tuple[float, int]:
+    ms, n = ctypes.c_float(0), ctypes.c_int32(0)
+    _check(lib().ralm_profile_scan_ms(ctypes.byref(ms), ctypes.byref(n)))
+    return float(ms.value), int(n.value)

@@ -1,0 +1,282 @@
+// Speculative retrieval from the per-request caches, the verification compare, and the
+// small elementwise helpers (gfx950).
+//
+//  cache_lookup_kernel  Q.retrieve(q_i) of Alg. 1: rank the request's cached rows with the
+//                       retriever's own metric (Section 3 "Speculative retrieval", Fig. 2)
+//                       and return the top one.  Scores are formed exactly as the final
+//                       scores of the knowledge-base retrieval (double products and sum,
+//                       one rounding to fp32), so a cached entry gets the same number from
+//                       both and "top-1 of the knowledge base is cached => it is the cache's
+//                       top-1" holds bit for bit.
+//  verify_kernel        m = argmin_i (d^_i != d_i) of Alg. 1, per request.
+#include "ralm_common.h"
+#include "ralm_kernels.h"
+
+namespace ralm {
+
+namespace {
+
+constexpr int CL_GS = 16;          // lanes that share one cached row
+constexpr int CL_ROWS = 64 / CL_GS;   // rows per wave step
+constexpr int CL_LDS_BYTES = 56 * 1024;
+
+__device__ __forceinline__ void clamp_range(const int64_t *off, int64_t r, int64_t Qt, int64_t &lo, int64_t &hi)
+{
+    lo = off[r];
+    hi = off[r + 1];
+    lo = lo < 0 ? 0 : (lo > Qt ? Qt : lo);
+    hi = hi < lo ? lo : (hi > Qt ? Qt : hi);
+}
+
+// NCH = float4 chunks of a row held by one lane (row element (c*CL_GS + sub)*4 .. +4)
+template <int EX, int NCH>
+__global__ __launch_bounds__(256) void cache_lookup_kernel(
+    const int32_t *__restrict__ cache_ids, const int32_t *__restrict__ cache_len, int C,
+    const float *__restrict__ queries, int64_t Qt, const int64_t *__restrict__ q_offsets,
+    const void *__restrict__ exact, int64_t ld, int64_t N, int d, int qgroup,
+    int32_t *__restrict__ spec_ids, float *__restrict__ spec_scores)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *qs = reinterpret_cast<float *>(smem);                   // [qgroup][d]
+    u64 *best = reinterpret_cast<u64 *>(qs + (size_t)qgroup * d);   // [4 waves][CL_ROWS][qgroup]
+
+    const int64_t r = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = lane % CL_GS, slot = lane / CL_GS;
+    int64_t q_lo, q_hi;
+    clamp_range(q_offsets, r, Qt, q_lo, q_hi);
+    int len = cache_len[r];
+    len = len < 0 ? 0 : (len > C ? C : len);
+    const int32_t *ids = cache_ids + r * (int64_t)C;
+
+    for (int64_t g0 = q_lo; g0 < q_hi; g0 += qgroup) {
+        const int nq = (int)((q_hi - g0) < qgroup ? (q_hi - g0) : qgroup);
+        __syncthreads();
+        for (int i = tid * 4; i < nq * d; i += 1024)
+            *reinterpret_cast<float4 *>(qs + i) = *reinterpret_cast<const float4 *>(queries + g0 * d + i);
+        for (int i = tid; i < 4 * CL_ROWS * qgroup; i += 256) best[i] = 0ull;
+        __syncthreads();
+        u64 *my_best = best + (wave * CL_ROWS + slot) * qgroup;
+
+        for (int e0 = wave * CL_ROWS; e0 < len; e0 += 4 * CL_ROWS) {
+            const int e = e0 + slot;
+            const int32_t id = e < len ? ids[e] : -1;
+            const bool ok = id >= 0 && (int64_t)id < N;
+            float4 x[NCH];
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int j = (c * CL_GS + sub) * 4;
+                x[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (ok && j < d) {
+                    if constexpr (EX == DT_F32) {
+                        x[c] = *reinterpret_cast<const float4 *>(static_cast<const float *>(exact) +
+                                                                 (int64_t)id * ld + j);
+                    } else {
+                        const uint2 h = *reinterpret_cast<const uint2 *>(
+                            static_cast<const uint16_t *>(exact) + (int64_t)id * ld + j);
+                        x[c] = make_float4(f16_bits_to_f32(h.x & 0xffffu), f16_bits_to_f32(h.x >> 16),
+                                           f16_bits_to_f32(h.y & 0xffffu), f16_bits_to_f32(h.y >> 16));
+                    }
+                }
+            }
+            for (int qi = 0; qi < nq; ++qi) {
+                const float *qv = qs + (size_t)qi * d;
+                double sum = 0.0;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    const int j = (c * CL_GS + sub) * 4;
+                    if (j < d) {
+                        const float4 y = *reinterpret_cast<const float4 *>(qv + j);
+                        sum += (double)x[c].x * (double)y.x;
+                        sum += (double)x[c].y * (double)y.y;
+                        sum += (double)x[c].z * (double)y.z;
+                        sum += (double)x[c].w * (double)y.w;
+                    }
+                }
+#pragma unroll
+                for (int o = CL_GS / 2; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+                if (sub == 0 && ok) {
+                    const u64 key = make_key((float)sum, id);
+                    if (key > my_best[qi]) my_best[qi] = key;
+                }
+            }
+        }
+        __syncthreads();
+        for (int qi = tid; qi < nq; qi += 256) {
+            u64 b = 0ull;
+            for (int w = 0; w < 4 * CL_ROWS; ++w) {
+                const u64 v = best[w * qgroup + qi];
+                b = v > b ? v : b;
+            }
+            spec_ids[g0 + qi] = b ? key_id(b) : -1;
+            spec_scores[g0 + qi] = b ? key_score(b) : -__builtin_inff();
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void verify_kernel(const int32_t *__restrict__ spec,
+                                                     const int32_t *__restrict__ truth,
+                                                     int64_t true_stride, int64_t Qt,
+                                                     const int64_t *__restrict__ q_offsets, int64_t R,
+                                                     int32_t *__restrict__ first_mismatch)
+{
+    // one wave per request; lanes look at 64 consecutive steps at a time
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= R) return;
+    int64_t lo, hi;
+    clamp_range(q_offsets, r, Qt, lo, hi);
+    const int64_t s = hi - lo;
+    int64_t m = s;
+    for (int64_t base = 0; base < s; base += 64) {
+        const int64_t i = base + lane;
+        const bool differ = i < s && spec[lo + i] != truth[(lo + i) * true_stride];
+        const unsigned long long mask = __ballot(differ);
+        if (mask) {
+            m = base + __ffsll((long long)mask) - 1;
+            break;
+        }
+    }
+    if (lane == 0) first_mismatch[r] = (int32_t)m;
+}
+
+__global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+__global__ void fill_u64_kernel(u64 *p, u64 v, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+// query preparation: queries rounded to the scan dtype, zero padded to [Qpad, dpad]
+template <int DT>
+__global__ void query_prep_kernel(const float *__restrict__ q, int64_t Q, int d, uint16_t *__restrict__ out,
+                                  int64_t Qpad, int dpad)
+{
+    const int64_t n = Qpad * dpad;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = i / dpad;
+        const int col = (int)(i % dpad);
+        uint32_t bits = 0;
+        if (row < Q && col < d) bits = f32_to_scan_bits<DT>(q[row * d + col]);
+        out[i] = (uint16_t)bits;
+    }
+}
+
+template <int DT>
+__global__ void convert_rows_kernel(const float *__restrict__ src, int64_t src_ld, uint16_t *__restrict__ dst,
+                                    int64_t dst_ld, int64_t N, int d8)
+{
+    // one 8-element chunk per thread step
+    const int64_t n = N * d8;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = i / d8;
+        const int c = (int)(i % d8) * 8;
+        const float4 a = *reinterpret_cast<const float4 *>(src + row * src_ld + c);
+        const float4 b = *reinterpret_cast<const float4 *>(src + row * src_ld + c + 4);
+        *reinterpret_cast<uint4 *>(dst + row * dst_ld + c) = pack8<DT>(a, b);
+    }
+}
+
+int grid_for(int64_t n, int block)
+{
+    int64_t g = (n + block - 1) / block;
+    if (g > 256 * 32) g = 256 * 32;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+
+template <int EX>
+hipError_t launch_cache_ex(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
+                           const float *queries, int64_t Qt, const int64_t *q_offsets, const void *exact,
+                           int64_t ld, int64_t N, int32_t d, int32_t *spec_ids, float *spec_scores,
+                           hipStream_t stream)
+{
+    int qgroup = CL_LDS_BYTES / (d * 4);
+    if (qgroup > 16) qgroup = 16;
+    if (qgroup < 1) return hipErrorInvalidValue;
+    const size_t smem = (size_t)qgroup * d * 4 + (size_t)4 * CL_ROWS * qgroup * sizeof(u64);
+    const int nch = (d + CL_GS * 4 - 1) / (CL_GS * 4);
+#define RALM_CL(NCHV)                                                                                      \
+    hipLaunchKernelGGL((cache_lookup_kernel<EX, NCHV>), dim3((unsigned)R), dim3(256), smem, stream,        \
+                       cache_ids, cache_len, C, queries, Qt, q_offsets, exact, ld, N, d, qgroup, spec_ids, \
+                       spec_scores)
+    if (nch <= 4) RALM_CL(4);
+    else if (nch <= 8) RALM_CL(8);
+    else if (nch <= 12) RALM_CL(12);
+    else if (nch <= 16) RALM_CL(16);
+    else if (nch <= 32) RALM_CL(32);
+    else return hipErrorInvalidValue;
+#undef RALM_CL
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
+                               const float *queries, int64_t Qt, const int64_t *q_offsets,
+                               const void *exact, int32_t exact_dtype, int64_t ld, int64_t N, int32_t d,
+                               int32_t *spec_ids, float *spec_scores, hipStream_t stream)
+{
+    if (R <= 0) return hipSuccess;
+    if (exact_dtype == DT_F16)
+        return launch_cache_ex<DT_F16>(cache_ids, cache_len, C, R, queries, Qt, q_offsets, exact, ld, N, d,
+                                       spec_ids, spec_scores, stream);
+    return launch_cache_ex<DT_F32>(cache_ids, cache_len, C, R, queries, Qt, q_offsets, exact, ld, N, d,
+                                   spec_ids, spec_scores, stream);
+}
+
+hipError_t launch_verify(const int32_t *spec, const int32_t *truth, int64_t true_stride, int64_t Qt,
+                         const int64_t *q_offsets, int64_t R, int32_t *first_mismatch, hipStream_t stream)
+{
+    if (R <= 0) return hipSuccess;
+    hipLaunchKernelGGL(verify_kernel, dim3((unsigned)((R + 3) / 4)), dim3(256), 0, stream, spec, truth,
+                       true_stride, Qt, q_offsets, R, first_mismatch);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t stream)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for(n, 256)), dim3(256), 0, stream, p, v, n);
+    return hipGetLastError();
+}
+hipError_t launch_fill_u64(u64 *p, u64 v, int64_t n, hipStream_t stream)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_u64_kernel, dim3(grid_for(n, 256)), dim3(256), 0, stream, p, v, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_query_prep(const float *q, int64_t Q, int32_t d, uint16_t *out, int64_t Qpad, int32_t dpad,
+                             int32_t scan_dtype, hipStream_t stream)
+{
+    const int64_t n = Qpad * dpad;
+    if (n <= 0) return hipSuccess;
+    if (scan_dtype == DT_F16)
+        hipLaunchKernelGGL(query_prep_kernel<DT_F16>, dim3(grid_for(n, 256)), dim3(256), 0, stream, q, Q, d,
+                           out, Qpad, dpad);
+    else
+        hipLaunchKernelGGL(query_prep_kernel<DT_BF16>, dim3(grid_for(n, 256)), dim3(256), 0, stream, q, Q, d,
+                           out, Qpad, dpad);
+    return hipGetLastError();
+}
+
+hipError_t launch_convert_rows(const float *src, int64_t src_ld, void *dst, int32_t dst_dtype, int64_t dst_ld,
+                               int64_t N, int32_t d, hipStream_t stream)
+{
+    const int64_t n = N * (d / 8);
+    if (n <= 0) return hipSuccess;
+    if (dst_dtype == DT_F16)
+        hipLaunchKernelGGL(convert_rows_kernel<DT_F16>, dim3(grid_for(n, 256)), dim3(256), 0, stream, src,
+                           src_ld, static_cast<uint16_t *>(dst), dst_ld, N, d / 8);
+    else
+        hipLaunchKernelGGL(convert_rows_kernel<DT_BF16>, dim3(grid_for(n, 256)), dim3(256), 0, stream, src,
+                           src_ld, static_cast<uint16_t *>(dst), dst_ld, N, d / 8);
+    return hipGetLastError();
+}
+
+}  // namespace ralm

@@ -1,0 +1,345 @@
+// C ABI of the retrieval library: argument checks (all on the host, before any launch),
+// workspace carve-up, stage planning and kernel sequencing.  See include/ralm.h for the
+// contract of every entry point.
+//
+// How one ralm_retrieve_topk_ex call runs (everything on the caller's stream):
+//   1. queries are rounded to the scan dtype into a zero-padded matrix;
+//   2. a ladder of scan stages runs over nested, strided samples of the datastore's row
+//      tiles, the last stage being the whole datastore.  Stage i admits a score only if its
+//      ranking key is >= the k'-th best key of stage i-1 (a subset of stage i's rows, so that
+//      key is a valid lower bound on stage i's own k'-th best); the first stage is small
+//      enough to keep everything.  Each stage: zero the per-query counters, scan, select the
+//      k'-th best key per query.
+//   3. the k' keys kept by the last stage are re-scored from the exact copy and ranked.
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/ralm.h"
+#include "ralm_common.h"
+#include "ralm_kernels.h"
+
+using namespace ralm;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+ralm_status fail(ralm_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+#define RALM_HIP(call)                                                                          \
+    do {                                                                                        \
+        hipError_t e_ = (call);                                                                 \
+        if (e_ != hipSuccess)                                                                   \
+            return fail(RALM_ERR_DEVICE, "%s failed: %s", #call, hipGetErrorString(e_));        \
+    } while (0)
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+int elem_bytes(int dt) { return dt == RALM_F32 ? 4 : 2; }
+
+// ---- stage plan ---------------------------------------------------------------------------
+struct Plan {
+    int32_t k_prime;
+    int32_t ratio;        // sample ratio between consecutive stages
+    uint32_t cap;         // candidate slots per query
+    int64_t Qpad;
+    int32_t dpad;
+    int n_stages;
+    int64_t stride[16];   // tile stride of each stage, first = coarsest, last = 1
+    // workspace offsets
+    size_t off_q, off_tau, off_cnt, off_selcnt, off_flags, off_cand, off_sel, total;
+};
+
+int32_t default_k_prime(int32_t k)
+{
+    if (k <= 32) return 64;
+    int32_t kp = 64;
+    while (kp < 2 * k) kp <<= 1;
+    return kp;
+}
+
+ralm_status make_plan(int64_t Q, const ralm_datastore_t *ds, int32_t k, int32_t k_prime, Plan &pl)
+{
+    if (k_prime == 0) k_prime = default_k_prime(k);
+    if (k < 1 || k > RALM_MAX_K || (int64_t)k > ds->N)
+        return fail(RALM_ERR_K, "k=%d must be in [1, min(N, %d)]", k, RALM_MAX_K);
+    if (k_prime < k || k_prime > RALM_MAX_K_PRIME)
+        return fail(RALM_ERR_K, "k_prime=%d must be in [k, %d]", k_prime, RALM_MAX_K_PRIME);
+    pl.k_prime = k_prime;
+    // expected admissions per query and stage = k' * ratio; the slots leave 4x (2x for large k')
+    // head room, far beyond the spread of that count for rows in random order
+    pl.ratio = k_prime <= 256 ? 64 : 32;
+    const int64_t safety = k_prime <= 256 ? 4 : 2;
+    pl.cap = (uint32_t)(safety * k_prime * pl.ratio);
+    if (pl.cap < 16384u) pl.cap = 16384u;
+    pl.Qpad = (Q + SCAN_QPAD - 1) / SCAN_QPAD * SCAN_QPAD;
+    pl.dpad = (ds->d + SCAN_BK - 1) / SCAN_BK * SCAN_BK;
+
+    const int64_t tiles = (ds->N + SCAN_BM - 1) / SCAN_BM;
+    int64_t strides[16];
+    int n = 0;
+    int64_t s = 1;
+    strides[n++] = 1;
+    // coarsen until a stage's rows all fit the candidate slots (that stage keeps everything)
+    while (((tiles + s - 1) / s) * SCAN_BM > (int64_t)pl.cap && n < 16) {
+        s *= pl.ratio;
+        strides[n++] = s;
+    }
+    pl.n_stages = n;
+    for (int i = 0; i < n; ++i) pl.stride[i] = strides[n - 1 - i];
+
+    size_t off = 0;
+    pl.off_flags = off;  off += 256;   // always first: word 0 = overflowed queries of the last call
+    pl.off_q = off;      off += up256((size_t)pl.Qpad * pl.dpad * 2);
+    pl.off_tau = off;    off += up256((size_t)pl.Qpad * 8);
+    pl.off_cnt = off;    off += up256((size_t)pl.Qpad * 4);
+    pl.off_selcnt = off; off += up256((size_t)pl.Qpad * 4);
+    pl.off_cand = off;   off += up256((size_t)Q * pl.cap * 8);
+    pl.off_sel = off;    off += up256((size_t)Q * k_prime * 8);
+    pl.total = off;
+    return RALM_OK;
+}
+
+ralm_status check_datastore(const ralm_datastore_t *ds, bool need_scan)
+{
+    if (!ds) return fail(RALM_ERR_NULL, "datastore descriptor is NULL");
+    if (!ds->exact) return fail(RALM_ERR_NULL, "datastore.exact is NULL");
+    if (ds->N < 1 || ds->N > 0x7fffffffLL) return fail(RALM_ERR_SHAPE, "N=%lld out of [1, 2^31)", (long long)ds->N);
+    if (ds->d < 8 || ds->d % 8 != 0 || ds->d > 16384)
+        return fail(RALM_ERR_SHAPE, "d=%d must be a multiple of 8 in [8, 16384]", ds->d);
+    if (ds->exact_dtype != RALM_F32 && ds->exact_dtype != RALM_F16)
+        return fail(RALM_ERR_DTYPE, "exact_dtype must be RALM_F32 or RALM_F16");
+    const int64_t es = ds->exact_stride ? ds->exact_stride : ds->d;
+    if (es < ds->d) return fail(RALM_ERR_SHAPE, "exact_stride < d");
+    if (!aligned16(ds->exact) || (es * elem_bytes(ds->exact_dtype)) % 16)
+        return fail(RALM_ERR_ALIGN, "exact copy: base and row pitch must be multiples of 16 bytes");
+    if (need_scan && ds->scan) {
+        if (ds->scan_dtype != RALM_BF16 && ds->scan_dtype != RALM_F16 && ds->scan_dtype != RALM_F32)
+            return fail(RALM_ERR_DTYPE, "scan_dtype unknown");
+        const int64_t ss = ds->scan_stride ? ds->scan_stride : ds->d;
+        if (ss < ds->d) return fail(RALM_ERR_SHAPE, "scan_stride < d");
+        if (!aligned16(ds->scan) || (ss * elem_bytes(ds->scan_dtype)) % 16)
+            return fail(RALM_ERR_ALIGN, "scan copy: base and row pitch must be multiples of 16 bytes");
+    }
+    return RALM_OK;
+}
+
+int device_cus()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
+// ---- scan timing aid ------------------------------------------------------------------------
+constexpr int MAX_PROF = 256;
+bool g_prof_on = false;
+int g_prof_n = 0;
+hipEvent_t g_prof_ev[MAX_PROF][2];
+int g_prof_made = 0;
+
+}  // namespace
+
+extern "C" {
+
+const char *ralm_last_error(void) { return g_err; }
+
+size_t ralm_workspace_bytes(int64_t Q, const ralm_datastore_t *ds, int32_t k, int32_t k_prime)
+{
+    if (Q < 1 || check_datastore(ds, true) != RALM_OK) return 0;
+    Plan pl;
+    if (make_plan(Q, ds, k, k_prime, pl) != RALM_OK) return 0;
+    return pl.total;
+}
+
+ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_datastore_t *ds, int32_t k,
+                                  int32_t k_prime, int32_t *out_ids, float *out_scores, float *out_margin,
+                                  void *workspace, size_t workspace_bytes, void *stream_)
+{
+    if (!queries || !out_ids || !out_scores) return fail(RALM_ERR_NULL, "queries/out_ids/out_scores is NULL");
+    if (Q < 1 || Q > (1 << 20)) return fail(RALM_ERR_SHAPE, "Q=%lld out of [1, 2^20]", (long long)Q);
+    ralm_status st = check_datastore(ds, true);
+    if (st != RALM_OK) return st;
+    if (!aligned16(queries)) return fail(RALM_ERR_ALIGN, "queries must be 16-byte aligned");
+    Plan pl;
+    st = make_plan(Q, ds, k, k_prime, pl);
+    if (st != RALM_OK) return st;
+    if (!workspace) return fail(RALM_ERR_WORKSPACE, "workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(RALM_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (workspace_bytes < pl.total)
+        return fail(RALM_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, pl.total);
+
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    uint16_t *qs = reinterpret_cast<uint16_t *>(ws + pl.off_q);
+    u64 *tau = reinterpret_cast<u64 *>(ws + pl.off_tau);
+    uint32_t *cnt = reinterpret_cast<uint32_t *>(ws + pl.off_cnt);
+    uint32_t *sel_cnt = reinterpret_cast<uint32_t *>(ws + pl.off_selcnt);
+    int32_t *flags = reinterpret_cast<int32_t *>(ws + pl.off_flags);
+    u64 *cand = reinterpret_cast<u64 *>(ws + pl.off_cand);
+    u64 *sel = reinterpret_cast<u64 *>(ws + pl.off_sel);
+
+    const void *scan = ds->scan ? ds->scan : ds->exact;
+    const int scan_dt = ds->scan ? ds->scan_dtype : ds->exact_dtype;
+    const int64_t scan_ld = ds->scan ? (ds->scan_stride ? ds->scan_stride : ds->d)
+                                     : (ds->exact_stride ? ds->exact_stride : ds->d);
+    const int mma_dt = scan_dt == RALM_F16 ? RALM_F16 : RALM_BF16;   // fp32 rows are rounded to bf16
+    const int n_cu = device_cus();
+
+    RALM_HIP(launch_query_prep(queries, Q, ds->d, qs, pl.Qpad, pl.dpad, mma_dt, stream));
+    RALM_HIP(launch_fill_u64(tau, 0ull, pl.Qpad, stream));
+    RALM_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(flags), 0u, 64, stream));
+
+    const int64_t tiles = (ds->N + SCAN_BM - 1) / SCAN_BM;
+    for (int s = 0; s < pl.n_stages; ++s) {
+        const bool last = s == pl.n_stages - 1;
+        RALM_HIP(launch_fill_u32(cnt, 0u, pl.Qpad, stream));
+        ScanParams sp;
+        sp.X = scan; sp.ldx = scan_ld; sp.N = ds->N; sp.d = ds->d; sp.in_dtype = scan_dt;
+        sp.Qs = qs; sp.dpad = pl.dpad; sp.Q = (int32_t)Q;
+        sp.tau = tau; sp.cand = cand; sp.cnt = cnt; sp.cap = pl.cap;
+        sp.tile_stride = pl.stride[s];
+        sp.n_row_tiles = (tiles + pl.stride[s] - 1) / pl.stride[s];
+        const bool prof = last && g_prof_on && g_prof_n < MAX_PROF;
+        if (prof) {
+            while (g_prof_made <= g_prof_n) {
+                RALM_HIP(hipEventCreate(&g_prof_ev[g_prof_made][0]));
+                RALM_HIP(hipEventCreate(&g_prof_ev[g_prof_made][1]));
+                ++g_prof_made;
+            }
+            RALM_HIP(hipEventRecord(g_prof_ev[g_prof_n][0], stream));
+        }
+        RALM_HIP(launch_scan(sp, n_cu, stream));
+        if (prof) {
+            RALM_HIP(hipEventRecord(g_prof_ev[g_prof_n][1], stream));
+            ++g_prof_n;
+        }
+        RALM_HIP(launch_select(cand, cnt, pl.cap, pl.k_prime, Q, tau, last ? sel : nullptr,
+                               last ? sel_cnt : nullptr, flags, stream));
+    }
+    const int64_t exact_ld = ds->exact_stride ? ds->exact_stride : ds->d;
+    RALM_HIP(launch_rescore(sel, sel_cnt, pl.k_prime, queries, Q, ds->exact, ds->exact_dtype, exact_ld, ds->d, k,
+                            out_ids, out_scores, out_margin, stream));
+    return RALM_OK;
+}
+
+ralm_status ralm_workspace_overflows(const void *workspace, void *stream_, int32_t *count)
+{
+    if (!workspace || !count) return fail(RALM_ERR_NULL, "workspace/count is NULL");
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    RALM_HIP(hipStreamSynchronize(stream));
+    RALM_HIP(hipMemcpy(count, workspace, sizeof(int32_t), hipMemcpyDeviceToHost));
+    return RALM_OK;
+}
+
+ralm_status ralm_retrieve_topk(const float *queries, int64_t Q, const float *datastore, int64_t N, int32_t d,
+                               int32_t k, int32_t *out_ids, float *out_scores)
+{
+    if (!queries || !datastore || !out_ids || !out_scores) return fail(RALM_ERR_NULL, "a pointer is NULL");
+    ralm_datastore_t ds;
+    memset(&ds, 0, sizeof(ds));
+    ds.exact = datastore;
+    ds.exact_dtype = RALM_F32;
+    ds.scan = nullptr;
+    ds.N = N;
+    ds.d = d;
+    if (Q < 1 || Q > (1 << 20)) return fail(RALM_ERR_SHAPE, "Q=%lld out of [1, 2^20]", (long long)Q);
+    ralm_status st = check_datastore(&ds, true);
+    if (st != RALM_OK) return st;
+    Plan pl;
+    st = make_plan(Q, &ds, k, 0, pl);
+    if (st != RALM_OK) return st;
+    void *ws = nullptr;
+    RALM_HIP(hipMalloc(&ws, pl.total));
+    st = ralm_retrieve_topk_ex(queries, Q, &ds, k, 0, out_ids, out_scores, nullptr, ws, pl.total, nullptr);
+    int32_t overflows = 0;
+    if (st == RALM_OK) st = ralm_workspace_overflows(ws, nullptr, &overflows);
+    hipError_t e = hipFree(ws);
+    if (st == RALM_OK && e != hipSuccess) return fail(RALM_ERR_DEVICE, "hipFree failed: %s", hipGetErrorString(e));
+    if (st == RALM_OK && overflows > 0)
+        return fail(RALM_ERR_OVERFLOW, "%d queries overflowed their candidate buffers", overflows);
+    return st;
+}
+
+ralm_status ralm_build_scan_copy(const float *src, int64_t src_stride, void *dst, int32_t dst_dtype,
+                                 int64_t dst_stride, int64_t N, int32_t d, void *stream)
+{
+    if (!src || !dst) return fail(RALM_ERR_NULL, "src/dst is NULL");
+    if (N < 1 || d < 8 || d % 8) return fail(RALM_ERR_SHAPE, "N >= 1 and d a multiple of 8 required");
+    if (dst_dtype != RALM_BF16 && dst_dtype != RALM_F16) return fail(RALM_ERR_DTYPE, "dst_dtype must be RALM_BF16 or RALM_F16");
+    if (src_stride == 0) src_stride = d;
+    if (dst_stride == 0) dst_stride = d;
+    if (src_stride < d || dst_stride < d) return fail(RALM_ERR_SHAPE, "stride < d");
+    if (!aligned16(src) || !aligned16(dst) || (src_stride * 4) % 16 || (dst_stride * 2) % 16)
+        return fail(RALM_ERR_ALIGN, "bases and row pitches must be multiples of 16 bytes");
+    RALM_HIP(launch_convert_rows(src, src_stride, dst, dst_dtype, dst_stride, N, d, static_cast<hipStream_t>(stream)));
+    return RALM_OK;
+}
+
+ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
+                              const float *queries, int64_t Qt, const int64_t *q_offsets,
+                              const ralm_datastore_t *ds, int32_t *spec_ids, float *spec_scores, void *stream)
+{
+    if (!cache_ids || !cache_len || !queries || !q_offsets || !spec_ids || !spec_scores)
+        return fail(RALM_ERR_NULL, "a pointer is NULL");
+    if (R < 0 || R > 0x7fffffffLL || C < 1) return fail(RALM_ERR_SHAPE, "R=%lld, C=%d out of range", (long long)R, C);
+    if (Qt < 0) return fail(RALM_ERR_RANGE, "Qt=%lld is negative", (long long)Qt);
+    ralm_status st = check_datastore(ds, false);
+    if (st != RALM_OK) return st;
+    if (ds->d > 2048) return fail(RALM_ERR_SHAPE, "cache lookup supports d <= 2048");
+    if (!aligned16(queries)) return fail(RALM_ERR_ALIGN, "queries must be 16-byte aligned");
+    const int64_t ld = ds->exact_stride ? ds->exact_stride : ds->d;
+    RALM_HIP(launch_cache_lookup(cache_ids, cache_len, C, R, queries, Qt, q_offsets, ds->exact, ds->exact_dtype, ld,
+                                 ds->N, ds->d, spec_ids, spec_scores, static_cast<hipStream_t>(stream)));
+    return RALM_OK;
+}
+
+ralm_status ralm_verify(const int32_t *spec_ids, const int32_t *true_ids, int64_t true_stride, int64_t Qt,
+                        const int64_t *q_offsets, int64_t R, int32_t *first_mismatch, void *stream)
+{
+    if (!spec_ids || !true_ids || !q_offsets || !first_mismatch) return fail(RALM_ERR_NULL, "a pointer is NULL");
+    if (R < 0 || R > 0x7fffffffLL) return fail(RALM_ERR_SHAPE, "R=%lld out of range", (long long)R);
+    if (Qt < 0 || true_stride < 1) return fail(RALM_ERR_RANGE, "Qt >= 0 and true_stride >= 1 required");
+    RALM_HIP(launch_verify(spec_ids, true_ids, true_stride, Qt, q_offsets, R, first_mismatch,
+                           static_cast<hipStream_t>(stream)));
+    return RALM_OK;
+}
+
+void ralm_profile_enable(int32_t on)
+{
+    g_prof_on = on != 0;
+}
+
+ralm_status ralm_profile_scan_ms(float *total_ms, int32_t *launches)
+{
+    if (!total_ms || !launches) return fail(RALM_ERR_NULL, "total_ms/launches is NULL");
+    float total = 0.f;
+    for (int i = 0; i < g_prof_n; ++i) {
+        RALM_HIP(hipEventSynchronize(g_prof_ev[i][1]));
+        float ms = 0.f;
+        RALM_HIP(hipEventElapsedTime(&ms, g_prof_ev[i][0], g_prof_ev[i][1]));
+        total += ms;
+    }
+    *total_ms = total;
+    *launches = g_prof_n;
+    g_prof_n = 0;
+    return RALM_OK;
+}
+
+}  // extern "C"

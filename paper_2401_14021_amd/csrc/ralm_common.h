@@ -1,0 +1,72 @@
+// Shared device helpers of the retrieval library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ralm {
+
+typedef unsigned long long u64;
+
+enum { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---- ranking keys -----------------------------------------------------------------------
+// A candidate (score, row id) is packed into one 64-bit key whose unsigned order is the
+// library's ranking: larger key = better = (higher score, then lower id).  -0.0 is folded
+// into +0.0 first so that equal floats always give equal score bits.
+__device__ __forceinline__ uint32_t score_bits(float s)
+{
+    s += 0.0f;
+    uint32_t u = __float_as_uint(s);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float bits_score(uint32_t b)
+{
+    uint32_t u = (b & 0x80000000u) ? (b & 0x7fffffffu) : ~b;
+    return __uint_as_float(u);
+}
+__device__ __forceinline__ u64 make_key(float s, int32_t id)
+{
+    return ((u64)score_bits(s) << 32) | (uint32_t)(0x7fffffff - id);
+}
+__device__ __forceinline__ int32_t key_id(u64 key) { return 0x7fffffff - (int32_t)(uint32_t)key; }
+__device__ __forceinline__ float key_score(u64 key) { return bits_score((uint32_t)(key >> 32)); }
+
+// ---- element conversions ----------------------------------------------------------------
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f)
+{
+    _Float16 h = (_Float16)f;   // v_cvt_f16_f32, round to nearest even
+    return (uint32_t)__builtin_bit_cast(unsigned short, h);
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t h)
+{
+    return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+}
+template <int DT>
+__device__ __forceinline__ uint32_t f32_to_scan_bits(float f)
+{
+    return DT == DT_F16 ? f32_to_f16_bits(f) : f32_to_bf16_bits(f);
+}
+template <int DT>
+__device__ __forceinline__ uint4 pack8(const float4 &a, const float4 &b)
+{
+    uint4 r;
+    r.x = f32_to_scan_bits<DT>(a.x) | (f32_to_scan_bits<DT>(a.y) << 16);
+    r.y = f32_to_scan_bits<DT>(a.z) | (f32_to_scan_bits<DT>(a.w) << 16);
+    r.z = f32_to_scan_bits<DT>(b.x) | (f32_to_scan_bits<DT>(b.y) << 16);
+    r.w = f32_to_scan_bits<DT>(b.z) | (f32_to_scan_bits<DT>(b.w) << 16);
+    return r;
+}
+
+}  // namespace ralm

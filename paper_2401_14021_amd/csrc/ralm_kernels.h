@@ -1,0 +1,66 @@
+// Launchers of the retrieval kernels (internal to libralm.so).  Every launcher only
+// enqueues work on `stream`; argument validation happens in the C-ABI layer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ralm {
+
+typedef unsigned long long u64;
+
+constexpr int SCAN_BM = 256;       // datastore rows per scan tile (all variants)
+constexpr int SCAN_BK = 64;        // reduction elements staged per pipeline step
+constexpr int SCAN_QPAD = 256;     // query matrix is zero-padded to a multiple of this
+
+struct ScanParams {
+    const void *X;          // scan copy [N, ldx]
+    int64_t ldx;            // elements
+    int64_t N;
+    int32_t d;              // true reduction length (multiple of 8)
+    int32_t in_dtype;       // DT_* of X
+    const uint16_t *Qs;     // converted queries [Qpad, dpad], zero padded
+    int32_t dpad;           // multiple of SCAN_BK
+    int32_t Q;
+    const u64 *tau;         // [Q] admission keys (0 = admit everything)
+    u64 *cand;              // [Q, cap]
+    uint32_t *cnt;          // [Q]
+    uint32_t cap;
+    int64_t n_row_tiles;    // tiles visited in this stage
+    int64_t tile_stride;    // visited tile t covers rows [t*tile_stride*BM, +BM)
+};
+
+// query tile width chosen for Q
+int scan_bn_for(int64_t Q);
+hipError_t launch_scan(const ScanParams &p, int n_cu, hipStream_t stream);
+
+hipError_t launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t stream);
+hipError_t launch_fill_u64(u64 *p, u64 v, int64_t n, hipStream_t stream);
+
+// fp32 [Q, d] -> scan dtype [Qpad, dpad], zero padded
+hipError_t launch_query_prep(const float *q, int64_t Q, int32_t d, uint16_t *out, int64_t Qpad,
+                             int32_t dpad, int32_t scan_dtype, hipStream_t stream);
+
+hipError_t launch_convert_rows(const float *src, int64_t src_ld, void *dst, int32_t dst_dtype,
+                               int64_t dst_ld, int64_t N, int32_t d, hipStream_t stream);
+
+// per query: k'-th best key of cand[q, 0..cnt[q]) -> tau[q]; optionally the k' best keys
+hipError_t launch_select(const u64 *cand, const uint32_t *cnt, uint32_t cap, int32_t k_prime, int64_t Q,
+                         u64 *tau, u64 *sel, uint32_t *sel_cnt, int32_t *overflow_count,
+                         hipStream_t stream);
+
+// per query: exact scores of the selected rows, final ranking, top k out
+hipError_t launch_rescore(const u64 *sel, const uint32_t *sel_cnt, int32_t k_prime, const float *queries,
+                          int64_t Q, const void *exact, int32_t exact_dtype, int64_t ld, int32_t d,
+                          int32_t k, int32_t *out_ids, float *out_scores, float *out_margin,
+                          hipStream_t stream);
+
+hipError_t launch_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
+                               const float *queries, int64_t Qt, const int64_t *q_offsets,
+                               const void *exact, int32_t exact_dtype, int64_t ld, int64_t N, int32_t d,
+                               int32_t *spec_ids, float *spec_scores, hipStream_t stream);
+
+hipError_t launch_verify(const int32_t *spec, const int32_t *truth, int64_t true_stride, int64_t Qt,
+                         const int64_t *q_offsets, int64_t R, int32_t *first_mismatch,
+                         hipStream_t stream);
+
+}  // namespace ralm

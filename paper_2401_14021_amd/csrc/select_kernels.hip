@@ -1,0 +1,238 @@
+// Per-query selection and exact re-scoring (gfx950).
+//
+//  select_kernel   exact k'-th best of a query's candidate keys by an 8-bit radix descent
+//                  over the 64-bit ranking key; writes the admission key for the next scan
+//                  stage and, on request, the k' best keys themselves.
+//  rescore_kernel  for the k' rows kept by the scan: inner product with the fp32 query from
+//                  the EXACT datastore copy, products and sum in double, one rounding to
+//                  fp32; final ranking (score descending, id ascending); first k written.
+//                  This is what makes the result that of the paper's exact dense retriever
+//                  (Section 5.1) although the scan ran in bf16/fp16.
+#include "ralm_common.h"
+#include "ralm_kernels.h"
+
+namespace ralm {
+
+namespace {
+
+// inclusive prefix sum over the 256 threads of a block
+__device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t x, uint32_t *wave_tot /*[4] LDS*/)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t y = __shfl_up(x, o, 64);
+        if (lane >= o) x += y;
+    }
+    if (lane == 63) wave_tot[wave] = x;
+    __syncthreads();
+    uint32_t add = 0;
+    for (int w = 0; w < wave; ++w) add += wave_tot[w];
+    __syncthreads();
+    return x + add;
+}
+
+__global__ __launch_bounds__(256) void select_kernel(const u64 *__restrict__ cand,
+                                                     const uint32_t *__restrict__ cnt, uint32_t cap,
+                                                     int k_prime, u64 *__restrict__ tau,
+                                                     u64 *__restrict__ sel, uint32_t *__restrict__ sel_cnt,
+                                                     int32_t *__restrict__ overflow_count)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t wave_tot[4];
+    __shared__ uint32_t s_digit, s_remaining, s_out;
+
+    const int64_t q = blockIdx.x;
+    const int tid = threadIdx.x;
+    const uint32_t n = cnt[q];
+    const u64 *c = cand + q * (int64_t)cap;
+
+    if (n > cap) {   // buffer overflowed: this query cannot be answered from it
+        if (tid == 0) {
+            tau[q] = ~0ull;
+            if (sel_cnt) sel_cnt[q] = 0xffffffffu;
+            atomicAdd(overflow_count, 1);
+        }
+        return;
+    }
+
+    u64 kth = 0;   // 0 admits everything (fewer than k' candidates exist)
+    if (n > (uint32_t)k_prime) {
+        u64 prefix = 0, mask = 0;
+        uint32_t remaining = (uint32_t)k_prime;
+        for (int shift = 56; shift >= 0; shift -= 8) {
+            hist[tid] = 0;
+            __syncthreads();
+            for (uint32_t i = tid; i < n; i += 256) {
+                const u64 key = c[i];
+                if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            // thread t looks at digit 255 - t: walk digits from the best downwards
+            const uint32_t h = hist[255 - tid];
+            const uint32_t incl = block_inclusive_scan(h, wave_tot);
+            if (incl >= remaining && incl - h < remaining) {
+                s_digit = 255 - tid;
+                s_remaining = remaining - (incl - h);
+            }
+            __syncthreads();
+            prefix |= (u64)s_digit << shift;
+            mask |= 0xffull << shift;
+            remaining = s_remaining;
+            __syncthreads();
+        }
+        kth = prefix;
+    }
+    if (tid == 0) tau[q] = kth;
+
+    if (sel) {
+        if (tid == 0) s_out = 0;
+        __syncthreads();
+        u64 *out = sel + q * (int64_t)k_prime;
+        for (uint32_t i = tid; i < n; i += 256) {
+            const u64 key = c[i];
+            if (key >= kth) {
+                const uint32_t at = atomicAdd(&s_out, 1u);
+                if (at < (uint32_t)k_prime) out[at] = key;
+            }
+        }
+        __syncthreads();
+        if (tid == 0) sel_cnt[q] = s_out < (uint32_t)k_prime ? s_out : (uint32_t)k_prime;
+    }
+}
+
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+template <int EX>   // DT_F32 or DT_F16 exact rows
+__global__ __launch_bounds__(256) void rescore_kernel(const u64 *__restrict__ sel,
+                                                      const uint32_t *__restrict__ sel_cnt, int k_prime,
+                                                      int kp2, const float *__restrict__ queries,
+                                                      const void *__restrict__ exact, int64_t ld, int d,
+                                                      int k, int32_t *__restrict__ out_ids,
+                                                      float *__restrict__ out_scores,
+                                                      float *__restrict__ out_margin)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    u64 *keys = reinterpret_cast<u64 *>(smem);   // [kp2]
+    __shared__ u64 s_min_scan[4];
+
+    const int64_t q = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t n_raw = sel_cnt[q];
+    const bool overflow = n_raw == 0xffffffffu;
+    const int n = overflow ? 0 : (int)n_raw;
+    const u64 *mine = sel + q * (int64_t)k_prime;
+    const float *qv = queries + q * (int64_t)d;
+
+    u64 min_scan = ~0ull;
+    for (int c = wave; c < n; c += 4) {
+        const u64 skey = mine[c];
+        min_scan = skey < min_scan ? skey : min_scan;
+        const int32_t id = key_id(skey);
+        double sum = 0.0;
+        if constexpr (EX == DT_F32) {
+            const float *row = static_cast<const float *>(exact) + (int64_t)id * ld;
+            for (int j = lane * 4; j < d; j += 256) {
+                const float4 x = *reinterpret_cast<const float4 *>(row + j);
+                const float4 y = *reinterpret_cast<const float4 *>(qv + j);
+                sum += (double)x.x * (double)y.x;
+                sum += (double)x.y * (double)y.y;
+                sum += (double)x.z * (double)y.z;
+                sum += (double)x.w * (double)y.w;
+            }
+        } else {
+            const uint16_t *row = static_cast<const uint16_t *>(exact) + (int64_t)id * ld;
+            for (int j = lane * 8; j < d; j += 512) {
+                const uint4 x = *reinterpret_cast<const uint4 *>(row + j);
+                const float4 y0 = *reinterpret_cast<const float4 *>(qv + j);
+                const float4 y1 = *reinterpret_cast<const float4 *>(qv + j + 4);
+                sum += (double)f16_bits_to_f32(x.x & 0xffffu) * (double)y0.x;
+                sum += (double)f16_bits_to_f32(x.x >> 16) * (double)y0.y;
+                sum += (double)f16_bits_to_f32(x.y & 0xffffu) * (double)y0.z;
+                sum += (double)f16_bits_to_f32(x.y >> 16) * (double)y0.w;
+                sum += (double)f16_bits_to_f32(x.z & 0xffffu) * (double)y1.x;
+                sum += (double)f16_bits_to_f32(x.z >> 16) * (double)y1.y;
+                sum += (double)f16_bits_to_f32(x.w & 0xffffu) * (double)y1.z;
+                sum += (double)f16_bits_to_f32(x.w >> 16) * (double)y1.w;
+            }
+        }
+        sum = wave_sum(sum);
+        if (lane == 0) keys[c] = make_key((float)sum, id);
+    }
+    for (int c = n + tid; c < kp2; c += 256) keys[c] = 0ull;
+    if (lane == 0) s_min_scan[wave] = min_scan;
+    __syncthreads();
+
+    // bitonic sort, descending by key
+    for (int size = 2; size <= kp2; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int t = tid; t < kp2 / 2; t += 256) {
+                const int lo = 2 * t - (t & (stride - 1));
+                const int hi = lo + stride;
+                const bool desc = (lo & size) == 0;
+                const u64 a = keys[lo], b = keys[hi];
+                if ((a < b) == desc) {
+                    keys[lo] = b;
+                    keys[hi] = a;
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    for (int r = tid; r < k; r += 256) {
+        const u64 key = keys[r];
+        const bool have = r < n;
+        out_ids[q * k + r] = have ? key_id(key) : -1;
+        out_scores[q * k + r] = have ? key_score(key) : (overflow ? __builtin_nanf("") : -__builtin_inff());
+    }
+    if (out_margin && tid == 0) {
+        u64 ms = s_min_scan[0];
+        for (int w = 1; w < 4; ++w) ms = s_min_scan[w] < ms ? s_min_scan[w] : ms;
+        float margin;
+        if (overflow || n < k)
+            margin = __builtin_nanf("");
+        else if (n < k_prime)
+            margin = __builtin_inff();   // every row of the datastore was re-scored
+        else
+            margin = key_score(keys[k - 1]) - key_score(ms);
+        out_margin[q] = margin;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_select(const u64 *cand, const uint32_t *cnt, uint32_t cap, int32_t k_prime, int64_t Q,
+                         u64 *tau, u64 *sel, uint32_t *sel_cnt, int32_t *overflow_count,
+                         hipStream_t stream)
+{
+    if (Q <= 0) return hipSuccess;
+    hipLaunchKernelGGL(select_kernel, dim3((unsigned)Q), dim3(256), 0, stream, cand, cnt, cap, k_prime,
+                       tau, sel, sel_cnt, overflow_count);
+    return hipGetLastError();
+}
+
+hipError_t launch_rescore(const u64 *sel, const uint32_t *sel_cnt, int32_t k_prime, const float *queries,
+                          int64_t Q, const void *exact, int32_t exact_dtype, int64_t ld, int32_t d,
+                          int32_t k, int32_t *out_ids, float *out_scores, float *out_margin,
+                          hipStream_t stream)
+{
+    if (Q <= 0) return hipSuccess;
+    int kp2 = 2;
+    while (kp2 < k_prime) kp2 <<= 1;
+    const size_t smem = (size_t)kp2 * sizeof(u64);
+    if (exact_dtype == DT_F16)
+        hipLaunchKernelGGL(rescore_kernel<DT_F16>, dim3((unsigned)Q), dim3(256), smem, stream, sel, sel_cnt,
+                           k_prime, kp2, queries, exact, ld, d, k, out_ids, out_scores, out_margin);
+    else
+        hipLaunchKernelGGL(rescore_kernel<DT_F32>, dim3((unsigned)Q), dim3(256), smem, stream, sel, sel_cnt,
+                           k_prime, kp2, queries, exact, ld, d, k, out_ids, out_scores, out_margin);
+    return hipGetLastError();
+}
+
+}  // namespace ralm

@@ -1,0 +1,86 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header
+declares, and rejects bad arguments with a status before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2401_14021_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2401_14021_amd import build
+        build.build()
+    return binding.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    text = open(os.path.join(ROOT, "include", "ralm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(ralm_[a-z0-9_]+)\s*\(", text))
+    assert {"ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_cache_lookup", "ralm_verify",
+            "ralm_workspace_bytes", "ralm_build_scan_copy", "ralm_last_error"} <= names
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def _ds(binding, N=1000, d=768, exact=0x1000, exact_dtype=0, scan=0x2000, scan_dtype=1):
+    ds = binding.ralm_datastore_t()
+    ds.exact, ds.exact_dtype, ds.scan, ds.scan_dtype = exact, exact_dtype, scan, scan_dtype
+    ds.N, ds.d, ds.exact_stride, ds.scan_stride = N, d, 0, 0
+    return ds
+
+
+def test_argument_errors_return_status_without_a_device(L):
+    from paper_2401_14021_amd import binding as b
+    P = 0x10000   # fake, aligned, never dereferenced: every call below fails validation first
+    ds = _ds(b)
+    ref = ctypes.byref
+    ws = L.ralm_workspace_bytes(8, ref(ds), 5, 0)
+    assert ws > 0
+    call = L.ralm_retrieve_topk_ex
+    assert call(None, 8, ref(ds), 5, 0, P, P, None, P, ws, None) == 1            # NULL queries
+    assert b"NULL" in L.ralm_last_error()
+    assert call(P, 0, ref(ds), 5, 0, P, P, None, P, ws, None) == 2               # Q < 1
+    assert call(P, 8, ref(ds), 0, 0, P, P, None, P, ws, None) == 3               # k < 1
+    assert call(P, 8, ref(ds), 2000, 0, P, P, None, P, ws, None) == 3            # k > N and > max
+    assert call(P, 8, ref(ds), 5, 4, P, P, None, P, ws, None) == 3               # k' < k
+    assert call(P, 8, ref(ds), 5, 8192, P, P, None, P, ws, None) == 3            # k' > max
+    assert call(P, 8, ref(_ds(b, exact_dtype=1)), 5, 0, P, P, None, P, ws, None) == 4   # bf16 exact copy
+    assert call(P, 8, ref(_ds(b, scan_dtype=7)), 5, 0, P, P, None, P, ws, None) == 4
+    assert call(P, 8, ref(_ds(b, d=770)), 5, 0, P, P, None, P, ws, None) == 2    # d not a multiple of 8
+    assert call(P, 8, ref(_ds(b, exact=0x1004)), 5, 0, P, P, None, P, ws, None) == 5
+    assert call(P + 4, 8, ref(ds), 5, 0, P, P, None, P, ws, None) == 5
+    assert call(P, 8, ref(ds), 5, 0, P, P, None, None, ws, None) == 6            # no workspace
+    assert call(P, 8, ref(ds), 5, 0, P, P, None, P + 16, ws, None) == 6          # misaligned workspace
+    assert call(P, 8, ref(ds), 5, 0, P, P, None, P, ws - 1, None) == 6           # too small
+    assert L.ralm_workspace_bytes(8, ref(ds), 0, 0) == 0
+    assert L.ralm_workspace_bytes(0, ref(ds), 5, 0) == 0
+    # workspace grows with Q and with k'
+    assert L.ralm_workspace_bytes(1024, ref(ds), 5, 0) > ws
+    assert L.ralm_workspace_bytes(8, ref(ds), 1000, 0) > ws
+    # simple form
+    assert L.ralm_retrieve_topk(None, 8, P, 1000, 768, 5, P, P) == 1
+    assert L.ralm_retrieve_topk(P, 8, P, 1000, 768, 1001, P, P) == 3
+    # cache lookup / verify / scan copy
+    assert L.ralm_cache_lookup(None, P, 4, 2, P, 6, P, ref(ds), P, P, None) == 1
+    assert L.ralm_cache_lookup(P, P, 0, 2, P, 6, P, ref(ds), P, P, None) == 2
+    assert L.ralm_cache_lookup(P, P, 4, 2, P, -1, P, ref(ds), P, P, None) == 7
+    assert L.ralm_verify(P, None, 1, 6, P, 2, P, None) == 1
+    assert L.ralm_verify(P, P, 0, 6, P, 2, P, None) == 7
+    assert L.ralm_verify(P, P, 1, 6, P, -1, P, None) == 2
+    assert L.ralm_build_scan_copy(P, 0, P, 0, 0, 10, 768, None) == 4             # fp32 is not a scan copy
+    assert L.ralm_build_scan_copy(P, 0, P, 1, 0, 10, 12, None) == 2
+    assert L.ralm_build_scan_copy(P, 0, None, 1, 0, 10, 768, None) == 1
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch):
+    from paper_2401_14021_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libralm.so")
+    with pytest.raises(FileNotFoundError):
+        binding.lib()

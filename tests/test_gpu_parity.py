@@ -1,0 +1,235 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integer / index results are bit-exact; floating point follows tests/parity.py."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from parity import check_topk
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(scope="module")
+def B():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2401_14021_amd import binding
+    binding.lib()
+    return binding
+
+
+def _score_fn(oracle, Qm, Xnp):
+    def f(i, ids):
+        return oracle.scores(Qm[i], Xnp[np.asarray(ids, dtype=np.int64)])
+    return f
+
+
+def _retrieve_both(B, oracle, X, Qm, k, k_prime=0, scan_dtype=torch.bfloat16, margin=False):
+    dev = "cuda"
+    Xd = X.to(dev)
+    ds = B.Datastore.from_fp32(Xd, scan_dtype) if X.dtype == torch.float32 else B.Datastore(Xd, None)
+    qd = Qm.to(dev)
+    ws = B.alloc_workspace(qd.shape[0], ds, k, k_prime)
+    mg = torch.empty(qd.shape[0], dtype=torch.float32, device=dev) if margin else None
+    ids, sc = B.ralm_retrieve_topk_ex(qd, ds, k, k_prime, workspace=ws, out_margin=mg)
+    assert B.ralm_workspace_overflows(ws) == 0
+    want_ids, want_sc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), k)
+    return ids.cpu().numpy(), sc.cpu().numpy(), want_ids, want_sc, (mg.cpu().numpy() if margin else None)
+
+
+def _pad8(a):
+    out = np.zeros((a.shape[0], 8), dtype=np.float32)
+    out[:, :a.shape[1]] = a
+    return out
+
+
+def test_hand_enumerated_rankings_on_gpu(B, oracle):
+    from test_oracle_pins import _read_hand_cases
+    X, cases = _read_hand_cases()
+    Xp = torch.from_numpy(_pad8(X))
+    Qm = torch.from_numpy(_pad8(np.array([c[0] for c in cases], dtype=np.float32)))
+    for k in (1, 3, 6):
+        ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, Xp, Qm, k)
+        assert ids.tolist() == [c[1][:k] for c in cases]
+        assert sc.tolist() == [c[2][:k] for c in cases]
+        assert np.array_equal(ids, wi) and np.array_equal(sc, wsc)
+
+
+@pytest.mark.parametrize("N,d,Q,k", [
+    (805, 8, 1, 1), (805, 72, 3, 5), (2101, 768, 33, 20), (2101, 136, 70, 64),
+    (5000, 768, 130, 100), (1300, 1024, 300, 7), (300, 64, 5, 300), (70000, 256, 9, 20),
+])
+def test_integer_valued_data_bit_exact(B, oracle, N, d, Q, k):
+    """Small integers are exact in bf16 and every sum is exact in fp32, so the scan, the
+    selection, the ties (by lowest id) and the re-score must reproduce the oracle bit for bit.
+    Sizes span several 256-row tiles with a ragged tail, ragged query tiles and d tails."""
+    g = torch.Generator().manual_seed(N * 31 + d + Q)
+    X = torch.randint(-3, 4, (N, d), generator=g).float()
+    Qm = torch.randint(-3, 4, (Q, d), generator=g).float()
+    ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, X, Qm, k)
+    assert np.array_equal(ids, wi)
+    assert np.array_equal(sc, wsc)
+
+
+@pytest.mark.parametrize("scan_dtype", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("N,d,Q,k", [(40000, 768, 6, 20), (9000, 256, 150, 5)])
+def test_clustered_real_valued(B, oracle, scan_dtype, N, d, Q, k):
+    from paper_2401_14021_amd import inputs
+    X, _ = inputs.clustered_datastore(N, d, 64, seed=N + d)
+    rows = inputs.pick_rows(N, Q, seed=5)
+    Qm = inputs.queries_near_rows(X, rows, seed=6)
+    ids, sc, wi, wsc, mg = _retrieve_both(B, oracle, X, Qm, k, scan_dtype=scan_dtype, margin=True)
+    exact, subs, total = check_topk(ids, sc, wi, wsc, _score_fn(oracle, Qm.numpy(), X.numpy()))
+    assert exact >= 0.99 * total
+    assert np.all(np.isfinite(mg))
+
+
+def test_simple_form_fp32_datastore(B, oracle):
+    from paper_2401_14021_amd import inputs
+    X, _ = inputs.clustered_datastore(30000, 768, 32, seed=77)
+    Qm = inputs.queries_near_rows(X, inputs.pick_rows(30000, 4, seed=1), seed=2)
+    ids, sc = B.ralm_retrieve_topk(Qm.cuda(), X.cuda(), 5)
+    wi, wsc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), 5)
+    check_topk(ids.cpu().numpy(), sc.cpu().numpy(), wi, wsc, _score_fn(oracle, Qm.numpy(), X.numpy()))
+
+
+def test_fp16_keys_are_the_truth_large_k(B, oracle):
+    """KNN-LM shape at reduced N: fp16 keys (no fp32 copy), raw inner product, k = 1024."""
+    from paper_2401_14021_amd import inputs
+    N, d, Q, k = 60000, 1024, 12, 1024
+    keys, _ = inputs.knnlm_datastore(N, d, 16, seed=4)
+    Qm = inputs.queries_near_rows(keys, inputs.pick_rows(N, Q, seed=8), seed=9, sigma=0.5)
+    ds = B.Datastore(keys.cuda(), None)
+    ws = B.alloc_workspace(Q, ds, k)
+    ids, sc = B.ralm_retrieve_topk_ex(Qm.cuda(), ds, k, workspace=ws)
+    assert B.ralm_workspace_overflows(ws) == 0
+    wi, wsc = oracle.retrieve_topk(Qm.numpy(), keys.numpy(), k)
+    exact, subs, total = check_topk(ids.cpu().numpy(), sc.cpu().numpy(), wi, wsc,
+                                    _score_fn(oracle, Qm.numpy(), keys.numpy()))
+    assert exact >= 0.98 * total
+
+
+def test_edge_cases(B, oracle):
+    g = torch.Generator().manual_seed(3)
+    # N smaller than a tile and than k'; k = N
+    X = torch.randn(40, 16, generator=g)
+    Qm = torch.randn(2, 16, generator=g)
+    ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, X, Qm, 40)
+    check_topk(ids, sc, wi, wsc, _score_fn(oracle, Qm.numpy(), X.numpy()))
+    # all scores equal (zero query): ties resolve to the lowest ids, no candidate overflow
+    X = torch.randn(50000, 64, generator=g)
+    Qz = torch.zeros(3, 64)
+    ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, X, Qz, 20)
+    assert np.array_equal(ids, np.tile(np.arange(20, dtype=np.int32), (3, 1))) and np.array_equal(ids, wi)
+    assert np.all(sc == 0)
+    # heavy duplication: 30000 copies of 3 distinct rows
+    base = torch.randint(-2, 3, (3, 32), generator=g).float()
+    X = base[torch.randint(0, 3, (30000,), generator=g)]
+    Qm = torch.randint(-2, 3, (4, 32), generator=g).float()
+    ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, X, Qm, 50)
+    assert np.array_equal(ids, wi) and np.array_equal(sc, wsc)
+
+
+def test_batched_equals_sequential_and_is_deterministic(B, oracle):
+    """A query's result does not depend on what else is in the batch (the property that makes
+    batched verification output-preserving), nor on the run."""
+    from paper_2401_14021_amd import inputs
+    X, _ = inputs.clustered_datastore(50000, 768, 64, seed=21)
+    Qm = inputs.queries_near_rows(X, inputs.pick_rows(50000, 140, seed=3), seed=4)
+    ds = B.Datastore.from_fp32(X.cuda())
+    qd = Qm.cuda()
+    full_ids, full_sc = B.ralm_retrieve_topk_ex(qd, ds, 5)
+    for rep in range(2):
+        i2, s2 = B.ralm_retrieve_topk_ex(qd, ds, 5)
+        assert torch.equal(i2, full_ids) and torch.equal(s2, full_sc)
+    for lo, hi in ((0, 1), (7, 8), (0, 33), (60, 140)):
+        i2, s2 = B.ralm_retrieve_topk_ex(qd[lo:hi].contiguous(), ds, 5)
+        assert torch.equal(i2, full_ids[lo:hi]) and torch.equal(s2, full_sc[lo:hi])
+
+
+def test_scan_copy_rounding(B):
+    g = torch.Generator().manual_seed(1)
+    X = (torch.randn(1000, 72, generator=g) * 3).cuda()
+    for dt in (torch.bfloat16, torch.float16):
+        out = torch.empty(X.shape, dtype=dt, device="cuda")
+        B.ralm_build_scan_copy(X, out)
+        assert torch.equal(out, X.to(dt))          # torch rounds to nearest even too
+
+
+# ---------------------------------------------------------------------------------------------
+def test_verify_worked_example_and_random(B, oracle):
+    for line in open(os.path.join(GOLDEN, "verify_worked_example.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        spec, truth, m = line.split("|")
+        spec = torch.tensor([int(v) for v in spec.split()], dtype=torch.int32).cuda()
+        truth = torch.tensor([int(v) for v in truth.split()], dtype=torch.int32).cuda()
+        off = torch.tensor([0, len(spec)], dtype=torch.int64).cuda()
+        assert B.ralm_verify(spec, truth, off).cpu().tolist() == [int(m)]
+    rng = np.random.default_rng(0)
+    strides = rng.integers(0, 9, size=700).tolist() + [64, 65, 200, 0, 1]
+    off = np.concatenate([[0], np.cumsum(strides)]).astype(np.int64)
+    Qt, k = int(off[-1]), 5
+    truth = rng.integers(0, 50, size=(Qt, k)).astype(np.int32)
+    spec = truth[:, 0].copy()
+    flip = rng.random(Qt) < 0.15
+    spec[flip] = -7
+    spec[off[-4] + 150] = -9                      # a mismatch deep inside the 200-step request
+    want = oracle.verify(spec, truth.reshape(-1), off, true_stride=k)
+    got = B.ralm_verify(torch.from_numpy(spec).cuda(), torch.from_numpy(truth).cuda().reshape(-1),
+                        torch.from_numpy(off).cuda(), true_stride=k)
+    assert np.array_equal(got.cpu().numpy(), want)
+
+
+def test_cache_lookup_against_oracle(B, oracle):
+    from paper_2401_14021_amd import inputs
+    N, d, R, C = 20000, 768, 37, 300
+    X, assign = inputs.clustered_datastore(N, d, 32, seed=12)
+    strides = inputs.uniform_strides(R - 3, 1, 8, seed=2) + [0, 40, 1]   # empty, > one LDS group, single
+    off = inputs.stride_offsets(strides)
+    rows = inputs.pick_rows(N, int(off[-1]), seed=3)
+    Qm = inputs.queries_near_rows(X, rows, seed=4)
+    cids, clen = inputs.speculation_caches(N, R, C, off, rows, assign, seed=5)
+    clen[5] = 0                                                          # an empty cache
+    clen[6] = 1
+    want_ids, want_sc = oracle.cache_lookup(cids.numpy(), clen.numpy(), Qm.numpy(), off.numpy(), X.numpy())
+    ds = B.Datastore(X.cuda(), None)
+    got_ids, got_sc = B.ralm_cache_lookup(cids.cuda(), clen.cuda(), Qm.cuda(), off.cuda(), ds)
+    assert np.array_equal(got_ids.cpu().numpy(), want_ids)
+    assert np.array_equal(got_sc.cpu().numpy(), want_sc)
+    # rank preservation against the knowledge-base retrieval on the GPU (Section 3)
+    ds2 = B.Datastore.from_fp32(X.cuda())
+    true_ids, true_sc = B.ralm_retrieve_topk_ex(Qm.cuda(), ds2, 1)
+    t, s = true_ids.cpu().numpy()[:, 0], true_sc.cpu().numpy()[:, 0]
+    hits = 0
+    for r in range(R):
+        mine = set(cids[r, :clen[r]].tolist())
+        for i in range(int(off[r]), int(off[r + 1])):
+            if int(t[i]) in mine:
+                hits += 1
+                assert got_ids[i].item() == t[i] and got_sc[i].item() == s[i]
+    assert hits > 10
+
+
+def test_tiny_config_whole_path(B, oracle):
+    """The tiny configuration end to end: cache top-1 for the 3 speculative steps, one batched
+    exact top-1 retrieval of the 3 queries, first-mismatch compare."""
+    from paper_2401_14021_amd import inputs
+    w = inputs.WORKLOADS["tiny"]
+    X, assign = inputs.clustered_datastore(w.N, w.d, w.n_clusters, seed=w.seed)
+    off = inputs.stride_offsets([3])
+    rows = inputs.pick_rows(w.N, 3, seed=w.seed + 1)
+    Qm = inputs.queries_near_rows(X, rows, seed=w.seed + 2)
+    cids, clen = inputs.speculation_caches(w.N, 1, w.cache_C, off, rows, assign, seed=w.seed + 3)
+    ds = B.Datastore.from_fp32(X.cuda())
+    spec, spec_sc = B.ralm_cache_lookup(cids.cuda(), clen.cuda(), Qm.cuda(), off.cuda(), ds)
+    ids, sc = B.ralm_retrieve_topk_ex(Qm.cuda(), ds, w.k, w.k_prime)
+    m = B.ralm_verify(spec, ids, off.cuda(), true_stride=w.k)
+    wi, wsc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), w.k)
+    ws_ids, ws_sc = oracle.cache_lookup(cids.numpy(), clen.numpy(), Qm.numpy(), off.numpy(), X.numpy())
+    wm = oracle.verify(ws_ids, wi.reshape(-1), off.numpy(), true_stride=w.k)
+    check_topk(ids.cpu().numpy(), sc.cpu().numpy(), wi, wsc, _score_fn(oracle, Qm.numpy(), X.numpy()))
+    assert np.array_equal(spec.cpu().numpy(), ws_ids) and np.array_equal(spec_sc.cpu().numpy(), ws_sc)
+    assert np.array_equal(m.cpu().numpy(), wm)
