@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the retrieval hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic queries:
+speculative cache top-1 for every query, the batched exact top-k retrieval
+(query rounding, MFMA scan with fused selection, k'-select, exact re-score) and
+the first-mismatch compare.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: queries/s for the headline batch size, the roofline
+figures of the dominant kernel (the full-datastore scan) measured with HIP
+events inside the library, a sweep over the other batch sizes, and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_PEAK_TFLOPS = 2500.0    # dense bf16 / fp16
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="dense21m", choices=["tiny", "medium", "dense21m", "knnlm100m"])
+    ap.add_argument("--Q", type=int, default=0, help="headline batch size (0 = workload default)")
+    ap.add_argument("--k", type=int, default=0)
+    ap.add_argument("--N", type=int, default=0, help="override datastore rows (for quick runs)")
+    ap.add_argument("--sweep", default="", help="comma-separated extra batch sizes ('' = workload default, 'none')")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build is a one-GPU kernel path; run with --gpus 1 "
+              "(row-sharding over several GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2401_14021_amd import binding as B, inputs
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    w = inputs.WORKLOADS[args.workload]
+    N = args.N or w.N
+    k = args.k or w.k
+    defaults = {"tiny": (3, []), "medium": (128, [16, 32, 64]),
+                "dense21m": (1024, [1, 8, 64, 256]), "knnlm100m": (256, [])}
+    Qh, sweep = defaults[args.workload]
+    if args.Q:
+        Qh = args.Q
+    if args.sweep == "none":
+        sweep = []
+    elif args.sweep:
+        sweep = [int(v) for v in args.sweep.split(",")]
+    sweep = [q for q in sweep if q != Qh]
+
+    # ---- inputs, resident in HBM -------------------------------------------------------------
+    t0 = time.time()
+    if w.exact_dtype == "f16":
+        keys = torch.empty(N, w.d, dtype=torch.float16, device=dev)
+        inputs.knnlm_datastore(N, w.d, w.n_clusters, w.seed, device=dev, out=keys)
+        ds = B.Datastore(keys, None)
+        assign = None
+        q_sigma = 0.5
+    else:
+        X = torch.empty(N, w.d, dtype=torch.float32, device=dev)
+        _, assign = inputs.clustered_datastore(N, w.d, w.n_clusters, w.seed, device=dev, out=X)
+        ds = B.Datastore.from_fp32(X, torch.bfloat16 if w.scan_dtype == "bf16" else torch.float16)
+        q_sigma = 0.05
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+
+    C = w.cache_C or 1024
+    stride = 4
+
+    def make_batch(Q, seed):
+        R = max(1, (Q + stride - 1) // stride)
+        strides = [min(stride, Q - r * stride) for r in range(R)]
+        off = inputs.stride_offsets(strides)
+        rows = inputs.pick_rows(N, Q, seed=seed)
+        Qm = inputs.queries_near_rows(ds.exact, rows.to(dev), seed=seed + 1, sigma=q_sigma)
+        # caches: source rows with probability 1/2 plus uniform filler (drawn on the host)
+        cids, clen = inputs.speculation_caches(N, R, C, off, rows, None, seed=seed + 2)
+        return dict(Q=Q, R=R, off=off.to(dev), Qm=Qm, cids=cids.to(dev), clen=clen.to(dev),
+                    ws=B.alloc_workspace(Q, ds, k, w.k_prime),
+                    ids=torch.empty(Q, k, dtype=torch.int32, device=dev),
+                    sc=torch.empty(Q, k, dtype=torch.float32, device=dev),
+                    spec=torch.empty(Q, dtype=torch.int32, device=dev),
+                    spec_sc=torch.empty(Q, dtype=torch.float32, device=dev),
+                    mism=torch.empty(R, dtype=torch.int32, device=dev))
+
+    def step(b):
+        B.ralm_cache_lookup(b["cids"], b["clen"], b["Qm"], b["off"], ds, b["spec"], b["spec_sc"])
+        B.ralm_retrieve_topk_ex(b["Qm"], ds, k, w.k_prime, workspace=b["ws"], out_ids=b["ids"],
+                                out_scores=b["sc"])
+        B.ralm_verify(b["spec"], b["ids"], b["off"], true_stride=k, first_mismatch=b["mism"])
+
+    def run(Q, steps, warmup):
+        b = make_batch(Q, seed=w.seed * 7 + Q)
+        for _ in range(warmup):
+            step(b)
+        torch.cuda.synchronize()
+        B.ralm_profile_enable(True)
+        B.ralm_profile_scan_ms()          # reset
+        t = time.perf_counter()
+        for _ in range(steps):
+            step(b)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        scan_ms, launches = B.ralm_profile_scan_ms()
+        B.ralm_profile_enable(False)
+        assert launches == steps
+        assert B.ralm_workspace_overflows(b["ws"]) == 0, "candidate buffer overflow"
+        ms = dt / steps * 1e3
+        scan = scan_ms / launches
+        bytes_scan = N * w.d * 2
+        flops = 2.0 * Q * N * w.d
+        hit = float((b["spec"] == b["ids"][:, 0]).float().mean().item())
+        return dict(Q=Q, ms_per_step=ms, qps=Q / ms * 1e3, scan_ms=scan,
+                    scan_GBps=bytes_scan / scan / 1e6, scan_TFLOPs=flops / scan / 1e9,
+                    spec_hit_rate=hit), b
+
+    head, hb = run(Qh, args.steps, args.warmup)
+    sweep_out = []
+    for q in sweep:
+        r, _ = run(q, args.steps, args.warmup)
+        sweep_out.append({kk: (round(v, 4) if isinstance(v, float) else v) for kk, v in r.items()})
+
+    hbm_bound = head["Q"] < 300          # arithmetic intensity of the scan is Q flop/byte; ridge ~ 312
+    if hbm_bound:
+        roof = {"bound": "hbm", "achieved": round(head["scan_GBps"], 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(head["scan_GBps"] / HBM_PEAK_GBS, 4), "traffic": None}
+    else:
+        roof = {"bound": "mfma", "achieved": round(head["scan_TFLOPs"], 1), "peak": MFMA_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(head["scan_TFLOPs"] / MFMA_PEAK_TFLOPS, 4), "traffic": None}
+    roof["kernel"] = "scan_kernel (full-datastore stage)"
+    roof["kernel_ms"] = round(head["scan_ms"], 4)
+
+    # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        n_s = min(N, 6_000_000)
+        q_s = min(Qh, 16)
+        Xs = ds.exact[:n_s].cpu().numpy()
+        qs = hb["Qm"][:q_s].cpu().numpy()
+        t = time.perf_counter()
+        o_ids, _ = oracle.retrieve_topk(qs, Xs, k)
+        ot = time.perf_counter() - t
+        # retrieval over the first n_s rows costs n_s/N of a full query (scores are linear in N)
+        cpu = {"value": round(q_s / (ot * N / n_s), 4), "unit": "queries/s", "cores": oracle.threads(),
+               "kind": "oracle",
+               "sample": f"{q_s} queries x first {n_s} of {N} rows, exact top-{k}; {ot:.1f} s measured, "
+                         f"scaled by N/{n_s} to a full-datastore query"}
+
+    out = {
+        "metric": "queries/sec exact top-k over 21M x 768 datastore" if args.workload == "dense21m" and not args.N
+                  else f"queries/sec exact top-k over {N} x {w.d} datastore",
+        "value": round(head["qps"], 2), "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(head["ms_per_step"], 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.scan_dtype == "bf16" else "f16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: N={N} d={w.d} scan={w.scan_dtype} exact={w.exact_dtype} "
+                               f"Q={head['Q']} k={k} k_prime={w.k_prime} requests={hb['R']} stride<={stride} "
+                               f"cache={C}",
+                   "gen_seconds": round(gen_s, 1), "spec_hit_rate": round(head["spec_hit_rate"], 3)},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "sweep": sweep_out,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
