@@ -8,11 +8,19 @@
 // that pass are appended to that query's candidate list.
 //
 // Tiling: a workgroup of 4 waves owns a 256-row x BN-query tile; the reduction dimension is
-// walked in steps of 64 elements staged through LDS (double buffered, global loads for step
-// t+1 in flight while step t is multiplied).  Datastore rows are the A operand of
-// v_mfma_f32_32x32x16, queries the B operand, so every accumulator register of a lane
-// belongs to ONE query (column = lane % 32) and the lane can hold that query's threshold in
-// a register.
+// walked in strips of BK elements.  Datastore rows are the A operand of v_mfma_f32_32x32x16,
+// queries the B operand, so every accumulator register of a lane belongs to ONE query
+// (column = lane % 32) and the lane can hold that query's threshold in a register.
+//
+// Two kernels share that tiling and the epilogue:
+//   scan_dma_kernel     bf16 / fp16 datastore copies.  Strips go from global memory straight
+//                       into LDS (global_load_lds_dwordx4, no VGPR staging) through a ring of
+//                       S stages that runs ahead of the multiply and keeps running across tile
+//                       boundaries; the 16-byte chunks of a row are XOR-swizzled on the way in
+//                       (by choosing which global chunk each lane fetches) so that the MFMA
+//                       operand reads (32 rows, same chunk) are free of bank conflicts.
+//   scan_staged_kernel  fp32 datastore: rows are rounded to bf16 in registers on the way to
+//                       LDS (double buffered).
 //
 // Work items (row tile, query tile) are dealt to a persistent grid so that workgroups that
 // run at the same time on one XCD (workgroup b lands on XCD b % 8) hold consecutive items:
@@ -74,9 +82,57 @@ __device__ __forceinline__ f32x16 mfma32(const uint4 &a, const uint4 &b, const f
                                                        __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// Selection epilogue shared by both kernels: one query per lane and MFMA block column.
+// acc[i][j][v] is the score of datastore row  row0 + (wm*TM + i)*32 + (v/4)*8 + (lane/32)*4 + v%4
+// against query  q0 + (wn*TN + j)*32 + lane%32.  A score is appended to its query's candidate
+// list iff its ranking key is >= the query's admission key.
+template <int WM, int WN, int TM, int TN>
+__device__ __forceinline__ void select_epilogue(const ScanParams &p, const u64 *tau_lds,
+                                                f32x16 (&acc)[TM][TN], int64_t row0, int q0, int wm,
+                                                int wn, int lane)
+{
+    const int fr = lane & 31;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int q = q0 + (wn * TN + j) * 32 + fr;
+        const bool qok = q < p.Q;
+        const u64 tkey = qok ? (tau_lds ? tau_lds[q] : p.tau[q]) : ~0ull;
+        const float tsc = qok ? key_score(tkey) : __builtin_inff();
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            float m = acc[i][j][0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) m = fmaxf(m, acc[i][j][v]);
+            // tkey == 0 admits everything (its score bits decode to NaN: compare separately)
+            if (qok && (tkey == 0ull || m >= tsc)) {
+                const int64_t rbase = row0 + (wm * TM + i) * 32 + (lane >> 5) * 4;
+                uint32_t pass = 0;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int64_t g = rbase + (v >> 2) * 8 + (v & 3);
+                    if (g < p.N && make_key(acc[i][j][v], (int32_t)g) >= tkey) pass |= 1u << v;
+                }
+                if (pass) {
+                    const uint32_t n = __popc(pass);
+                    uint32_t at = atomicAdd(p.cnt + q, n);
+                    u64 *dst = p.cand + (int64_t)q * p.cap;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        if (pass & (1u << v)) {
+                            const int64_t g = rbase + (v >> 2) * 8 + (v & 3);
+                            if (at < p.cap) dst[at] = make_key(acc[i][j][v], (int32_t)g);
+                            ++at;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
 // IN: dtype of the datastore copy being scanned.  WM x WN waves, each TM x TN MFMA blocks.
 template <int IN, int WM, int WN, int TM, int TN>
-__global__ __launch_bounds__(256) void scan_kernel(const ScanParams p, const int nqt)
+__global__ __launch_bounds__(256) void scan_staged_kernel(const ScanParams p, const int nqt)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = SCAN_BK, LDA = BK + 8;
     constexpr int PA = BM / 32, PB = BN / 32;
@@ -166,43 +222,230 @@ __global__ __launch_bounds__(256) void scan_kernel(const ScanParams p, const int
             __syncthreads();
         }
 
-        // ---- selection epilogue: one query per lane and MFMA block column ----
+        select_epilogue<WM, WN, TM, TN>(p, nullptr, acc, row0, q0, wm, wn, lane);
+    }
+}
+
+
+// ---- direct-to-LDS pipelined kernel ----------------------------------------------------------
+// LDS chunk swizzle: row r of a strip stores its global 16-byte chunk c at chunk slot c ^ swz(r).
+// Chosen so that 8 or 16 consecutive rows reading the same global chunk touch distinct
+// 16-byte bank groups, for both 128 B and 256 B of LDS banking.
+template <int BK>
+__device__ __forceinline__ int swz(int r)
+{
+    if constexpr (BK == 64)
+        return (r ^ (r >> 3)) & 7;
+    else
+        return ((r >> 2) & 1) | ((((r >> 1) ^ (r >> 3)) & 1) << 1);
+}
+
+// 64 lanes x 16 bytes from per-lane global addresses to 1 KB of LDS starting at lds_base
+// (wave-uniform).  Written as inline asm so that the compiler does not track it: completion is
+// awaited by hand with s_waitcnt vmcnt(n) (loads complete in order).
+__device__ __forceinline__ void dma_1kb(const void *gptr, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+constexpr int TAU_LDS_MAX_Q = 3072;   // admission keys of up to this many queries are kept in LDS
+
+// wait until at most `later` of this wave's stage loads are still in flight
+template <int LPS, int MAXL>
+__device__ __forceinline__ void wait_stages(int64_t later)
+{
+    if (later >= MAXL)
+        wait_vmcnt<LPS * MAXL>();
+    else if (MAXL > 1 && later == 1)
+        wait_vmcnt<LPS>();
+    else
+        wait_vmcnt<0>();
+}
+
+template <bool F16, int WM, int WN, int TM, int TN, int BK, int S>
+__global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const int nqt, const int tau_in_lds)
+{
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr int ROWB = BK * 2;                 // bytes of one strip row
+    constexpr int CPR = BK / 8;                  // 16-byte chunks per strip row
+    constexpr int RPI = 64 / CPR;                // rows covered by one wave load
+    constexpr int NA = BM / RPI / 4, NB = BN / RPI / 4;   // wave loads per wave and stage
+    constexpr int LPS = NA + NB;
+    constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
+    constexpr int KS = BK / 16;
+    static_assert(WM * WN == 4 && BM == SCAN_BM && NB >= 1, "tile shape");
+    static_assert(S >= 3 && S <= 4 && KS % 2 == 0, "ring depth / k-steps per stage");
+    static_assert(LPS * (S - 2) < 64, "vmcnt range");
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    u64 *tau_lds = reinterpret_cast<u64 *>(smem + S * STAGE);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int fr = lane & 31;
+    const int l_r = lane / CPR, l_c = lane % CPR;
+
+    const int64_t G = gridDim.x;
+    const int64_t vb = (int64_t)(blockIdx.x % 8) * (G / 8) + blockIdx.x / 8;
+    const int64_t total = p.n_row_tiles * nqt;
+    const int KT = p.dpad / BK;
+    const int64_t n_mine = vb < total ? (total - vb + G - 1) / G : 0;
+    const int64_t n_stages = n_mine * KT;
+    if (n_stages == 0) return;
+    const unsigned char *Xb = static_cast<const unsigned char *>(p.X);
+    const unsigned char *Qb = reinterpret_cast<const unsigned char *>(p.Qs);
+
+    if (tau_in_lds)
+        for (int q = tid; q < p.Q; q += 256) tau_lds[q] = p.tau[q];
+
+    // ---- issue cursor: runs ahead of the multiply, also across tile boundaries ----
+    int64_t is_item = vb;
+    int is_kt = 0, is_buf = 0;
+    auto issue = [&]() {
+        const int64_t rt = is_item / nqt;
+        const int qt = (int)(is_item - rt * nqt);
+        const int64_t row0 = rt * p.tile_stride * BM;
+        const int q0 = qt * BN;
+        const uint32_t sb = lds0 + is_buf * STAGE;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int q = q0 + (wn * TN + j) * 32 + fr;
-            const bool qok = q < p.Q;
-            const u64 tkey = qok ? p.tau[q] : ~0ull;
-            const float tsc = qok ? key_score(tkey) : __builtin_inff();
+        for (int j = 0; j < NA; ++j) {
+            const int row = (wave * NA + j) * RPI + l_r;
+            int kc = is_kt * BK + ((l_c ^ swz<BK>(row & 15)) << 3);
+            kc = kc < p.d - 8 ? kc : p.d - 8;   // past-the-end chunks re-read valid data (query is 0 there)
+            int64_t g = row0 + row;
+            g = g < p.N ? g : p.N - 1;          // rows past N are scored but never admitted
+            dma_1kb(Xb + (g * p.ldx + kc) * 2, __builtin_amdgcn_readfirstlane(sb + (wave * NA + j) * 1024));
+        }
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                float m = acc[i][j][0];
+        for (int j = 0; j < NB; ++j) {
+            const int row = (wave * NB + j) * RPI + l_r;
+            const int kc = is_kt * BK + ((l_c ^ swz<BK>(row & 15)) << 3);
+            dma_1kb(Qb + ((int64_t)(q0 + row) * p.dpad + kc) * 2,
+                    __builtin_amdgcn_readfirstlane(sb + A_BYTES + (wave * NB + j) * 1024));
+        }
+        is_buf = is_buf + 1 == S ? 0 : is_buf + 1;
+        if (++is_kt == KT) {
+            is_kt = 0;
+            is_item += G;
+        }
+    };
+
+    int64_t issued = 0;
+    for (; issued < S - 1 && issued < n_stages; ++issued) issue();
+
+    // operand read offsets of this lane inside a stage (bytes)
+    int a_off[KS], b_off[KS];
 #pragma unroll
-                for (int v = 1; v < 16; ++v) m = fmaxf(m, acc[i][j][v]);
-                // tkey == 0 admits everything (its score bits decode to NaN: compare separately)
-                if (qok && (tkey == 0ull || m >= tsc)) {
-                    const int64_t rbase = row0 + (wm * TM + i) * 32 + (lane >> 5) * 4;
-                    uint32_t pass = 0;
+    for (int kk = 0; kk < KS; ++kk) {
+        const int c = kk * 2 + (lane >> 5);
+        const int sw = (c ^ swz<BK>(fr & 15)) << 4;
+        a_off[kk] = (wm * TM * 32 + fr) * ROWB + sw;
+        b_off[kk] = A_BYTES + (wn * TN * 32 + fr) * ROWB + sw;
+    }
+    uint4 fa[2][TM], fb[2][TN];
+    auto load_frags = [&](int slot, const unsigned char *sbase, int kk) {
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int64_t g = rbase + (v >> 2) * 8 + (v & 3);
-                        if (g < p.N && make_key(acc[i][j][v], (int32_t)g) >= tkey) pass |= 1u << v;
-                    }
-                    if (pass) {
-                        const uint32_t n = __popc(pass);
-                        uint32_t at = atomicAdd(p.cnt + q, n);
-                        u64 *dst = p.cand + (int64_t)q * p.cap;
+        for (int i = 0; i < TM; ++i)
+            fa[slot][i] = *reinterpret_cast<const uint4 *>(sbase + a_off[kk] + i * 32 * ROWB);
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            if (pass & (1u << v)) {
-                                const int64_t g = rbase + (v >> 2) * 8 + (v & 3);
-                                if (at < p.cap) dst[at] = make_key(acc[i][j][v], (int32_t)g);
-                                ++at;
-                            }
-                        }
+        for (int j = 0; j < TN; ++j)
+            fb[slot][j] = *reinterpret_cast<const uint4 *>(sbase + b_off[kk] + j * 32 * ROWB);
+    };
+
+    // stage 0 must be in LDS before the first operand read
+    wait_stages<LPS, S - 2>(issued - 1);
+    __syncthreads();
+    load_frags(0, smem, 0);
+
+    int buf = 0;
+    int64_t g = 0;
+    for (int64_t item = vb; item < total; item += G) {
+        f32x16 acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+        for (int kt = 0; kt < KT; ++kt, ++g) {
+            const unsigned char *sb = smem + buf * STAGE;
+            const int nbuf = buf + 1 == S ? 0 : buf + 1;
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) {
+                const int cur = kk & 1;
+                // operands of the next k-step (possibly the next tile's first) are fetched while
+                // this one multiplies
+                if (kk + 1 < KS)
+                    load_frags(cur ^ 1, sb, kk + 1);
+                else if (g + 1 < n_stages)
+                    load_frags(cur ^ 1, smem + nbuf * STAGE, 0);
+                if (kk == 0) {
+                    // Mid-stage rendezvous.  After it: stage g+1 is complete in LDS for every
+                    // wave, and every wave has finished reading stage g-1, whose slot is refilled.
+                    if (g + 1 < n_stages) wait_stages<LPS, S - 3>(issued - 2 - g);
+                    __syncthreads();
+                    if (issued < n_stages) {
+                        issue();
+                        ++issued;
                     }
                 }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) acc[i][j] = mfma32<F16>(fa[cur][i], fb[cur][j], acc[i][j]);
             }
+            buf = nbuf;
         }
+        const int64_t rt = item / nqt;
+        const int qt = (int)(item - rt * nqt);
+        select_epilogue<WM, WN, TM, TN>(p, tau_in_lds ? tau_lds : nullptr, acc, rt * p.tile_stride * BM, qt * BN,
+                                        wm, wn, lane);
+    }
+}
+
+template <bool F16, int WM, int WN, int TM, int TN, int BK, int S>
+hipError_t launch_dma_variant(const ScanParams &p, int n_cu, hipStream_t stream)
+{
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr size_t ring = (size_t)S * (BM + BN) * BK * 2;
+    constexpr size_t smem = ring + (size_t)TAU_LDS_MAX_Q * 8;
+    static_assert(smem <= 160 * 1024, "LDS budget");
+    auto kern = scan_dma_kernel<F16, WM, WN, TM, TN, BK, S>;
+    const int tau_in_lds = p.Q <= TAU_LDS_MAX_Q ? 1 : 0;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    const int nqt = (int)((p.Q + BN - 1) / BN);
+    const int64_t total = p.n_row_tiles * nqt;
+    if (total <= 0) return hipSuccess;
+    const int per_cu = smem * 2 <= 160 * 1024 ? 2 : 1;
+    int64_t grid = (int64_t)n_cu * per_cu;
+    if (total < grid) grid = total;
+    grid = (grid + 7) / 8 * 8;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), smem, stream, p, nqt, tau_in_lds);
+    return hipGetLastError();
+}
+
+template <bool F16>
+hipError_t launch_dma(const ScanParams &p, int n_cu, hipStream_t stream)
+{
+    const int bn = scan_bn_for(p.Q);
+    switch (bn) {
+        case 32: return launch_dma_variant<F16, 4, 1, 2, 1, 64, 3>(p, n_cu, stream);
+        case 64: return launch_dma_variant<F16, 4, 1, 2, 2, 64, 3>(p, n_cu, stream);
+        case 128: return launch_dma_variant<F16, 2, 2, 4, 2, 32, 4>(p, n_cu, stream);
+        default: return launch_dma_variant<F16, 2, 2, 4, 4, 32, 4>(p, n_cu, stream);
     }
 }
 
@@ -211,7 +454,7 @@ hipError_t launch_variant(const ScanParams &p, int n_cu, hipStream_t stream)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, LDA = SCAN_BK + 8;
     constexpr size_t smem = (size_t)2 * (BM + BN) * LDA * sizeof(uint16_t);
-    auto kern = scan_kernel<IN, WM, WN, TM, TN>;
+    auto kern = scan_staged_kernel<IN, WM, WN, TM, TN>;
     static bool attr_done = false;   // per instantiation
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -256,8 +499,8 @@ hipError_t launch_scan(const ScanParams &p, int n_cu, hipStream_t stream)
 {
     switch (p.in_dtype) {
         case DT_F32: return launch_in<DT_F32>(p, n_cu, stream);
-        case DT_F16: return launch_in<DT_F16>(p, n_cu, stream);
-        default: return launch_in<DT_BF16>(p, n_cu, stream);
+        case DT_F16: return launch_dma<true>(p, n_cu, stream);
+        default: return launch_dma<false>(p, n_cu, stream);
     }
 }
 
