@@ -240,12 +240,13 @@ __device__ __forceinline__ int swz(int r)
         return ((r >> 2) & 1) | ((((r >> 1) ^ (r >> 3)) & 1) << 1);
 }
 
-// 64 lanes x 16 bytes from per-lane global addresses to 1 KB of LDS starting at lds_base
-// (wave-uniform).  Written as inline asm so that the compiler does not track it: completion is
-// awaited by hand with s_waitcnt vmcnt(n) (loads complete in order).
-__device__ __forceinline__ void dma_1kb(const void *gptr, uint32_t lds_base)
+// 64 lanes x 16 bytes, from  base + per-lane byte offset,  to 1 KB of LDS starting at lds_base
+// (base and lds_base are wave-uniform).  Written as inline asm so that the compiler does not
+// track it: completion is awaited by hand with s_waitcnt vmcnt(n) (loads complete in order).
+__device__ __forceinline__ void dma_1kb(const unsigned char *base, uint32_t voff, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(base)
+                 : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
@@ -267,6 +268,12 @@ __device__ __forceinline__ void wait_stages(int64_t later)
         wait_vmcnt<0>();
 }
 
+#define RALM_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// The instruction stream of a stage is laid out by hand (one wave per SIMD: nothing else fills
+// the issue slots between MFMAs).  After each MFMA exactly one "side" instruction follows:
+// an LDS operand read for the next k-step, or one 1 KB global->LDS load of the strip that is
+// S-1 stages ahead.  sched_barrier keeps the compiler from regrouping them.
 template <bool F16, int WM, int WN, int TM, int TN, int BK, int S>
 __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const int nqt, const int tau_in_lds)
 {
@@ -278,6 +285,7 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
     constexpr int LPS = NA + NB;
     constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
     constexpr int KS = BK / 16;
+    constexpr int NM = TM * TN, NR = TM + TN;
     static_assert(WM * WN == 4 && BM == SCAN_BM && NB >= 1, "tile shape");
     static_assert(S >= 3 && S <= 4 && KS % 2 == 0, "ring depth / k-steps per stage");
     static_assert(LPS * (S - 2) < 64, "vmcnt range");
@@ -286,7 +294,8 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
     u64 *tau_lds = reinterpret_cast<u64 *>(smem + S * STAGE);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int fr = lane & 31;
     const int l_r = lane / CPR, l_c = lane % CPR;
@@ -300,44 +309,79 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
     if (n_stages == 0) return;
     const unsigned char *Xb = static_cast<const unsigned char *>(p.X);
     const unsigned char *Qb = reinterpret_cast<const unsigned char *>(p.Qs);
+    const uint32_t ldx2 = (uint32_t)p.ldx * 2u, dpad2 = (uint32_t)p.dpad * 2u;
 
     if (tau_in_lds)
         for (int q = tid; q < p.Q; q += 256) tau_lds[q] = p.tau[q];
 
     // ---- issue cursor: runs ahead of the multiply, also across tile boundaries ----
-    int64_t is_item = vb;
+    // per-lane constants of the loads: tile row and swizzled chunk offset of each wave load
+    uint32_t a_row[NA], a_chunk[NA], b_voff[NB];
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+        const int row = (wave * NA + j) * RPI + l_r;
+        a_row[j] = row;
+        a_chunk[j] = (uint32_t)((l_c ^ swz<BK>(row & 15)) << 4);
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int row = (wave * NB + j) * RPI + l_r;
+        b_voff[j] = (uint32_t)row * dpad2 + (uint32_t)((l_c ^ swz<BK>(row & 15)) << 4);
+    }
+    // (row tile, query tile) of an item advance by (G / nqt, G % nqt) from one item of this
+    // workgroup to its next: no division in the loop
+    const int64_t step_rt = G / nqt;
+    const int step_qt = (int)(G % nqt);
+    int64_t is_rt = vb / nqt;
+    int is_qt = (int)(vb % nqt);
     int is_kt = 0, is_buf = 0;
-    auto issue = [&]() {
-        const int64_t rt = is_item / nqt;
-        const int qt = (int)(is_item - rt * nqt);
-        const int64_t row0 = rt * p.tile_stride * BM;
-        const int q0 = qt * BN;
-        const uint32_t sb = lds0 + is_buf * STAGE;
-#pragma unroll
-        for (int j = 0; j < NA; ++j) {
-            const int row = (wave * NA + j) * RPI + l_r;
-            int kc = is_kt * BK + ((l_c ^ swz<BK>(row & 15)) << 3);
-            kc = kc < p.d - 8 ? kc : p.d - 8;   // past-the-end chunks re-read valid data (query is 0 there)
-            int64_t g = row0 + row;
-            g = g < p.N ? g : p.N - 1;          // rows past N are scored but never admitted
-            dma_1kb(Xb + (g * p.ldx + kc) * 2, __builtin_amdgcn_readfirstlane(sb + (wave * NA + j) * 1024));
+    // wave-uniform state of the stage being issued
+    const unsigned char *is_abase = nullptr, *is_bbase = nullptr;
+    uint32_t is_rowmax = 0, is_kmax = 0, is_lds = 0;
+    auto issue_begin = [&]() {
+        if (is_kt == 0) {
+            const int64_t row0 = is_rt * p.tile_stride * BM;
+            is_abase = Xb + row0 * p.ldx * 2;
+            is_bbase = Qb + (int64_t)is_qt * BN * p.dpad * 2;
+            const int64_t left = p.N - 1 - row0;            // rows past N re-read row N-1
+            is_rowmax = (uint32_t)(left < BM - 1 ? left : BM - 1);
         }
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            const int row = (wave * NB + j) * RPI + l_r;
-            const int kc = is_kt * BK + ((l_c ^ swz<BK>(row & 15)) << 3);
-            dma_1kb(Qb + ((int64_t)(q0 + row) * p.dpad + kc) * 2,
-                    __builtin_amdgcn_readfirstlane(sb + A_BYTES + (wave * NB + j) * 1024));
+        const int kleft = (p.d - 8 - is_kt * BK) * 2;        // chunks past d re-read the last valid one
+        is_kmax = (uint32_t)(kleft < ROWB - 16 ? kleft : ROWB - 16);
+        is_lds = lds0 + is_buf * STAGE + wave * (NA * 1024);
+    };
+    auto issue_part = [&](int idx) {
+        if (idx < NA) {
+            const uint32_t r = a_row[idx] < is_rowmax ? a_row[idx] : is_rowmax;
+            const uint32_t c = a_chunk[idx] < is_kmax ? a_chunk[idx] : is_kmax;
+            dma_1kb(is_abase, r * ldx2 + c, is_lds + idx * 1024);
+        } else {
+            const int j = idx - NA;
+            dma_1kb(is_bbase, b_voff[j], lds0 + is_buf * STAGE + A_BYTES + (wave * NB + j) * 1024);
         }
+    };
+    auto issue_end = [&]() {
+        is_abase += ROWB;
+        is_bbase += ROWB;
         is_buf = is_buf + 1 == S ? 0 : is_buf + 1;
         if (++is_kt == KT) {
             is_kt = 0;
-            is_item += G;
+            is_rt += step_rt;
+            is_qt += step_qt;
+            if (is_qt >= nqt) {
+                is_qt -= nqt;
+                ++is_rt;
+            }
         }
     };
 
     int64_t issued = 0;
-    for (; issued < S - 1 && issued < n_stages; ++issued) issue();
+    for (; issued < S - 1 && issued < n_stages; ++issued) {
+        issue_begin();
+#pragma unroll
+        for (int idx = 0; idx < LPS; ++idx) issue_part(idx);
+        issue_end();
+    }
 
     // operand read offsets of this lane inside a stage (bytes)
     int a_off[KS], b_off[KS];
@@ -349,23 +393,24 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
         b_off[kk] = A_BYTES + (wn * TN * 32 + fr) * ROWB + sw;
     }
     uint4 fa[2][TM], fb[2][TN];
-    auto load_frags = [&](int slot, const unsigned char *sbase, int kk) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-            fa[slot][i] = *reinterpret_cast<const uint4 *>(sbase + a_off[kk] + i * 32 * ROWB);
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-            fb[slot][j] = *reinterpret_cast<const uint4 *>(sbase + b_off[kk] + j * 32 * ROWB);
+    auto read_frag = [&](int slot, const unsigned char *sbase, int kk, int idx) {
+        if (idx < TM)
+            fa[slot][idx] = *reinterpret_cast<const uint4 *>(sbase + a_off[kk] + idx * 32 * ROWB);
+        else
+            fb[slot][idx - TM] = *reinterpret_cast<const uint4 *>(sbase + b_off[kk] + (idx - TM) * 32 * ROWB);
     };
 
     // stage 0 must be in LDS before the first operand read
     wait_stages<LPS, S - 2>(issued - 1);
     __syncthreads();
-    load_frags(0, smem, 0);
+#pragma unroll
+    for (int idx = 0; idx < NR; ++idx) read_frag(0, smem, 0, idx);
 
     int buf = 0;
     int64_t g = 0;
-    for (int64_t item = vb; item < total; item += G) {
+    int64_t cur_rt = vb / nqt;
+    int cur_qt = (int)(vb % nqt);
+    for (int64_t it = 0; it < n_mine; ++it) {
         f32x16 acc[TM][TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -377,36 +422,53 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
         for (int kt = 0; kt < KT; ++kt, ++g) {
             const unsigned char *sb = smem + buf * STAGE;
             const int nbuf = buf + 1 == S ? 0 : buf + 1;
+            const bool more = g + 1 < n_stages;
+            const bool do_issue = issued < n_stages;
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk) {
                 const int cur = kk & 1;
-                // operands of the next k-step (possibly the next tile's first) are fetched while
-                // this one multiplies
-                if (kk + 1 < KS)
-                    load_frags(cur ^ 1, sb, kk + 1);
-                else if (g + 1 < n_stages)
-                    load_frags(cur ^ 1, smem + nbuf * STAGE, 0);
-                if (kk == 0) {
-                    // Mid-stage rendezvous.  After it: stage g+1 is complete in LDS for every
-                    // wave, and every wave has finished reading stage g-1, whose slot is refilled.
-                    if (g + 1 < n_stages) wait_stages<LPS, S - 3>(issued - 2 - g);
-                    __syncthreads();
-                    if (issued < n_stages) {
-                        issue();
-                        ++issued;
+                const bool last_kk = kk + 1 == KS;
+                const unsigned char *nsb = last_kk ? smem + nbuf * STAGE : sb;
+                const int nkk = last_kk ? 0 : kk + 1;
+                const bool do_read = !last_kk || more;
+                // side instructions of this k-step: the global->LDS loads (k-step 1 only), then
+                // the operand reads of the next k-step
+                constexpr int ND_MAX = LPS;
+                const int nd = kk == 1 ? ND_MAX : 0;
+                if (kk == 1 && do_issue) issue_begin();
+                RALM_SCHED_FENCE();
+#pragma unroll
+                for (int m = 0; m < (NM > ND_MAX + NR ? NM : ND_MAX + NR); ++m) {
+                    if (m < NM) acc[m / TN][m % TN] = mfma32<F16>(fa[cur][m / TN], fb[cur][m % TN], acc[m / TN][m % TN]);
+                    if (m < nd) {
+                        if (do_issue) issue_part(m);
+                    } else if (m - nd < NR) {
+                        if (do_read) read_frag(cur ^ 1, nsb, nkk, m - nd);
                     }
+                    RALM_SCHED_FENCE();
                 }
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) acc[i][j] = mfma32<F16>(fa[cur][i], fb[cur][j], acc[i][j]);
+                if (kk == 1 && do_issue) {
+                    issue_end();
+                    ++issued;
+                }
+                if (kk == 0) {
+                    // Rendezvous.  After it: stage g+1 is complete in LDS for every wave, and
+                    // every wave has finished reading stage g-1, whose slot is refilled next.
+                    if (more) wait_stages<LPS, S - 3>(issued - 2 - g);
+                    __syncthreads();
+                }
+                RALM_SCHED_FENCE();
             }
             buf = nbuf;
         }
-        const int64_t rt = item / nqt;
-        const int qt = (int)(item - rt * nqt);
-        select_epilogue<WM, WN, TM, TN>(p, tau_in_lds ? tau_lds : nullptr, acc, rt * p.tile_stride * BM, qt * BN,
-                                        wm, wn, lane);
+        select_epilogue<WM, WN, TM, TN>(p, tau_in_lds ? tau_lds : nullptr, acc, cur_rt * p.tile_stride * BM,
+                                        cur_qt * BN, wm, wn, lane);
+        cur_rt += step_rt;
+        cur_qt += step_qt;
+        if (cur_qt >= nqt) {
+            cur_qt -= nqt;
+            ++cur_rt;
+        }
     }
 }
 
