@@ -14,7 +14,7 @@ from typing import Optional, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libralm.so")
+LIB_PATH = os.environ.get("RALM_LIB_PATH") or os.path.join(_HERE, "libralm.so")
 
 RALM_F32, RALM_BF16, RALM_F16 = 0, 1, 2
 _DT = {torch.float32: RALM_F32, torch.bfloat16: RALM_BF16, torch.float16: RALM_F16}

@@ -16,7 +16,9 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libralm.so")
 SOURCES = ["ralm_api.hip", "scan_kernels.hip", "select_kernels.hip", "cache_verify_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # the scan kernel's stage bodies are fully unrolled by design (static register indices)
+         "-mllvm", "-pragma-unroll-threshold=1000000"]
 
 
 def _compile(src: str) -> str:

@@ -215,6 +215,7 @@ ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_da
         sp.Qs = qs; sp.dpad = pl.dpad; sp.Q = (int32_t)Q;
         sp.tau = tau; sp.cand = cand; sp.cnt = cnt; sp.cap = pl.cap;
         sp.tile_stride = pl.stride[s];
+        sp.park_pushes = s > 0 ? 1 : 0;
         sp.n_row_tiles = (tiles + pl.stride[s] - 1) / pl.stride[s];
         const bool prof = last && g_prof_on && g_prof_n < MAX_PROF;
         if (prof) {

@@ -27,6 +27,7 @@ struct ScanParams {
     uint32_t cap;
     int64_t n_row_tiles;    // tiles visited in this stage
     int64_t tile_stride;    // visited tile t covers rows [t*tile_stride*BM, +BM)
+    int32_t park_pushes;    // 1: thresholds are selective, collect admitted scores in LDS first
 };
 
 // query tile width chosen for Q

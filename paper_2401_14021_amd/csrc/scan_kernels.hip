@@ -26,6 +26,8 @@
 // run at the same time on one XCD (workgroup b lands on XCD b % 8) hold consecutive items:
 // all query tiles of a row tile, then the next row tile.  The row tile's second to last
 // readers therefore hit that XCD's L2.
+#include <type_traits>
+
 #include "ralm_common.h"
 #include "ralm_kernels.h"
 
@@ -82,21 +84,26 @@ __device__ __forceinline__ f32x16 mfma32(const uint4 &a, const uint4 &b, const f
                                                        __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-// Selection epilogue shared by both kernels: one query per lane and MFMA block column.
-// acc[i][j][v] is the score of datastore row  row0 + (wm*TM + i)*32 + (v/4)*8 + (lane/32)*4 + v%4
-// against query  q0 + (wn*TN + j)*32 + lane%32.  A score is appended to its query's candidate
-// list iff its ranking key is >= the query's admission key.
+#define RALM_LDS __attribute__((address_space(3)))
+
+// acc[i][j][v] of a wave is the score of datastore row
+//     row0 + (wm*TM + i)*32 + (v/4)*8 + (lane/32)*4 + v%4
+// against query  q0 + (wn*TN + j)*32 + lane%32.  A score is admitted (appended to its query's
+// candidate list) iff its ranking key is >= the query's admission key.
+
+// Direct epilogue (staged kernel): admitted scores go straight to the global candidate lists,
+// one atomic per lane and 32x32 block.
 template <int WM, int WN, int TM, int TN>
-__device__ __forceinline__ void select_epilogue(const ScanParams &p, const u64 *tau_lds,
-                                                f32x16 (&acc)[TM][TN], int64_t row0, int q0, int wm,
-                                                int wn, int lane)
+__device__ __forceinline__ void select_epilogue_direct(const ScanParams &p, f32x16 (&acc)[TM][TN], int32_t row0,
+                                                       int q0, int wm, int wn, int lane)
 {
     const int fr = lane & 31;
+    const int32_t n_rows = (int32_t)p.N;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int q = q0 + (wn * TN + j) * 32 + fr;
         const bool qok = q < p.Q;
-        const u64 tkey = qok ? (tau_lds ? tau_lds[q] : p.tau[q]) : ~0ull;
+        const u64 tkey = qok ? p.tau[q] : ~0ull;
         const float tsc = qok ? key_score(tkey) : __builtin_inff();
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -105,28 +112,123 @@ __device__ __forceinline__ void select_epilogue(const ScanParams &p, const u64 *
             for (int v = 1; v < 16; ++v) m = fmaxf(m, acc[i][j][v]);
             // tkey == 0 admits everything (its score bits decode to NaN: compare separately)
             if (qok && (tkey == 0ull || m >= tsc)) {
-                const int64_t rbase = row0 + (wm * TM + i) * 32 + (lane >> 5) * 4;
+                const int32_t rbase = row0 + (wm * TM + i) * 32 + (lane >> 5) * 4;
                 uint32_t pass = 0;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int64_t g = rbase + (v >> 2) * 8 + (v & 3);
-                    if (g < p.N && make_key(acc[i][j][v], (int32_t)g) >= tkey) pass |= 1u << v;
+                    const int32_t g = rbase + (v >> 2) * 8 + (v & 3);
+                    if (g < n_rows && make_key(acc[i][j][v], g) >= tkey) pass |= 1u << v;
                 }
                 if (pass) {
-                    const uint32_t n = __popc(pass);
-                    uint32_t at = atomicAdd(p.cnt + q, n);
+                    uint32_t at = atomicAdd(p.cnt + q, (uint32_t)__popc(pass));
                     u64 *dst = p.cand + (int64_t)q * p.cap;
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         if (pass & (1u << v)) {
-                            const int64_t g = rbase + (v >> 2) * 8 + (v & 3);
-                            if (at < p.cap) dst[at] = make_key(acc[i][j][v], (int32_t)g);
+                            if (at < p.cap) dst[at] = make_key(acc[i][j][v], rbase + (v >> 2) * 8 + (v & 3));
                             ++at;
                         }
                     }
                 }
             }
         }
+    }
+}
+
+#ifdef RALM_SCAN_TIMING
+// debug builds only: per-wave cycle totals {whole kernel, load waits, barriers, tile ends, stages}
+__device__ unsigned long long g_scan_timing[8];
+#define RALM_T0(var) const unsigned long long var = __builtin_amdgcn_s_memtime()
+#define RALM_TADD(acc, var) acc += __builtin_amdgcn_s_memtime() - var
+#else
+#define RALM_T0(var)
+#define RALM_TADD(acc, var)
+#endif
+
+// Parked epilogue (pipelined kernel).  Admitted scores are first parked in a small LDS list
+// (an LDS atomic is ~20x quicker than a global atomic round trip, which a lone wave per SIMD
+// cannot hide) and moved to the global lists in batches by flush_parked().  An entry that
+// finds the list full goes to its global list directly, so nothing is ever lost.
+struct PushList {
+    RALM_LDS uint32_t *count;   // entries appended so far (may exceed cap; the excess went to global)
+    RALM_LDS u64 *keys;         // [cap]
+    RALM_LDS uint32_t *qs;      // [cap]
+    uint32_t cap;
+};
+
+__device__ __forceinline__ void push_global(const ScanParams &p, int q, u64 key)
+{
+    const uint32_t at = atomicAdd(p.cnt + q, 1u);
+    if (at < p.cap) p.cand[(int64_t)q * p.cap + at] = key;
+}
+
+// all 256 threads, after a barrier that follows the last append: moves the first n parked
+// entries to the global lists and empties the LDS list
+__device__ __forceinline__ void flush_parked(const ScanParams &p, const PushList pl, uint32_t n)
+{
+    for (uint32_t e = threadIdx.x; e < n; e += 256) push_global(p, (int)pl.qs[e], pl.keys[e]);
+    __syncthreads();
+    if (threadIdx.x == 0) *pl.count = 0;
+    __syncthreads();
+}
+
+// one 32x32 block of one wave: out[v] for row rbase + (v/4)*8 + v%4 and query q.
+//
+// The common case (no lane of the wave holds an admitted score) must be a handful of
+// instructions: the pipelined kernel's last stage contains 16 copies of this function, and
+// anything bulky here pushes that stage out of the instruction cache.  So the rare case does
+// not unroll over the 16 values: a lane that may hold an admitted score writes its 16 values
+// to a 64-byte LDS slot and walks them in a rolled loop (registers cannot be indexed
+// dynamically, LDS can).  Slots are handed out by rank among the candidate lanes, 8 per round.
+constexpr int SLOW_SLOTS = 8;   // 64-byte slots per wave
+__device__ __forceinline__ void select_block_parked(const ScanParams &p, const PushList pl,
+                                                    RALM_LDS float *wave_slots, const f32x16 &out,
+                                                    int32_t rbase, int32_t n_rows, int q, bool qok, u64 tkey,
+                                                    float tsc)
+{
+    float m = out[0];
+#pragma unroll
+    for (int v = 1; v < 16; ++v) m = fmaxf(m, out[v]);
+    // tkey == 0 admits everything (its score bits decode to NaN: compare separately)
+    bool cand = qok && (tkey == 0ull || m >= tsc);
+    unsigned long long mask = __builtin_amdgcn_ballot_w64(cand);
+    while (mask) {   // wave-uniform
+        const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                        __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+        const bool mine = cand && rank < (uint32_t)SLOW_SLOTS;
+        if (mine) {
+            RALM_LDS float *slot = wave_slots + rank * 16;
+            typedef float f32x4v __attribute__((ext_vector_type(4)));
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                f32x4v t = {out[c * 4], out[c * 4 + 1], out[c * 4 + 2], out[c * 4 + 3]};
+                *(RALM_LDS f32x4v *)(slot + c * 4) = t;
+            }
+            // which of the 16 values reach the threshold score (cheap, in registers) ...
+            uint32_t pm = 0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) pm |= (tkey == 0ull || out[v] >= tsc) ? (1u << v) : 0u;
+            // ... and only those are fetched back and tested exactly (usually one or two)
+#pragma unroll 1
+            while (pm) {
+                const int v = __builtin_ctz(pm);
+                pm &= pm - 1;
+                const int32_t g = rbase + (v >> 2) * 8 + (v & 3);
+                const u64 key = make_key(slot[v], g);
+                if (g < n_rows && key >= tkey) {
+                    const uint32_t at =
+                        __hip_atomic_fetch_add(pl.count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    if (at < pl.cap) {
+                        pl.keys[at] = key;
+                        pl.qs[at] = (uint32_t)q;
+                    } else {
+                        push_global(p, q, key);
+                    }
+                }
+            }
+        }
+        cand = cand && !mine;
+        mask = __builtin_amdgcn_ballot_w64(cand);
     }
 }
 
@@ -222,7 +324,7 @@ __global__ __launch_bounds__(256) void scan_staged_kernel(const ScanParams p, co
             __syncthreads();
         }
 
-        select_epilogue<WM, WN, TM, TN>(p, nullptr, acc, row0, q0, wm, wn, lane);
+        select_epilogue_direct<WM, WN, TM, TN>(p, acc, (int32_t)row0, q0, wm, wn, lane);
     }
 }
 
@@ -254,26 +356,17 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-constexpr int TAU_LDS_MAX_Q = 3072;   // admission keys of up to this many queries are kept in LDS
-
-// wait until at most `later` of this wave's stage loads are still in flight
-template <int LPS, int MAXL>
-__device__ __forceinline__ void wait_stages(int64_t later)
-{
-    if (later >= MAXL)
-        wait_vmcnt<LPS * MAXL>();
-    else if (MAXL > 1 && later == 1)
-        wait_vmcnt<LPS>();
-    else
-        wait_vmcnt<0>();
-}
+constexpr int TAU_LDS_MAX_Q = 2560;   // admission keys of up to this many queries are kept in LDS
+constexpr int PARK_CAP = 832;         // parked admitted scores per workgroup (12 bytes each)
 
 #define RALM_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 // The instruction stream of a stage is laid out by hand (one wave per SIMD: nothing else fills
-// the issue slots between MFMAs).  After each MFMA exactly one "side" instruction follows:
-// an LDS operand read for the next k-step, or one 1 KB global->LDS load of the strip that is
-// S-1 stages ahead.  sched_barrier keeps the compiler from regrouping them.
+// the issue slots between MFMAs).  After each MFMA exactly one "side" instruction follows: an
+// LDS operand read for the next k-step, or one 1 KB global->LDS load of the strip that is S-1
+// stages ahead.  sched_barrier keeps the compiler from regrouping them.  In a tile's last
+// k-step the MFMA results are written to VGPRs and each block's selection test runs two MFMAs
+// behind its last multiply, so the selection costs no separate pass over the accumulators.
 template <bool F16, int WM, int WN, int TM, int TN, int BK, int S>
 __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const int nqt, const int tau_in_lds)
 {
@@ -286,13 +379,20 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
     constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
     constexpr int KS = BK / 16;
     constexpr int NM = TM * TN, NR = TM + TN;
+    constexpr int LAG = NM > 2 ? 2 : NM - 1;     // selection runs this many MFMAs behind
     static_assert(WM * WN == 4 && BM == SCAN_BM && NB >= 1, "tile shape");
     static_assert(S >= 3 && S <= 4 && KS % 2 == 0, "ring depth / k-steps per stage");
     static_assert(LPS * (S - 2) < 64, "vmcnt range");
 
     extern __shared__ __align__(16) unsigned char smem[];
-    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
-    u64 *tau_lds = reinterpret_cast<u64 *>(smem + S * STAGE);
+    const uint32_t lds0 = (uint32_t)(size_t)(RALM_LDS unsigned char *)smem;
+    RALM_LDS u64 *tau_lds = (RALM_LDS u64 *)(smem + S * STAGE);
+    PushList pl;
+    pl.keys = tau_lds + TAU_LDS_MAX_Q;
+    pl.qs = (RALM_LDS uint32_t *)(pl.keys + PARK_CAP);
+    pl.count = pl.qs + PARK_CAP;
+    pl.cap = PARK_CAP;
+    RALM_LDS float *wave_slots = (RALM_LDS float *)(pl.count + 4) + (threadIdx.x >> 6) * (SLOW_SLOTS * 16);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -305,16 +405,21 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
     const int64_t total = p.n_row_tiles * nqt;
     const int KT = p.dpad / BK;
     const int64_t n_mine = vb < total ? (total - vb + G - 1) / G : 0;
-    const int64_t n_stages = n_mine * KT;
-    if (n_stages == 0) return;
+    if (n_mine == 0) return;
     const unsigned char *Xb = static_cast<const unsigned char *>(p.X);
     const unsigned char *Qb = reinterpret_cast<const unsigned char *>(p.Qs);
     const uint32_t ldx2 = (uint32_t)p.ldx * 2u, dpad2 = (uint32_t)p.dpad * 2u;
+    const int32_t n_rows = (int32_t)p.N;
 
+    if (tid == 0) *pl.count = 0;
     if (tau_in_lds)
         for (int q = tid; q < p.Q; q += 256) tau_lds[q] = p.tau[q];
+#ifdef RALM_SCAN_TIMING
+    unsigned long long t_wait = 0, t_bar = 0, t_epi = 0;
+    RALM_T0(t_begin);
+#endif
 
-    // ---- issue cursor: runs ahead of the multiply, also across tile boundaries ----
+    // ---- issue cursor: runs S-1 stages ahead of the multiply, also across tile boundaries ----
     // per-lane constants of the loads: tile row and swizzled chunk offset of each wave load
     uint32_t a_row[NA], a_chunk[NA], b_voff[NB];
 #pragma unroll
@@ -338,9 +443,12 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
     // wave-uniform state of the stage being issued
     const unsigned char *is_abase = nullptr, *is_bbase = nullptr;
     uint32_t is_rowmax = 0, is_kmax = 0, is_lds = 0;
-    auto issue_begin = [&]() {
+    auto issue_begin = [&]() __attribute__((always_inline)) {
         if (is_kt == 0) {
-            const int64_t row0 = is_rt * p.tile_stride * BM;
+            // The cursor is never stopped: past this workgroup's last tile it fetches (valid)
+            // strips that nobody multiplies, so the steady-state loop has no conditionals.
+            const int64_t rt = is_rt < p.n_row_tiles ? is_rt : 0;
+            const int64_t row0 = rt * p.tile_stride * BM;
             is_abase = Xb + row0 * p.ldx * 2;
             is_bbase = Qb + (int64_t)is_qt * BN * p.dpad * 2;
             const int64_t left = p.N - 1 - row0;            // rows past N re-read row N-1
@@ -350,7 +458,7 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
         is_kmax = (uint32_t)(kleft < ROWB - 16 ? kleft : ROWB - 16);
         is_lds = lds0 + is_buf * STAGE + wave * (NA * 1024);
     };
-    auto issue_part = [&](int idx) {
+    auto issue_part = [&](int idx) __attribute__((always_inline)) {
         if (idx < NA) {
             const uint32_t r = a_row[idx] < is_rowmax ? a_row[idx] : is_rowmax;
             const uint32_t c = a_chunk[idx] < is_kmax ? a_chunk[idx] : is_kmax;
@@ -360,7 +468,7 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
             dma_1kb(is_bbase, b_voff[j], lds0 + is_buf * STAGE + A_BYTES + (wave * NB + j) * 1024);
         }
     };
-    auto issue_end = [&]() {
+    auto issue_end = [&]() __attribute__((always_inline)) {
         is_abase += ROWB;
         is_bbase += ROWB;
         is_buf = is_buf + 1 == S ? 0 : is_buf + 1;
@@ -375,8 +483,7 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
         }
     };
 
-    int64_t issued = 0;
-    for (; issued < S - 1 && issued < n_stages; ++issued) {
+    for (int st = 0; st < S - 1; ++st) {
         issue_begin();
 #pragma unroll
         for (int idx = 0; idx < LPS; ++idx) issue_part(idx);
@@ -393,7 +500,7 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
         b_off[kk] = A_BYTES + (wn * TN * 32 + fr) * ROWB + sw;
     }
     uint4 fa[2][TM], fb[2][TN];
-    auto read_frag = [&](int slot, const unsigned char *sbase, int kk, int idx) {
+    auto read_frag = [&](int slot, const unsigned char *sbase, int kk, int idx) __attribute__((always_inline)) {
         if (idx < TM)
             fa[slot][idx] = *reinterpret_cast<const uint4 *>(sbase + a_off[kk] + idx * 32 * ROWB);
         else
@@ -401,68 +508,127 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
     };
 
     // stage 0 must be in LDS before the first operand read
-    wait_stages<LPS, S - 2>(issued - 1);
+    wait_vmcnt<LPS *(S - 2)>();
     __syncthreads();
 #pragma unroll
     for (int idx = 0; idx < NR; ++idx) read_frag(0, smem, 0, idx);
 
+    uint32_t parked = 0;   // entries in the LDS list (uniform; maintained at tile ends)
     int buf = 0;
-    int64_t g = 0;
     int64_t cur_rt = vb / nqt;
     int cur_qt = (int)(vb % nqt);
     for (int64_t it = 0; it < n_mine; ++it) {
         f32x16 acc[TM][TN];
+        const int32_t row0 = (int32_t)(cur_rt * p.tile_stride * BM);
+        const int q0 = cur_qt * BN;
+        // admission keys of this lane's TN queries
+        u64 tkey[TN];
+        float tsc[TN];
+        bool qok[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        for (int j = 0; j < TN; ++j) {
+            const int q = q0 + (wn * TN + j) * 32 + fr;
+            qok[j] = q < p.Q;
+            tkey[j] = qok[j] ? (tau_in_lds ? tau_lds[q] : p.tau[q]) : ~0ull;
+            tsc[j] = qok[j] ? key_score(tkey[j]) : __builtin_inff();
+        }
 
-        for (int kt = 0; kt < KT; ++kt, ++g) {
+        // one stage; FIRST: accumulators start from zero; LAST: selection fused into the last k-step
+        auto stage = [&](auto first_tag, auto last_tag) __attribute__((always_inline)) {
+            constexpr bool FIRST = decltype(first_tag)::value, LAST = decltype(last_tag)::value;
             const unsigned char *sb = smem + buf * STAGE;
             const int nbuf = buf + 1 == S ? 0 : buf + 1;
-            const bool more = g + 1 < n_stages;
-            const bool do_issue = issued < n_stages;
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk) {
                 const int cur = kk & 1;
                 const bool last_kk = kk + 1 == KS;
                 const unsigned char *nsb = last_kk ? smem + nbuf * STAGE : sb;
                 const int nkk = last_kk ? 0 : kk + 1;
-                const bool do_read = !last_kk || more;
                 // side instructions of this k-step: the global->LDS loads (k-step 1 only), then
-                // the operand reads of the next k-step
-                constexpr int ND_MAX = LPS;
-                const int nd = kk == 1 ? ND_MAX : 0;
-                if (kk == 1 && do_issue) issue_begin();
+                // the operand reads of the next k-step (for the last k-step: of the next stage)
+                const int nd = kk == 1 ? LPS : 0;
+                f32x16 outs[LAG + 1];
+                if (kk == 1) issue_begin();
                 RALM_SCHED_FENCE();
 #pragma unroll
-                for (int m = 0; m < (NM > ND_MAX + NR ? NM : ND_MAX + NR); ++m) {
-                    if (m < NM) acc[m / TN][m % TN] = mfma32<F16>(fa[cur][m / TN], fb[cur][m % TN], acc[m / TN][m % TN]);
-                    if (m < nd) {
-                        if (do_issue) issue_part(m);
-                    } else if (m - nd < NR) {
-                        if (do_read) read_frag(cur ^ 1, nsb, nkk, m - nd);
+                for (int m = 0; m < (NM > LPS + NR ? NM : LPS + NR) + LAG; ++m) {
+                    if (m < NM) {
+                        const int i = m / TN, j = m % TN;
+                        if constexpr (FIRST) {
+                            if (kk == 0) {
+                                f32x16 zero;
+#pragma unroll
+                                for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+                                acc[i][j] = mfma32<F16>(fa[cur][i], fb[cur][j], zero);
+                            } else if (LAST && last_kk) {
+                                outs[m % (LAG + 1)] = mfma32<F16>(fa[cur][i], fb[cur][j], acc[i][j]);
+                            } else {
+                                acc[i][j] = mfma32<F16>(fa[cur][i], fb[cur][j], acc[i][j]);
+                            }
+                        } else {
+                            if (LAST && last_kk)
+                                outs[m % (LAG + 1)] = mfma32<F16>(fa[cur][i], fb[cur][j], acc[i][j]);
+                            else
+                                acc[i][j] = mfma32<F16>(fa[cur][i], fb[cur][j], acc[i][j]);
+                        }
+                    }
+                    if (m < nd)
+                        issue_part(m);
+                    else if (m - nd < NR)
+                        read_frag(cur ^ 1, nsb, nkk, m - nd);
+                    if (LAST && last_kk && m >= LAG && m - LAG < NM) {
+                        const int mm = m - LAG, i = mm / TN, j = mm % TN;
+                        select_block_parked(p, pl, wave_slots, outs[mm % (LAG + 1)],
+                                            row0 + (wm * TM + i) * 32 + (lane >> 5) * 4, n_rows,
+                                            q0 + (wn * TN + j) * 32 + fr, qok[j], tkey[j], tsc[j]);
                     }
                     RALM_SCHED_FENCE();
                 }
-                if (kk == 1 && do_issue) {
-                    issue_end();
-                    ++issued;
-                }
+                if (kk == 1) issue_end();
                 if (kk == 0) {
-                    // Rendezvous.  After it: stage g+1 is complete in LDS for every wave, and
-                    // every wave has finished reading stage g-1, whose slot is refilled next.
-                    if (more) wait_stages<LPS, S - 3>(issued - 2 - g);
-                    __syncthreads();
+                    // Rendezvous.  After it: the next stage is complete in LDS for every wave, and
+                    // every wave has finished reading the previous stage, whose slot is refilled
+                    // by the loads issued in k-step 1.  No LDS data is written by ds instructions
+                    // that another wave reads without a later full barrier, so no LDS fence is
+                    // needed here; the asm statements keep the compiler from moving memory
+                    // operations across the barrier.
+                    RALM_T0(tw);
+                    wait_vmcnt<LPS *(S - 3)>();
+                    RALM_TADD(t_wait, tw);
+                    RALM_T0(tb);
+                    asm volatile("" ::: "memory");
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                    RALM_TADD(t_bar, tb);
                 }
                 RALM_SCHED_FENCE();
             }
             buf = nbuf;
+        };
+
+        if (KT == 1) {
+            stage(std::true_type{}, std::true_type{});
+        } else {
+            stage(std::true_type{}, std::false_type{});
+            for (int kt = 1; kt + 1 < KT; ++kt) stage(std::false_type{}, std::false_type{});
+            stage(std::false_type{}, std::true_type{});
         }
-        select_epilogue<WM, WN, TM, TN>(p, tau_in_lds ? tau_lds : nullptr, acc, cur_rt * p.tile_stride * BM,
-                                        cur_qt * BN, wm, wn, lane);
+
+        // tile end: every few tiles the parked entries move to the global lists
+        RALM_T0(te);
+        const bool last_tile = it + 1 == n_mine;
+        if ((it & 3) == 3 || last_tile) {
+            __syncthreads();
+            const uint32_t n = *pl.count;   // uniform: read after the barrier
+            const uint32_t held = n < pl.cap ? n : pl.cap;
+            if (held >= pl.cap / 4 || (last_tile && held > 0)) {
+                flush_parked(p, pl, held);
+                parked = 0;
+            } else {
+                parked = held;
+            }
+        }
+        RALM_TADD(t_epi, te);
         cur_rt += step_rt;
         cur_qt += step_qt;
         if (cur_qt >= nqt) {
@@ -470,6 +636,17 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
             ++cur_rt;
         }
     }
+    (void)parked;
+    wait_vmcnt<0>();   // the run-ahead loads must land before this workgroup's LDS is released
+#ifdef RALM_SCAN_TIMING
+    if (lane == 0) {
+        atomicAdd(&g_scan_timing[0], __builtin_amdgcn_s_memtime() - t_begin);
+        atomicAdd(&g_scan_timing[1], t_wait);
+        atomicAdd(&g_scan_timing[2], t_bar);
+        atomicAdd(&g_scan_timing[3], t_epi);
+        atomicAdd(&g_scan_timing[4], (unsigned long long)(n_mine * KT));
+    }
+#endif
 }
 
 template <bool F16, int WM, int WN, int TM, int TN, int BK, int S>
@@ -477,7 +654,7 @@ hipError_t launch_dma_variant(const ScanParams &p, int n_cu, hipStream_t stream)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t ring = (size_t)S * (BM + BN) * BK * 2;
-    constexpr size_t smem = ring + (size_t)TAU_LDS_MAX_Q * 8;
+    constexpr size_t smem = ring + (size_t)TAU_LDS_MAX_Q * 8 + (size_t)PARK_CAP * 12 + 16 + 4 * SLOW_SLOTS * 64;
     static_assert(smem <= 160 * 1024, "LDS budget");
     auto kern = scan_dma_kernel<F16, WM, WN, TM, TN, BK, S>;
     const int tau_in_lds = p.Q <= TAU_LDS_MAX_Q ? 1 : 0;
@@ -557,13 +734,27 @@ int scan_bn_for(int64_t Q)
     return 256;
 }
 
+#ifdef RALM_SCAN_TIMING
+extern "C" int ralm_debug_scan_timing(unsigned long long *out8, int reset)
+{
+    hipDeviceSynchronize();
+    if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_scan_timing), 64) != hipSuccess) return 1;
+    if (reset) {
+        unsigned long long z[8] = {0};
+        if (hipMemcpyToSymbol(HIP_SYMBOL(g_scan_timing), z, 64) != hipSuccess) return 1;
+    }
+    return 0;
+}
+#endif
+
 hipError_t launch_scan(const ScanParams &p, int n_cu, hipStream_t stream)
 {
-    switch (p.in_dtype) {
-        case DT_F32: return launch_in<DT_F32>(p, n_cu, stream);
-        case DT_F16: return launch_dma<true>(p, n_cu, stream);
-        default: return launch_dma<false>(p, n_cu, stream);
-    }
+    // Launches whose thresholds admit everything (the first, tiny stage of the ladder) append
+    // nearly every score: they take the staged kernel, whose epilogue writes to the global lists
+    // with one atomic per lane and block.  fp32 rows always do (they are rounded on the way in).
+    if (p.in_dtype == DT_F32) return launch_in<DT_F32>(p, n_cu, stream);
+    if (!p.park_pushes) return p.in_dtype == DT_F16 ? launch_in<DT_F16>(p, n_cu, stream) : launch_in<DT_BF16>(p, n_cu, stream);
+    return p.in_dtype == DT_F16 ? launch_dma<true>(p, n_cu, stream) : launch_dma<false>(p, n_cu, stream);
 }
 
 }  // namespace ralm

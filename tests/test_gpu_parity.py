@@ -132,6 +132,23 @@ def test_edge_cases(B, oracle):
     assert np.array_equal(ids, wi) and np.array_equal(sc, wsc)
 
 
+@pytest.mark.parametrize("Q", [5, 100, 300])
+def test_tile_admitting_more_than_the_parking_list(B, oracle, Q):
+    """A run of identical rows that is every query's best match makes single tiles admit thousands
+    of scores in a thresholded stage: more than the workgroup's on-chip list holds, so the tile is
+    redone in direct mode.  Results must still be exact, ties by lowest id."""
+    g = torch.Generator().manual_seed(11)
+    N, d = 40000, 64
+    X = torch.randint(-2, 3, (N, d), generator=g).float()
+    u = torch.randint(1, 3, (d,), generator=g).float()
+    X[20000:20400] = u
+    Qm = u.repeat(Q, 1)
+    Qm[::2] += torch.randint(0, 2, (Qm[::2].shape[0], d), generator=g).float()
+    ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, X, Qm, 20)
+    assert np.array_equal(ids, wi) and np.array_equal(sc, wsc)
+    assert ids[1].tolist() == list(range(20000, 20020))
+
+
 def test_batched_equals_sequential_and_is_deterministic(B, oracle):
     """A query's result does not depend on what else is in the batch (the property that makes
     batched verification output-preserving), nor on the run."""
