@@ -146,8 +146,20 @@ def main():
     else:
         roof = {"bound": "mfma", "achieved": round(head["scan_TFLOPs"], 1), "peak": MFMA_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(head["scan_TFLOPs"] / MFMA_PEAK_TFLOPS, 4), "traffic": None}
-    roof["kernel"] = "scan_kernel (full-datastore stage)"
+    roof["kernel"] = "scan kernel, full-datastore launch"
     roof["kernel_ms"] = round(head["scan_ms"], 4)
+    roof["algorithmic_bytes"] = N * w.d * 2
+    roof["algorithmic_flops"] = 2.0 * head["Q"] * N * w.d
+    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (summaries and the
+    # scaling against a copy kernel of known size are under profiles/); null if not measured for
+    # this workload and batch size
+    try:
+        with open(os.path.join(ROOT, "profiles", "scan_hbm_traffic.json")) as fh:
+            t = json.load(fh).get(f"{args.workload}:Q={head['Q']}") if not args.N else None
+        if t:
+            roof["traffic"] = t["fetch_bytes"] + t["write_bytes"]
+    except OSError:
+        pass
 
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
     cpu = None

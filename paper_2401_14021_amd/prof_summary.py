@@ -1,0 +1,80 @@
+"""Turn rocprofv3 CSV output into the short text summaries kept under profiles/.
+
+  python -m paper_2401_14021_amd.prof_summary trace <dir> [--label TEXT]
+      <dir> holds *_kernel_trace.csv from `rocprofv3 --kernel-trace --stats --output-format csv`.
+      Prints per-kernel call counts and average durations; launches of the scan kernels are
+      split into the full-datastore launch of each call (the longest class) and the short
+      sampling-stage launches, because one retrieval call launches the same kernel 2-3 times.
+
+  python -m paper_2401_14021_amd.prof_summary pmc <dir>
+      <dir> holds *_counter_collection.csv from `rocprofv3 --pmc ... --output-format csv`.
+      Prints, per kernel, the mean counter values of its longest launches.
+"""
+from __future__ import annotations
+
+import collections
+import csv
+import glob
+import os
+import re
+import sys
+
+
+def _short(name: str) -> str:
+    name = re.sub(r"\(anonymous namespace\)::", "", name)
+    name = re.sub(r"^void ", "", name)
+    return name.split("(")[0][:90]
+
+
+def _rows(d: str, pat: str):
+    files = sorted(glob.glob(os.path.join(d, "**", pat), recursive=True))
+    if not files:
+        raise SystemExit(f"no {pat} under {d}")
+    for f in files:
+        with open(f, newline="") as fh:
+            yield from csv.DictReader(fh)
+
+
+def trace(d: str) -> None:
+    per = collections.defaultdict(list)
+    for r in _rows(d, "*kernel_trace.csv"):
+        per[_short(r["Kernel_Name"])].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+    total = sum(sum(v) for v in per.values())
+    print(f"{'kernel':92s} {'calls':>6s} {'avg_us':>10s} {'total_ms':>9s} {'share':>6s}")
+    for k, v in sorted(per.items(), key=lambda kv: -sum(kv[1])):
+        if sum(v) / total < 0.002 and "ralm" not in k:
+            continue
+        if "scan_" in k and len(v) > 1:
+            top = max(v)
+            full = [x for x in v if x > 0.5 * top]
+            rest = [x for x in v if x <= 0.5 * top]
+            print(f"{k + ' [full-datastore launches]':92s} {len(full):6d} {sum(full)/len(full):10.1f} "
+                  f"{sum(full)/1e3:9.2f} {100*sum(full)/total:5.1f}%")
+            if rest:
+                print(f"{k + ' [sampling-stage launches]':92s} {len(rest):6d} {sum(rest)/len(rest):10.1f} "
+                      f"{sum(rest)/1e3:9.2f} {100*sum(rest)/total:5.1f}%")
+        else:
+            print(f"{k:92s} {len(v):6d} {sum(v)/len(v):10.1f} {sum(v)/1e3:9.2f} {100*sum(v)/total:5.1f}%")
+
+
+def pmc(d: str) -> None:
+    per = collections.defaultdict(lambda: collections.defaultdict(list))
+    for r in _rows(d, "*counter_collection.csv"):
+        k = _short(r["Kernel_Name"])
+        if "ralm" not in k:
+            continue
+        dur = int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
+        per[k][r["Counter_Name"]].append((dur, float(r["Counter_Value"])))
+    for k, cs in sorted(per.items()):
+        print(k)
+        for c, vals in sorted(cs.items()):
+            top = max(v[0] for v in vals)
+            sel = [v for v in vals if v[0] > 0.5 * top]
+            print(f"    {c:28s} launches={len(sel):3d} mean={sum(v[1] for v in sel)/len(sel):.6g} "
+                  f"mean_duration_us={sum(v[0] for v in sel)/len(sel)/1e3:.1f}")
+
+
+if __name__ == "__main__":
+    if len(sys.argv) < 3 or sys.argv[1] not in ("trace", "pmc"):
+        raise SystemExit(__doc__)
+    (trace if sys.argv[1] == "trace" else pmc)(sys.argv[2])
