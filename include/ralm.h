@@ -193,7 +193,8 @@ ralm_status ralm_verify(const int32_t *spec_ids, const int32_t *true_ids, int64_
 
 /*
  * Timing aid for benchmarks.  While enabled, ralm_retrieve_topk_ex brackets
- * its full-datastore scan kernel with HIP events on the call's stream.
+ * each launch of its full-datastore scan pass (one launch, or four segment
+ * launches for large batches) with HIP events on the call's stream.
  * ralm_profile_scan_ms synchronises those events and returns the total
  * milliseconds and the number of bracketed launches since the last reset
  * (host pointers), then resets.  Not thread-safe; off by default.

@@ -210,29 +210,50 @@ ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_da
     for (int s = 0; s < pl.n_stages; ++s) {
         const bool last = s == pl.n_stages - 1;
         RALM_HIP(launch_fill_u32(cnt, 0u, pl.Qpad, stream));
-        ScanParams sp;
-        sp.X = scan; sp.ldx = scan_ld; sp.N = ds->N; sp.d = ds->d; sp.in_dtype = scan_dt;
-        sp.Qs = qs; sp.dpad = pl.dpad; sp.Q = (int32_t)Q;
-        sp.tau = tau; sp.cand = cand; sp.cnt = cnt; sp.cap = pl.cap;
-        sp.tile_stride = pl.stride[s];
-        sp.park_pushes = s > 0 ? 1 : 0;
-        sp.n_row_tiles = (tiles + pl.stride[s] - 1) / pl.stride[s];
-        const bool prof = last && g_prof_on && g_prof_n < MAX_PROF;
-        if (prof) {
-            while (g_prof_made <= g_prof_n) {
-                RALM_HIP(hipEventCreate(&g_prof_ev[g_prof_made][0]));
-                RALM_HIP(hipEventCreate(&g_prof_ev[g_prof_made][1]));
-                ++g_prof_made;
+        const int64_t stage_tiles = (tiles + pl.stride[s] - 1) / pl.stride[s];
+        // With large query batches the selection's rare path (a score passes its threshold) is
+        // what limits the scan, so the full-datastore stage is cut into segments of 1/8, 1/8,
+        // 1/4 and 1/2 of the tiles and the thresholds are re-tightened from everything admitted
+        // so far after each segment: the later 7/8 of the rows then admit ~8-60x fewer scores.
+        // Candidates accumulate over the segments (the counters are not reset in between).
+        int n_seg = 1;
+        int64_t seg_end[4] = {stage_tiles, 0, 0, 0};
+        if (last && s > 0 && Q > 64 && stage_tiles >= 8192) {
+            n_seg = 4;
+            seg_end[0] = stage_tiles / 8;
+            seg_end[1] = stage_tiles / 4;
+            seg_end[2] = stage_tiles / 2;
+            seg_end[3] = stage_tiles;
+        }
+        int64_t seg_begin = 0;
+        for (int g = 0; g < n_seg; ++g) {
+            const bool final_launch = last && g == n_seg - 1;
+            ScanParams sp;
+            sp.X = scan; sp.ldx = scan_ld; sp.N = ds->N; sp.d = ds->d; sp.in_dtype = scan_dt;
+            sp.Qs = qs; sp.dpad = pl.dpad; sp.Q = (int32_t)Q;
+            sp.tau = tau; sp.cand = cand; sp.cnt = cnt; sp.cap = pl.cap;
+            sp.tile_stride = pl.stride[s];
+            sp.tile_begin = seg_begin;
+            sp.n_row_tiles = seg_end[g] - seg_begin;
+            sp.park_pushes = s > 0 ? 1 : 0;
+            const bool prof = last && g_prof_on && g_prof_n < MAX_PROF;
+            if (prof) {
+                while (g_prof_made <= g_prof_n) {
+                    RALM_HIP(hipEventCreate(&g_prof_ev[g_prof_made][0]));
+                    RALM_HIP(hipEventCreate(&g_prof_ev[g_prof_made][1]));
+                    ++g_prof_made;
+                }
+                RALM_HIP(hipEventRecord(g_prof_ev[g_prof_n][0], stream));
             }
-            RALM_HIP(hipEventRecord(g_prof_ev[g_prof_n][0], stream));
+            RALM_HIP(launch_scan(sp, n_cu, stream));
+            if (prof) {
+                RALM_HIP(hipEventRecord(g_prof_ev[g_prof_n][1], stream));
+                ++g_prof_n;
+            }
+            RALM_HIP(launch_select(cand, cnt, pl.cap, pl.k_prime, Q, tau, final_launch ? sel : nullptr,
+                                   final_launch ? sel_cnt : nullptr, flags, stream));
+            seg_begin = seg_end[g];
         }
-        RALM_HIP(launch_scan(sp, n_cu, stream));
-        if (prof) {
-            RALM_HIP(hipEventRecord(g_prof_ev[g_prof_n][1], stream));
-            ++g_prof_n;
-        }
-        RALM_HIP(launch_select(cand, cnt, pl.cap, pl.k_prime, Q, tau, last ? sel : nullptr,
-                               last ? sel_cnt : nullptr, flags, stream));
     }
     const int64_t exact_ld = ds->exact_stride ? ds->exact_stride : ds->d;
     RALM_HIP(launch_rescore(sel, sel_cnt, pl.k_prime, queries, Q, ds->exact, ds->exact_dtype, exact_ld, ds->d, k,

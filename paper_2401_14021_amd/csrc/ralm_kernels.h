@@ -26,7 +26,8 @@ struct ScanParams {
     uint32_t *cnt;          // [Q]
     uint32_t cap;
     int64_t n_row_tiles;    // tiles visited in this stage
-    int64_t tile_stride;    // visited tile t covers rows [t*tile_stride*BM, +BM)
+    int64_t tile_stride;    // visited tile t covers rows [(tile_begin+t)*tile_stride*BM, +BM)
+    int64_t tile_begin;     // first visited tile of this launch (segments of the last stage)
     int32_t park_pushes;    // 1: thresholds are selective, collect admitted scores in LDS first
 };
 

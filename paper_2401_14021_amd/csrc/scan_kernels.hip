@@ -258,7 +258,7 @@ __global__ __launch_bounds__(256) void scan_staged_kernel(const ScanParams p, co
     for (int64_t item = vb; item < total; item += G) {
         const int64_t rt = item / nqt;
         const int qt = (int)(item % nqt);
-        const int64_t row0 = rt * p.tile_stride * BM;
+        const int64_t row0 = (p.tile_begin + rt) * p.tile_stride * BM;
         const int q0 = qt * BN;
 
         f32x16 acc[TM][TN];
@@ -400,11 +400,13 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
     const int fr = lane & 31;
     const int l_r = lane / CPR, l_c = lane % CPR;
 
-    const int64_t G = gridDim.x;
-    const int64_t vb = (int64_t)(blockIdx.x % 8) * (G / 8) + blockIdx.x / 8;
-    const int64_t total = p.n_row_tiles * nqt;
+    // item indices fit 32 bits: at most 2^23 row tiles times a few query tiles (host checks)
+    const int G = (int)gridDim.x;
+    const int vb = (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8);
+    const int total = (int)p.n_row_tiles * nqt;
+    const int n_tiles = (int)p.n_row_tiles;
     const int KT = p.dpad / BK;
-    const int64_t n_mine = vb < total ? (total - vb + G - 1) / G : 0;
+    const int n_mine = vb < total ? (total - vb + G - 1) / G : 0;
     if (n_mine == 0) return;
     const unsigned char *Xb = static_cast<const unsigned char *>(p.X);
     const unsigned char *Qb = reinterpret_cast<const unsigned char *>(p.Qs);
@@ -435,10 +437,10 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
     }
     // (row tile, query tile) of an item advance by (G / nqt, G % nqt) from one item of this
     // workgroup to its next: no division in the loop
-    const int64_t step_rt = G / nqt;
-    const int step_qt = (int)(G % nqt);
-    int64_t is_rt = vb / nqt;
-    int is_qt = (int)(vb % nqt);
+    const int step_rt = G / nqt;
+    const int step_qt = G % nqt;
+    int is_rt = vb / nqt;
+    int is_qt = vb % nqt;
     int is_kt = 0, is_buf = 0;
     // wave-uniform state of the stage being issued
     const unsigned char *is_abase = nullptr, *is_bbase = nullptr;
@@ -447,8 +449,8 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
         if (is_kt == 0) {
             // The cursor is never stopped: past this workgroup's last tile it fetches (valid)
             // strips that nobody multiplies, so the steady-state loop has no conditionals.
-            const int64_t rt = is_rt < p.n_row_tiles ? is_rt : 0;
-            const int64_t row0 = rt * p.tile_stride * BM;
+            const int rt = is_rt < n_tiles ? is_rt : 0;
+            const int64_t row0 = (p.tile_begin + rt) * p.tile_stride * BM;
             is_abase = Xb + row0 * p.ldx * 2;
             is_bbase = Qb + (int64_t)is_qt * BN * p.dpad * 2;
             const int64_t left = p.N - 1 - row0;            // rows past N re-read row N-1
@@ -462,7 +464,7 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
         if (idx < NA) {
             const uint32_t r = a_row[idx] < is_rowmax ? a_row[idx] : is_rowmax;
             const uint32_t c = a_chunk[idx] < is_kmax ? a_chunk[idx] : is_kmax;
-            dma_1kb(is_abase, r * ldx2 + c, is_lds + idx * 1024);
+            dma_1kb(is_abase, __umul24(r, ldx2) + c, is_lds + idx * 1024);   // r < 2^8, ldx2 < 2^24
         } else {
             const int j = idx - NA;
             dma_1kb(is_bbase, b_voff[j], lds0 + is_buf * STAGE + A_BYTES + (wave * NB + j) * 1024);
@@ -501,10 +503,14 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
     }
     uint4 fa[2][TM], fb[2][TN];
     auto read_frag = [&](int slot, const unsigned char *sbase, int kk, int idx) __attribute__((always_inline)) {
-        if (idx < TM)
-            fa[slot][idx] = *reinterpret_cast<const uint4 *>(sbase + a_off[kk] + idx * 32 * ROWB);
-        else
-            fb[slot][idx - TM] = *reinterpret_cast<const uint4 *>(sbase + b_off[kk] + (idx - TM) * 32 * ROWB);
+        // in the order the MFMAs need them: A0, all of B, then A1..
+        if (idx == 0 || idx > TN) {
+            const int i = idx == 0 ? 0 : idx - TN;
+            fa[slot][i] = *reinterpret_cast<const uint4 *>(sbase + a_off[kk] + i * 32 * ROWB);
+        } else {
+            const int j = idx - 1;
+            fb[slot][j] = *reinterpret_cast<const uint4 *>(sbase + b_off[kk] + j * 32 * ROWB);
+        }
     };
 
     // stage 0 must be in LDS before the first operand read
@@ -515,11 +521,11 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
 
     uint32_t parked = 0;   // entries in the LDS list (uniform; maintained at tile ends)
     int buf = 0;
-    int64_t cur_rt = vb / nqt;
-    int cur_qt = (int)(vb % nqt);
-    for (int64_t it = 0; it < n_mine; ++it) {
+    int cur_rt = vb / nqt;
+    int cur_qt = vb % nqt;
+    for (int it = 0; it < n_mine; ++it) {
         f32x16 acc[TM][TN];
-        const int32_t row0 = (int32_t)(cur_rt * p.tile_stride * BM);
+        const int32_t row0 = (int32_t)((p.tile_begin + cur_rt) * p.tile_stride * BM);
         const int q0 = cur_qt * BN;
         // admission keys of this lane's TN queries
         u64 tkey[TN];
@@ -544,8 +550,8 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
                 const bool last_kk = kk + 1 == KS;
                 const unsigned char *nsb = last_kk ? smem + nbuf * STAGE : sb;
                 const int nkk = last_kk ? 0 : kk + 1;
-                // side instructions of this k-step: the global->LDS loads (k-step 1 only), then
-                // the operand reads of the next k-step (for the last k-step: of the next stage)
+                // side instructions of this k-step: the operand reads of the next k-step (for the
+                // last k-step: of the next stage), then the global->LDS loads (k-step 1 only)
                 const int nd = kk == 1 ? LPS : 0;
                 f32x16 outs[LAG + 1];
                 if (kk == 1) issue_begin();
@@ -572,10 +578,10 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
                                 acc[i][j] = mfma32<F16>(fa[cur][i], fb[cur][j], acc[i][j]);
                         }
                     }
-                    if (m < nd)
-                        issue_part(m);
-                    else if (m - nd < NR)
-                        read_frag(cur ^ 1, nsb, nkk, m - nd);
+                    if (m < NR)
+                        read_frag(cur ^ 1, nsb, nkk, m);
+                    else if (m - NR < nd)
+                        issue_part(m - NR);
                     if (LAST && last_kk && m >= LAG && m - LAG < NM) {
                         const int mm = m - LAG, i = mm / TN, j = mm % TN;
                         select_block_parked(p, pl, wave_slots, outs[mm % (LAG + 1)],
@@ -668,6 +674,7 @@ hipError_t launch_dma_variant(const ScanParams &p, int n_cu, hipStream_t stream)
     const int nqt = (int)((p.Q + BN - 1) / BN);
     const int64_t total = p.n_row_tiles * nqt;
     if (total <= 0) return hipSuccess;
+    if (total > 0x7fffffffLL) return hipErrorInvalidValue;   // the kernel counts items in 32 bits
     const int per_cu = smem * 2 <= 160 * 1024 ? 2 : 1;
     int64_t grid = (int64_t)n_cu * per_cu;
     if (total < grid) grid = total;

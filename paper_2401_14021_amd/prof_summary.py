@@ -3,8 +3,8 @@
   python -m paper_2401_14021_amd.prof_summary trace <dir> [--label TEXT]
       <dir> holds *_kernel_trace.csv from `rocprofv3 --kernel-trace --stats --output-format csv`.
       Prints per-kernel call counts and average durations; launches of the scan kernels are
-      split into the full-datastore launch of each call (the longest class) and the short
-      sampling-stage launches, because one retrieval call launches the same kernel 2-3 times.
+      grouped into duration classes, because one retrieval call launches the same kernel
+      several times (sampling stages, then the full datastore in one or four segments).
 
   python -m paper_2401_14021_amd.prof_summary pmc <dir>
       <dir> holds *_counter_collection.csv from `rocprofv3 --pmc ... --output-format csv`.
@@ -45,14 +45,18 @@ def trace(d: str) -> None:
         if sum(v) / total < 0.002 and "ralm" not in k:
             continue
         if "scan_" in k and len(v) > 1:
-            top = max(v)
-            full = [x for x in v if x > 0.5 * top]
-            rest = [x for x in v if x <= 0.5 * top]
-            print(f"{k + ' [full-datastore launches]':92s} {len(full):6d} {sum(full)/len(full):10.1f} "
-                  f"{sum(full)/1e3:9.2f} {100*sum(full)/total:5.1f}%")
-            if rest:
-                print(f"{k + ' [sampling-stage launches]':92s} {len(rest):6d} {sum(rest)/len(rest):10.1f} "
-                      f"{sum(rest)/1e3:9.2f} {100*sum(rest)/total:5.1f}%")
+            # one retrieval call launches the scan several times on very different row counts:
+            # group launches whose durations are within a factor 1.5 of each other
+            classes, cur = [], []
+            for x in sorted(v, reverse=True):
+                if cur and cur[0] > 1.5 * x:
+                    classes.append(cur)
+                    cur = []
+                cur.append(x)
+            classes.append(cur)
+            for c in classes:
+                print(f"{k + f' [launch class ~{c[0]/1e3:.2f} ms]':92s} {len(c):6d} {sum(c)/len(c):10.1f} "
+                      f"{sum(c)/1e3:9.2f} {100*sum(c)/total:5.1f}%")
         else:
             print(f"{k:92s} {len(v):6d} {sum(v)/len(v):10.1f} {sum(v)/1e3:9.2f} {100*sum(v)/total:5.1f}%")
 
