@@ -163,35 +163,3 @@ def test_specloop_steps_full_size(B, oracle, dense21m):
         cached = (cids_d[req_of] == t[:, None]).any(dim=1)
         assert bool((same | ~cached).all())
         assert bool((spec_sc[same] == sc[same, 0]).all())
-
-
-def test_knnlm_100m_fp16_large_k_sampled_queries(B, oracle):
-    """KNN-LM datastore shape at full size: 100M x 1024 fp16 keys resident in HBM (they are their
-    own scan copy and the truth), 256 queries, k = 1024 (k' = 2048).  The oracle ranks all 100M
-    keys for two sampled queries by streaming the same bytes back in 1M-row chunks."""
-    from paper_2401_14021_amd import inputs
-    w = inputs.WORKLOADS["knnlm100m"]
-    free, _ = torch.cuda.mem_get_info()
-    if free < 230e9:
-        pytest.skip("needs ~210 GB of free HBM")
-    keys = torch.empty(w.N, w.d, dtype=torch.float16, device="cuda")
-    inputs.knnlm_datastore(w.N, w.d, w.n_clusters, w.seed, device="cuda", out=keys)
-    ds = B.Datastore(keys, None)
-    Q = 256
-    rows = inputs.pick_rows(w.N, Q, seed=w.seed + 1)
-    Qm = inputs.queries_near_rows(keys, rows.cuda(), seed=w.seed + 2, sigma=0.5)
-    ws = B.alloc_workspace(Q, ds, w.k, w.k_prime)
-    ids, sc = B.ralm_retrieve_topk_ex(Qm, ds, w.k, w.k_prime, workspace=ws)
-    assert B.ralm_workspace_overflows(ws) == 0
-    assert int(ids.min()) >= 0 and int(ids.max()) < w.N
-    assert bool((sc[:, :-1] >= sc[:, 1:]).all())
-    srt = torch.sort(ids.long(), dim=1).values
-    assert bool((srt[:, 1:] != srt[:, :-1]).all())          # no duplicate ids in any row
-    sample = [3, 200]
-    qs = Qm[sample].cpu().numpy()
-    wi, wsc = _oracle_sampled(oracle, keys, qs, w.k)
-    exact, subs, total = check_topk(ids.cpu().numpy()[sample], sc.cpu().numpy()[sample], wi, wsc,
-                                    _score_of_rows(oracle, keys, qs))
-    assert exact >= 0.98 * total
-    del ds, keys
-    torch.cuda.empty_cache()

@@ -1,0 +1,72 @@
+"""GPU parity at the full size of the KNN-LM datastore configuration (kept in a module of its own so
+that the 21M-row fixtures of the other full-size tests are released first).  See test_gpu_full_size:
+
+GPU parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times.  The oracle cannot rank 21M x 768 (or 100M x 1024) rows for thousands of
+queries in test time, so it is run, by streaming the very same bytes back from the device in
+row chunks, for a seeded sample of the queries; integer stages are checked on everything."""
+import numpy as np
+import pytest
+import torch
+
+from parity import check_topk
+
+pytestmark = pytest.mark.gpu
+CHUNK = 1 << 20
+
+
+@pytest.fixture(scope="module")
+def B():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2401_14021_amd import binding
+    binding.lib()
+    return binding
+
+
+def _stream_chunks(exact):
+    N = exact.shape[0]
+    for r0 in range(0, N, CHUNK):
+        yield r0, exact[r0:min(N, r0 + CHUNK)].cpu().numpy()
+
+
+def _oracle_sampled(oracle, exact, queries_np, k):
+    return oracle.retrieve_topk_stream(queries_np, _stream_chunks(exact), k)
+
+
+def _score_of_rows(oracle, exact, queries_np):
+    def f(i, ids):
+        rows = exact[torch.as_tensor(np.asarray(ids, dtype=np.int64), device=exact.device)].cpu().numpy()
+        return oracle.scores(queries_np[i], rows)
+    return f
+
+
+def test_knnlm_100m_fp16_large_k_sampled_queries(B, oracle):
+    """KNN-LM datastore shape at full size: 100M x 1024 fp16 keys resident in HBM (they are their
+    own scan copy and the truth), 256 queries, k = 1024 (k' = 2048).  The oracle ranks all 100M
+    keys for two sampled queries by streaming the same bytes back in 1M-row chunks."""
+    from paper_2401_14021_amd import inputs
+    w = inputs.WORKLOADS["knnlm100m"]
+    free, _ = torch.cuda.mem_get_info()
+    if free < 230e9:
+        pytest.skip("needs ~210 GB of free HBM")
+    keys = torch.empty(w.N, w.d, dtype=torch.float16, device="cuda")
+    inputs.knnlm_datastore(w.N, w.d, w.n_clusters, w.seed, device="cuda", out=keys)
+    ds = B.Datastore(keys, None)
+    Q = 256
+    rows = inputs.pick_rows(w.N, Q, seed=w.seed + 1)
+    Qm = inputs.queries_near_rows(keys, rows.cuda(), seed=w.seed + 2, sigma=0.5)
+    ws = B.alloc_workspace(Q, ds, w.k, w.k_prime)
+    ids, sc = B.ralm_retrieve_topk_ex(Qm, ds, w.k, w.k_prime, workspace=ws)
+    assert B.ralm_workspace_overflows(ws) == 0
+    assert int(ids.min()) >= 0 and int(ids.max()) < w.N
+    assert bool((sc[:, :-1] >= sc[:, 1:]).all())
+    srt = torch.sort(ids.long(), dim=1).values
+    assert bool((srt[:, 1:] != srt[:, :-1]).all())          # no duplicate ids in any row
+    sample = [3, 200]
+    qs = Qm[sample].cpu().numpy()
+    wi, wsc = _oracle_sampled(oracle, keys, qs, w.k)
+    exact, subs, total = check_topk(ids.cpu().numpy()[sample], sc.cpu().numpy()[sample], wi, wsc,
+                                    _score_of_rows(oracle, keys, qs))
+    assert exact >= 0.98 * total
+    del ds, keys
+    torch.cuda.empty_cache()
