@@ -380,6 +380,7 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
     constexpr int KS = BK / 16;
     constexpr int NM = TM * TN, NR = TM + TN;
     constexpr int LAG = NM > 2 ? 2 : NM - 1;     // selection runs this many MFMAs behind
+    constexpr int RV = NR - 1;                   // k-step 0 slot after which the stage rendezvous sits
     static_assert(WM * WN == 4 && BM == SCAN_BM && NB >= 1, "tile shape");
     static_assert(S >= 3 && S <= 4 && KS % 2 == 0, "ring depth / k-steps per stage");
     static_assert(LPS * (S - 2) < 64, "vmcnt range");
@@ -552,9 +553,11 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
                 const int nkk = last_kk ? 0 : kk + 1;
                 // side instructions of this k-step: the operand reads of the next k-step (for the
                 // last k-step: of the next stage), then the global->LDS loads (k-step 1 only)
-                const int nd = kk == 1 ? LPS : 0;
+                // (the rendezvous sits inside k-step 0; the query part of the strip is requested
+                // after it in k-step 0, the datastore part in k-step 1)
+                const int nd = kk == 1 ? NA : (kk == 0 ? NB : 0);
+                const int d0 = kk == 1 ? 0 : NA;
                 f32x16 outs[LAG + 1];
-                if (kk == 1) issue_begin();
                 RALM_SCHED_FENCE();
 #pragma unroll
                 for (int m = 0; m < (NM > LPS + NR ? NM : LPS + NR) + LAG; ++m) {
@@ -581,7 +584,24 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
                     if (m < NR)
                         read_frag(cur ^ 1, nsb, nkk, m);
                     else if (m - NR < nd)
-                        issue_part(m - NR);
+                        issue_part(d0 + m - NR);
+                    if (kk == 0 && m == RV) {
+                        // Rendezvous.  After it: the next stage is complete in LDS for every
+                        // wave, and every wave has finished reading the previous stage, whose
+                        // slot is refilled by the loads issued from here on.  No LDS data is
+                        // written by ds instructions that another wave reads without a later
+                        // full barrier, so no LDS fence is needed; the asm statements keep the
+                        // compiler from moving memory operations across the barrier.
+                        RALM_T0(tw);
+                        wait_vmcnt<LPS *(S - 3)>();
+                        RALM_TADD(t_wait, tw);
+                        RALM_T0(tb);
+                        asm volatile("" ::: "memory");
+                        __builtin_amdgcn_s_barrier();
+                        asm volatile("" ::: "memory");
+                        RALM_TADD(t_bar, tb);
+                        issue_begin();
+                    }
                     if (LAST && last_kk && m >= LAG && m - LAG < NM) {
                         const int mm = m - LAG, i = mm / TN, j = mm % TN;
                         select_block_parked(p, pl, wave_slots, outs[mm % (LAG + 1)],
@@ -591,22 +611,6 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
                     RALM_SCHED_FENCE();
                 }
                 if (kk == 1) issue_end();
-                if (kk == 0) {
-                    // Rendezvous.  After it: the next stage is complete in LDS for every wave, and
-                    // every wave has finished reading the previous stage, whose slot is refilled
-                    // by the loads issued in k-step 1.  No LDS data is written by ds instructions
-                    // that another wave reads without a later full barrier, so no LDS fence is
-                    // needed here; the asm statements keep the compiler from moving memory
-                    // operations across the barrier.
-                    RALM_T0(tw);
-                    wait_vmcnt<LPS *(S - 3)>();
-                    RALM_TADD(t_wait, tw);
-                    RALM_T0(tb);
-                    asm volatile("" ::: "memory");
-                    __builtin_amdgcn_s_barrier();
-                    asm volatile("" ::: "memory");
-                    RALM_TADD(t_bar, tb);
-                }
                 RALM_SCHED_FENCE();
             }
             buf = nbuf;
