@@ -162,11 +162,11 @@ __device__ __forceinline__ void push_global(const ScanParams &p, int q, u64 key)
     if (at < p.cap) p.cand[(int64_t)q * p.cap + at] = key;
 }
 
-// all 256 threads, after a barrier that follows the last append: moves the first n parked
+// all threads of the workgroup, after a barrier that follows the last append: moves the first n parked
 // entries to the global lists and empties the LDS list
 __device__ __forceinline__ void flush_parked(const ScanParams &p, const PushList pl, uint32_t n)
 {
-    for (uint32_t e = threadIdx.x; e < n; e += 256) push_global(p, (int)pl.qs[e], pl.keys[e]);
+    for (uint32_t e = threadIdx.x; e < n; e += blockDim.x) push_global(p, (int)pl.qs[e], pl.keys[e]);
     __syncthreads();
     if (threadIdx.x == 0) *pl.count = 0;
     __syncthreads();
@@ -357,7 +357,7 @@ __device__ __forceinline__ void wait_vmcnt()
 }
 
 constexpr int TAU_LDS_MAX_Q = 2560;   // admission keys of up to this many queries are kept in LDS
-constexpr int PARK_CAP = 832;         // parked admitted scores per workgroup (12 bytes each)
+constexpr int PARK_CAP = 672;         // parked admitted scores per workgroup (12 bytes each)
 
 #define RALM_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -368,20 +368,21 @@ constexpr int PARK_CAP = 832;         // parked admitted scores per workgroup (1
 // k-step the MFMA results are written to VGPRs and each block's selection test runs two MFMAs
 // behind its last multiply, so the selection costs no separate pass over the accumulators.
 template <bool F16, int WM, int WN, int TM, int TN, int BK, int S>
-__global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const int nqt, const int tau_in_lds)
+__global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams p, const int nqt, const int tau_in_lds)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int ROWB = BK * 2;                 // bytes of one strip row
     constexpr int CPR = BK / 8;                  // 16-byte chunks per strip row
     constexpr int RPI = 64 / CPR;                // rows covered by one wave load
-    constexpr int NA = BM / RPI / 4, NB = BN / RPI / 4;   // wave loads per wave and stage
+    constexpr int NW = WM * WN, NT = NW * 64;     // waves (4: one per SIMD, 8: two per SIMD), threads
+    constexpr int NA = BM / RPI / NW, NB = BN / RPI / NW;   // wave loads per wave and stage
     constexpr int LPS = NA + NB;
     constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
     constexpr int KS = BK / 16;
     constexpr int NM = TM * TN, NR = TM + TN;
     constexpr int LAG = NM > 2 ? 2 : NM - 1;     // selection runs this many MFMAs behind
     constexpr int RV = NR - 1;                   // k-step 0 slot after which the stage rendezvous sits
-    static_assert(WM * WN == 4 && BM == SCAN_BM && NB >= 1, "tile shape");
+    static_assert((NW == 4 || NW == 8) && BM == SCAN_BM && NA >= 1 && NB >= 1, "tile shape");
     static_assert(S >= 3 && S <= 4 && KS % 2 == 0, "ring depth / k-steps per stage");
     static_assert(LPS * (S - 2) < 64, "vmcnt range");
 
@@ -416,7 +417,7 @@ __global__ __launch_bounds__(256) void scan_dma_kernel(const ScanParams p, const
 
     if (tid == 0) *pl.count = 0;
     if (tau_in_lds)
-        for (int q = tid; q < p.Q; q += 256) tau_lds[q] = p.tau[q];
+        for (int q = tid; q < p.Q; q += NT) tau_lds[q] = p.tau[q];
 #ifdef RALM_SCAN_TIMING
     unsigned long long t_wait = 0, t_bar = 0, t_epi = 0;
     RALM_T0(t_begin);
@@ -664,7 +665,7 @@ hipError_t launch_dma_variant(const ScanParams &p, int n_cu, hipStream_t stream)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t ring = (size_t)S * (BM + BN) * BK * 2;
-    constexpr size_t smem = ring + (size_t)TAU_LDS_MAX_Q * 8 + (size_t)PARK_CAP * 12 + 16 + 4 * SLOW_SLOTS * 64;
+    constexpr size_t smem = ring + (size_t)TAU_LDS_MAX_Q * 8 + (size_t)PARK_CAP * 12 + 16 + WM * WN * SLOW_SLOTS * 64;
     static_assert(smem <= 160 * 1024, "LDS budget");
     auto kern = scan_dma_kernel<F16, WM, WN, TM, TN, BK, S>;
     const int tau_in_lds = p.Q <= TAU_LDS_MAX_Q ? 1 : 0;
@@ -683,7 +684,7 @@ hipError_t launch_dma_variant(const ScanParams &p, int n_cu, hipStream_t stream)
     int64_t grid = (int64_t)n_cu * per_cu;
     if (total < grid) grid = total;
     grid = (grid + 7) / 8 * 8;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), smem, stream, p, nqt, tau_in_lds);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WM * WN * 64), smem, stream, p, nqt, tau_in_lds);
     return hipGetLastError();
 }
 
@@ -695,7 +696,7 @@ hipError_t launch_dma(const ScanParams &p, int n_cu, hipStream_t stream)
         case 32: return launch_dma_variant<F16, 4, 1, 2, 1, 64, 3>(p, n_cu, stream);
         case 64: return launch_dma_variant<F16, 4, 1, 2, 2, 64, 3>(p, n_cu, stream);
         case 128: return launch_dma_variant<F16, 2, 2, 4, 2, 32, 4>(p, n_cu, stream);
-        default: return launch_dma_variant<F16, 2, 2, 4, 4, 32, 4>(p, n_cu, stream);
+        default: return launch_dma_variant<F16, 2, 4, 4, 2, 32, 4>(p, n_cu, stream);
     }
 }
 
