@@ -129,9 +129,11 @@ def main():
         bytes_scan = N * w.d * 2
         flops = 2.0 * Q * N * w.d
         hit = float((b["spec"] == b["ids"][:, 0]).float().mean().item())
-        return dict(Q=Q, ms_per_step=ms, qps=Q / ms * 1e3, scan_ms=scan,
-                    scan_GBps=bytes_scan / scan / 1e6, scan_TFLOPs=flops / scan / 1e9,
-                    spec_hit_rate=hit), b
+        gbps, tflops = bytes_scan / scan / 1e6, flops / scan / 1e9
+        bound = "hbm" if Q < 300 else "mfma"      # scan intensity is Q flop/byte; the ridge is at ~312
+        frac = gbps / HBM_PEAK_GBS if bound == "hbm" else tflops / MFMA_PEAK_TFLOPS
+        return dict(Q=Q, ms_per_step=ms, qps=Q / ms * 1e3, scan_ms=scan, scan_GBps=gbps, scan_TFLOPs=tflops,
+                    bound=bound, roofline_frac=frac, spec_hit_rate=hit), b
 
     head, hb = run(Qh, args.steps, args.warmup)
     sweep_out = []
@@ -139,8 +141,7 @@ def main():
         r, _ = run(q, args.steps, args.warmup)
         sweep_out.append({kk: (round(v, 4) if isinstance(v, float) else v) for kk, v in r.items()})
 
-    hbm_bound = head["Q"] < 300          # arithmetic intensity of the scan is Q flop/byte; ridge ~ 312
-    if hbm_bound:
+    if head["bound"] == "hbm":
         roof = {"bound": "hbm", "achieved": round(head["scan_GBps"], 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(head["scan_GBps"] / HBM_PEAK_GBS, 4), "traffic": None}
     else:

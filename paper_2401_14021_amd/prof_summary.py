@@ -8,7 +8,7 @@
 
   python -m paper_2401_14021_amd.prof_summary pmc <dir>
       <dir> holds *_counter_collection.csv from `rocprofv3 --pmc ... --output-format csv`.
-      Prints, per kernel, the mean counter values of its longest launches.
+      Prints, per kernel and launch-duration class, the mean and the sum of each counter.
 """
 from __future__ import annotations
 
@@ -61,6 +61,18 @@ def trace(d: str) -> None:
             print(f"{k:92s} {len(v):6d} {sum(v)/len(v):10.1f} {sum(v)/1e3:9.2f} {100*sum(v)/total:5.1f}%")
 
 
+def _classes(vals):
+    """Group (duration, value) pairs whose durations are within a factor 1.5 of each other."""
+    out, cur = [], []
+    for v in sorted(vals, reverse=True):
+        if cur and cur[0][0] > 1.5 * v[0]:
+            out.append(cur)
+            cur = []
+        cur.append(v)
+    out.append(cur)
+    return out
+
+
 def pmc(d: str) -> None:
     per = collections.defaultdict(lambda: collections.defaultdict(list))
     for r in _rows(d, "*counter_collection.csv"):
@@ -72,10 +84,9 @@ def pmc(d: str) -> None:
     for k, cs in sorted(per.items()):
         print(k)
         for c, vals in sorted(cs.items()):
-            top = max(v[0] for v in vals)
-            sel = [v for v in vals if v[0] > 0.5 * top]
-            print(f"    {c:28s} launches={len(sel):3d} mean={sum(v[1] for v in sel)/len(sel):.6g} "
-                  f"mean_duration_us={sum(v[0] for v in sel)/len(sel)/1e3:.1f}")
+            for cl in _classes(vals):
+                print(f"    {c:24s} launches={len(cl):3d} mean={sum(v[1] for v in cl)/len(cl):.6g} "
+                      f"sum={sum(v[1] for v in cl):.6g} mean_duration_us={sum(v[0] for v in cl)/len(cl)/1e3:.1f}")
 
 
 if __name__ == "__main__":
