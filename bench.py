@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="dense21m", choices=["tiny", "medium", "dense21m", "knnlm100m"])
+    ap.add_argument("--workload", default="dense21m", choices=["tiny", "medium", "dense21m", "knnlm100m", "specloop"])
     ap.add_argument("--Q", type=int, default=0, help="headline batch size (0 = workload default)")
     ap.add_argument("--k", type=int, default=0)
     ap.add_argument("--N", type=int, default=0, help="override datastore rows (for quick runs)")
@@ -57,7 +57,7 @@ def main():
     N = args.N or w.N
     k = args.k or w.k
     defaults = {"tiny": (3, []), "medium": (128, [16, 32, 64]),
-                "dense21m": (1024, [1, 8, 64, 256]), "knnlm100m": (256, [])}
+                "dense21m": (1024, [1, 8, 64, 256]), "knnlm100m": (256, []), "specloop": (0, [])}
     Qh, sweep = defaults[args.workload]
     if args.Q:
         Qh = args.Q
@@ -87,8 +87,14 @@ def main():
     stride = 4
 
     def make_batch(Q, seed):
-        R = max(1, (Q + stride - 1) // stride)
-        strides = [min(stride, Q - r * stride) for r in range(R)]
+        if args.workload == "specloop":
+            # 512 concurrent requests, stride uniform in 1..8 drawn once per request (Q ~ 2300)
+            R = 512
+            strides = inputs.uniform_strides(R, 1, 8, seed=w.seed)
+            Q = sum(strides)
+        else:
+            R = max(1, (Q + stride - 1) // stride)
+            strides = [min(stride, Q - r * stride) for r in range(R)]
         off = inputs.stride_offsets(strides)
         rows = inputs.pick_rows(N, Q, seed=seed)
         Qm = inputs.queries_near_rows(ds.exact, rows.to(dev), seed=seed + 1, sigma=q_sigma)
@@ -127,11 +133,12 @@ def main():
         ms = dt / steps * 1e3
         scan = scan_ms / steps                            # all launches of one full-datastore pass
         bytes_scan = N * w.d * 2
-        flops = 2.0 * Q * N * w.d
+        flops = 2.0 * b["Q"] * N * w.d
         hit = float((b["spec"] == b["ids"][:, 0]).float().mean().item())
         gbps, tflops = bytes_scan / scan / 1e6, flops / scan / 1e9
-        bound = "hbm" if Q < 300 else "mfma"      # scan intensity is Q flop/byte; the ridge is at ~312
+        bound = "hbm" if b["Q"] < 300 else "mfma"      # scan intensity is Q flop/byte; the ridge is at ~312
         frac = gbps / HBM_PEAK_GBS if bound == "hbm" else tflops / MFMA_PEAK_TFLOPS
+        Q = b["Q"]
         return dict(Q=Q, ms_per_step=ms, qps=Q / ms * 1e3, scan_ms=scan, scan_GBps=gbps, scan_TFLOPs=tflops,
                     bound=bound, roofline_frac=frac, spec_hit_rate=hit), b
 
@@ -188,7 +195,7 @@ def main():
         "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.scan_dtype == "bf16" else "f16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: N={N} d={w.d} scan={w.scan_dtype} exact={w.exact_dtype} "
-                               f"Q={head['Q']} k={k} k_prime={w.k_prime} requests={hb['R']} stride<={stride} "
+                               f"Q={head['Q']} k={k} k_prime={w.k_prime} requests={hb['R']} "
                                f"cache={C}",
                    "gen_seconds": round(gen_s, 1), "spec_hit_rate": round(head["spec_hit_rate"], 3)},
         "roofline": roof,
