@@ -4,13 +4,15 @@
 //
 // How one ralm_retrieve_topk_ex call runs (everything on the caller's stream):
 //   1. queries are rounded to the scan dtype into a zero-padded matrix;
-//   2. a ladder of scan stages runs over nested, strided samples of the datastore's row
-//      tiles, the last stage being the whole datastore.  Stage i admits a score only if its
-//      ranking key is >= the k'-th best key of stage i-1 (a subset of stage i's rows, so that
-//      key is a valid lower bound on stage i's own k'-th best); the first stage is small
-//      enough to keep everything.  Each stage: zero the per-query counters, scan, select the
-//      k'-th best key per query.
-//   3. the k' keys kept by the last stage are re-scored from the exact copy and ranked.
+//   2. the datastore's 256-row tiles are scanned exactly once, in a ladder of stages that
+//      visit them in a progressively finer strided order: stage 0 visits every s0-th tile and
+//      keeps every score (s0 is chosen so that they fit the candidate lists); stage i visits
+//      the tiles at stride s0/g^i that no earlier stage visited.  After each stage the exact
+//      k'-th best key of everything scanned so far becomes the admission key of the next
+//      stage (a valid lower bound on the final k'-th best, because the scanned rows are a
+//      subset of all rows) and each list is cut down to its k' best.  Every stage's rows are
+//      a representative sample, so a stage admits only about k'*(g-1) scores per query.
+//   3. the k' keys left in each list are re-scored from the exact copy and ranked.
 #include <hip/hip_runtime.h>
 #include <stdarg.h>
 #include <stdio.h>
@@ -49,14 +51,13 @@ int elem_bytes(int dt) { return dt == RALM_F32 ? 4 : 2; }
 // ---- stage plan ---------------------------------------------------------------------------
 struct Plan {
     int32_t k_prime;
-    int32_t ratio;        // sample ratio between consecutive stages
     uint32_t cap;         // candidate slots per query
     int64_t Qpad;
     int32_t dpad;
     int n_stages;
-    int64_t stride[16];   // tile stride of each stage, first = coarsest, last = 1
+    int64_t stride[40];   // tile stride of each stage, first = coarsest, last = 1
     // workspace offsets
-    size_t off_q, off_tau, off_cnt, off_selcnt, off_flags, off_cand, off_sel, total;
+    size_t off_q, off_tau, off_cnt, off_flags, off_cand, off_sel, total;
 };
 
 int32_t default_k_prime(int32_t k)
@@ -75,36 +76,45 @@ ralm_status make_plan(int64_t Q, const ralm_datastore_t *ds, int32_t k, int32_t 
     if (k_prime < k || k_prime > RALM_MAX_K_PRIME)
         return fail(RALM_ERR_K, "k_prime=%d must be in [k, %d]", k_prime, RALM_MAX_K_PRIME);
     pl.k_prime = k_prime;
-    // expected admissions per query and stage = k' * ratio; the slots leave 4x (2x for large k')
-    // head room, far beyond the spread of that count for rows in random order
-    pl.ratio = k_prime <= 256 ? 64 : 32;
+    // Stage strides, finest first: 1, then multiplied by the stage's growth until a stage is
+    // small enough to keep every score (that one is stage 0).  A stage that refines by g is
+    // expected to admit k'*(g-1) scores per query.  Large batches are limited by the matrix
+    // cores and by the rare path of the selection, so their big last stages refine in steps
+    // of 2; small batches are limited by HBM and prefer few launches.
+    const int32_t g_fine = 2, g_coarse = Q > 64 ? 8 : (k_prime <= 256 ? 64 : 32);
+    const int64_t fine_until = Q > 64 ? 8 : 1;    // strides below this refine by g_fine
+    // the slots leave 4x (2x for large k') head room over that expectation, far beyond the
+    // spread of the count for rows in random order, and are never fewer than 16384 so that
+    // stage 0 can be a real sample
     const int64_t safety = k_prime <= 256 ? 4 : 2;
-    pl.cap = (uint32_t)(safety * k_prime * pl.ratio);
+    pl.cap = (uint32_t)(safety * k_prime * (g_coarse - 1) + k_prime);
     if (pl.cap < 16384u) pl.cap = 16384u;
     pl.Qpad = (Q + SCAN_QPAD - 1) / SCAN_QPAD * SCAN_QPAD;
     pl.dpad = (ds->d + SCAN_BK - 1) / SCAN_BK * SCAN_BK;
 
     const int64_t tiles = (ds->N + SCAN_BM - 1) / SCAN_BM;
-    int64_t strides[16];
+    auto fits = [&](int64_t s) { return ((tiles + s - 1) / s) * SCAN_BM <= (int64_t)pl.cap; };
+    int64_t rev[40];
     int n = 0;
     int64_t s = 1;
-    strides[n++] = 1;
-    // coarsen until a stage's rows all fit the candidate slots (that stage keeps everything)
-    while (((tiles + s - 1) / s) * SCAN_BM > (int64_t)pl.cap && n < 16) {
-        s *= pl.ratio;
-        strides[n++] = s;
+    rev[n++] = s;
+    while (!fits(s)) {
+        const int32_t g = s < fine_until ? g_fine : g_coarse;
+        int32_t f = 2;
+        while (f < g && !fits(s * f)) ++f;     // the coarsest step may be shorter
+        s *= f;
+        rev[n++] = s;
     }
     pl.n_stages = n;
-    for (int i = 0; i < n; ++i) pl.stride[i] = strides[n - 1 - i];
+    for (int i = 0; i < n; ++i) pl.stride[i] = rev[n - 1 - i];
 
     size_t off = 0;
     pl.off_flags = off;  off += 256;   // always first: word 0 = overflowed queries of the last call
     pl.off_q = off;      off += up256((size_t)pl.Qpad * pl.dpad * 2);
     pl.off_tau = off;    off += up256((size_t)pl.Qpad * 8);
     pl.off_cnt = off;    off += up256((size_t)pl.Qpad * 4);
-    pl.off_selcnt = off; off += up256((size_t)pl.Qpad * 4);
     pl.off_cand = off;   off += up256((size_t)Q * pl.cap * 8);
-    pl.off_sel = off;    off += up256((size_t)Q * k_prime * 8);
+    pl.off_sel = off;    off += up256((size_t)Q * k_prime * 8);   // scratch of the select kernel
     pl.total = off;
     return RALM_OK;
 }
@@ -148,7 +158,7 @@ int device_cus()
 }
 
 // ---- scan timing aid ------------------------------------------------------------------------
-constexpr int MAX_PROF = 256;
+constexpr int MAX_PROF = 2048;
 bool g_prof_on = false;
 int g_prof_n = 0;
 hipEvent_t g_prof_ev[MAX_PROF][2];
@@ -190,7 +200,6 @@ ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_da
     uint16_t *qs = reinterpret_cast<uint16_t *>(ws + pl.off_q);
     u64 *tau = reinterpret_cast<u64 *>(ws + pl.off_tau);
     uint32_t *cnt = reinterpret_cast<uint32_t *>(ws + pl.off_cnt);
-    uint32_t *sel_cnt = reinterpret_cast<uint32_t *>(ws + pl.off_selcnt);
     int32_t *flags = reinterpret_cast<int32_t *>(ws + pl.off_flags);
     u64 *cand = reinterpret_cast<u64 *>(ws + pl.off_cand);
     u64 *sel = reinterpret_cast<u64 *>(ws + pl.off_sel);
@@ -207,56 +216,44 @@ ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_da
     RALM_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(flags), 0u, 64, stream));
 
     const int64_t tiles = (ds->N + SCAN_BM - 1) / SCAN_BM;
+    RALM_HIP(launch_fill_u32(cnt, 0u, pl.Qpad, stream));
     for (int s = 0; s < pl.n_stages; ++s) {
-        const bool last = s == pl.n_stages - 1;
-        RALM_HIP(launch_fill_u32(cnt, 0u, pl.Qpad, stream));
-        const int64_t stage_tiles = (tiles + pl.stride[s] - 1) / pl.stride[s];
-        // With large query batches the selection's rare path (a score passes its threshold) is
-        // what limits the scan, so the full-datastore stage is cut into segments of 1/8, 1/8,
-        // 1/4 and 1/2 of the tiles and the thresholds are re-tightened from everything admitted
-        // so far after each segment: the later 7/8 of the rows then admit ~8-60x fewer scores.
-        // Candidates accumulate over the segments (the counters are not reset in between).
-        int n_seg = 1;
-        int64_t seg_end[4] = {stage_tiles, 0, 0, 0};
-        if (last && s > 0 && Q > 64 && stage_tiles >= 8192) {
-            n_seg = 4;
-            seg_end[0] = stage_tiles / 8;
-            seg_end[1] = stage_tiles / 4;
-            seg_end[2] = stage_tiles / 2;
-            seg_end[3] = stage_tiles;
+        const int64_t stride = pl.stride[s];
+        ScanParams sp;
+        sp.X = scan; sp.ldx = scan_ld; sp.N = ds->N; sp.d = ds->d; sp.in_dtype = scan_dt;
+        sp.Qs = qs; sp.dpad = pl.dpad; sp.Q = (int32_t)Q;
+        sp.tau = tau; sp.cand = cand; sp.cnt = cnt; sp.cap = pl.cap;
+        sp.tile_stride = stride;
+        if (s == 0) {
+            sp.tile_skip = 0;                                   // every multiple of the stride
+            sp.n_row_tiles = (tiles + stride - 1) / stride;
+            sp.park_pushes = 0;                                 // admits everything
+        } else {
+            const int64_t m_max = (tiles + stride - 1) / stride - 1;   // multiples m >= 1 with m*stride < tiles
+            const int64_t g = pl.stride[s - 1] / stride;        // ... that no earlier stage visited
+            sp.tile_skip = (int32_t)g;
+            sp.n_row_tiles = m_max - m_max / g;
+            sp.park_pushes = 1;
         }
-        int64_t seg_begin = 0;
-        for (int g = 0; g < n_seg; ++g) {
-            const bool final_launch = last && g == n_seg - 1;
-            ScanParams sp;
-            sp.X = scan; sp.ldx = scan_ld; sp.N = ds->N; sp.d = ds->d; sp.in_dtype = scan_dt;
-            sp.Qs = qs; sp.dpad = pl.dpad; sp.Q = (int32_t)Q;
-            sp.tau = tau; sp.cand = cand; sp.cnt = cnt; sp.cap = pl.cap;
-            sp.tile_stride = pl.stride[s];
-            sp.tile_begin = seg_begin;
-            sp.n_row_tiles = seg_end[g] - seg_begin;
-            sp.park_pushes = s > 0 ? 1 : 0;
-            const bool prof = last && g_prof_on && g_prof_n < MAX_PROF;
-            if (prof) {
-                while (g_prof_made <= g_prof_n) {
-                    RALM_HIP(hipEventCreate(&g_prof_ev[g_prof_made][0]));
-                    RALM_HIP(hipEventCreate(&g_prof_ev[g_prof_made][1]));
-                    ++g_prof_made;
-                }
-                RALM_HIP(hipEventRecord(g_prof_ev[g_prof_n][0], stream));
+        if (sp.n_row_tiles <= 0) continue;
+        const bool prof = g_prof_on && g_prof_n < MAX_PROF;
+        if (prof) {
+            while (g_prof_made <= g_prof_n) {
+                RALM_HIP(hipEventCreate(&g_prof_ev[g_prof_made][0]));
+                RALM_HIP(hipEventCreate(&g_prof_ev[g_prof_made][1]));
+                ++g_prof_made;
             }
-            RALM_HIP(launch_scan(sp, n_cu, stream));
-            if (prof) {
-                RALM_HIP(hipEventRecord(g_prof_ev[g_prof_n][1], stream));
-                ++g_prof_n;
-            }
-            RALM_HIP(launch_select(cand, cnt, pl.cap, pl.k_prime, Q, tau, final_launch ? sel : nullptr,
-                                   final_launch ? sel_cnt : nullptr, flags, stream));
-            seg_begin = seg_end[g];
+            RALM_HIP(hipEventRecord(g_prof_ev[g_prof_n][0], stream));
         }
+        RALM_HIP(launch_scan(sp, n_cu, stream));
+        if (prof) {
+            RALM_HIP(hipEventRecord(g_prof_ev[g_prof_n][1], stream));
+            ++g_prof_n;
+        }
+        RALM_HIP(launch_select(cand, cnt, pl.cap, pl.k_prime, Q, tau, sel, flags, stream));
     }
     const int64_t exact_ld = ds->exact_stride ? ds->exact_stride : ds->d;
-    RALM_HIP(launch_rescore(sel, sel_cnt, pl.k_prime, queries, Q, ds->exact, ds->exact_dtype, exact_ld, ds->d, k,
+    RALM_HIP(launch_rescore(cand, cnt, pl.cap, pl.k_prime, queries, Q, ds->exact, ds->exact_dtype, exact_ld, ds->d, k,
                             out_ids, out_scores, out_margin, stream));
     return RALM_OK;
 }

@@ -26,8 +26,8 @@ struct ScanParams {
     uint32_t *cnt;          // [Q]
     uint32_t cap;
     int64_t n_row_tiles;    // tiles visited in this stage
-    int64_t tile_stride;    // visited tile t covers rows [(tile_begin+t)*tile_stride*BM, +BM)
-    int64_t tile_begin;     // first visited tile of this launch (segments of the last stage)
+    int64_t tile_stride;    // visited tile t is datastore tile m(t) * tile_stride, where m(t) = t if
+    int32_t tile_skip;      // tile_skip == 0, else the t-th positive integer that is no multiple of tile_skip
     int32_t park_pushes;    // 1: thresholds are selective, collect admitted scores in LDS first
 };
 
@@ -45,15 +45,16 @@ hipError_t launch_query_prep(const float *q, int64_t Q, int32_t d, uint16_t *out
 hipError_t launch_convert_rows(const float *src, int64_t src_ld, void *dst, int32_t dst_dtype,
                                int64_t dst_ld, int64_t N, int32_t d, hipStream_t stream);
 
-// per query: k'-th best key of cand[q, 0..cnt[q]) -> tau[q]; optionally the k' best keys
-hipError_t launch_select(const u64 *cand, const uint32_t *cnt, uint32_t cap, int32_t k_prime, int64_t Q,
-                         u64 *tau, u64 *sel, uint32_t *sel_cnt, int32_t *overflow_count,
-                         hipStream_t stream);
+// per query: k'-th best key of cand[q, 0..cnt[q]) -> tau[q]; the list is then cut down, in place,
+// to its k' best keys (cnt[q] <- min(cnt[q], k')).  tmp is scratch of [Q, k'] keys.  A list
+// that overflowed its cap slots gets cnt[q] = 0xffffffff, tau[q] = ~0 and is counted once.
+hipError_t launch_select(u64 *cand, uint32_t *cnt, uint32_t cap, int32_t k_prime, int64_t Q, u64 *tau,
+                         u64 *tmp, int32_t *overflow_count, hipStream_t stream);
 
-// per query: exact scores of the selected rows, final ranking, top k out
-hipError_t launch_rescore(const u64 *sel, const uint32_t *sel_cnt, int32_t k_prime, const float *queries,
-                          int64_t Q, const void *exact, int32_t exact_dtype, int64_t ld, int32_t d,
-                          int32_t k, int32_t *out_ids, float *out_scores, float *out_margin,
+// per query: exact scores of the (at most k') rows left in its list, final ranking, top k out
+hipError_t launch_rescore(const u64 *cand, const uint32_t *cnt, uint32_t cap, int32_t k_prime,
+                          const float *queries, int64_t Q, const void *exact, int32_t exact_dtype, int64_t ld,
+                          int32_t d, int32_t k, int32_t *out_ids, float *out_scores, float *out_margin,
                           hipStream_t stream);
 
 hipError_t launch_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,

@@ -86,6 +86,16 @@ __device__ __forceinline__ f32x16 mfma32(const uint4 &a, const uint4 &b, const f
 
 #define RALM_LDS __attribute__((address_space(3)))
 
+// datastore tile of the t-th tile a launch visits (see ScanParams)
+__device__ __forceinline__ int64_t visited_tile(const ScanParams &p, int64_t t)
+{
+    if (p.tile_skip) {
+        const int64_t g1 = p.tile_skip - 1;
+        t = (t / g1) * p.tile_skip + t % g1 + 1;
+    }
+    return t * p.tile_stride;
+}
+
 // acc[i][j][v] of a wave is the score of datastore row
 //     row0 + (wm*TM + i)*32 + (v/4)*8 + (lane/32)*4 + v%4
 // against query  q0 + (wn*TN + j)*32 + lane%32.  A score is admitted (appended to its query's
@@ -258,7 +268,7 @@ __global__ __launch_bounds__(256) void scan_staged_kernel(const ScanParams p, co
     for (int64_t item = vb; item < total; item += G) {
         const int64_t rt = item / nqt;
         const int qt = (int)(item % nqt);
-        const int64_t row0 = (p.tile_begin + rt) * p.tile_stride * BM;
+        const int64_t row0 = visited_tile(p, rt) * BM;
         const int q0 = qt * BN;
 
         f32x16 acc[TM][TN];
@@ -452,7 +462,7 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
             // The cursor is never stopped: past this workgroup's last tile it fetches (valid)
             // strips that nobody multiplies, so the steady-state loop has no conditionals.
             const int rt = is_rt < n_tiles ? is_rt : 0;
-            const int64_t row0 = (p.tile_begin + rt) * p.tile_stride * BM;
+            const int64_t row0 = visited_tile(p, rt) * BM;
             is_abase = Xb + row0 * p.ldx * 2;
             is_bbase = Qb + (int64_t)is_qt * BN * p.dpad * 2;
             const int64_t left = p.N - 1 - row0;            // rows past N re-read row N-1
@@ -527,7 +537,7 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     int cur_qt = vb % nqt;
     for (int it = 0; it < n_mine; ++it) {
         f32x16 acc[TM][TN];
-        const int32_t row0 = (int32_t)((p.tile_begin + cur_rt) * p.tile_stride * BM);
+        const int32_t row0 = (int32_t)(visited_tile(p, cur_rt) * BM);
         const int q0 = cur_qt * BN;
         // admission keys of this lane's TN queries
         u64 tkey[TN];

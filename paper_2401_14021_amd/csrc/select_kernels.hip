@@ -1,8 +1,8 @@
 // Per-query selection and exact re-scoring (gfx950).
 //
 //  select_kernel   exact k'-th best of a query's candidate keys by an 8-bit radix descent
-//                  over the 64-bit ranking key; writes the admission key for the next scan
-//                  stage and, on request, the k' best keys themselves.
+//                  over the 64-bit ranking key; writes it as the admission key for the next
+//                  scan stage and cuts the list down to its k' best keys in place.
 //  rescore_kernel  for the k' rows kept by the scan: inner product with the fp32 query from
 //                  the EXACT datastore copy, products and sum in double, one rounding to
 //                  fp32; final ranking (score descending, id ascending); first k written.
@@ -32,11 +32,9 @@ __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t x, uint32_t *w
     return x + add;
 }
 
-__global__ __launch_bounds__(256) void select_kernel(const u64 *__restrict__ cand,
-                                                     const uint32_t *__restrict__ cnt, uint32_t cap,
-                                                     int k_prime, u64 *__restrict__ tau,
-                                                     u64 *__restrict__ sel, uint32_t *__restrict__ sel_cnt,
-                                                     int32_t *__restrict__ overflow_count)
+__global__ __launch_bounds__(256) void select_kernel(u64 *__restrict__ cand, uint32_t *__restrict__ cnt,
+                                                     uint32_t cap, int k_prime, u64 *__restrict__ tau,
+                                                     u64 *__restrict__ tmp, int32_t *__restrict__ overflow_count)
 {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t wave_tot[4];
@@ -45,59 +43,63 @@ __global__ __launch_bounds__(256) void select_kernel(const u64 *__restrict__ can
     const int64_t q = blockIdx.x;
     const int tid = threadIdx.x;
     const uint32_t n = cnt[q];
-    const u64 *c = cand + q * (int64_t)cap;
+    u64 *c = cand + q * (int64_t)cap;
 
-    if (n > cap) {   // buffer overflowed: this query cannot be answered from it
+    if (n == 0xffffffffu) return;   // flagged by an earlier stage
+    if (n > cap) {                  // list overflowed: this query cannot be answered from it
         if (tid == 0) {
-            tau[q] = ~0ull;
-            if (sel_cnt) sel_cnt[q] = 0xffffffffu;
+            tau[q] = ~0ull;         // admits nothing from now on
+            cnt[q] = 0xffffffffu;
             atomicAdd(overflow_count, 1);
         }
         return;
     }
-
-    u64 kth = 0;   // 0 admits everything (fewer than k' candidates exist)
-    if (n > (uint32_t)k_prime) {
-        u64 prefix = 0, mask = 0;
-        uint32_t remaining = (uint32_t)k_prime;
-        for (int shift = 56; shift >= 0; shift -= 8) {
-            hist[tid] = 0;
-            __syncthreads();
-            for (uint32_t i = tid; i < n; i += 256) {
-                const u64 key = c[i];
-                if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
-            }
-            __syncthreads();
-            // thread t looks at digit 255 - t: walk digits from the best downwards
-            const uint32_t h = hist[255 - tid];
-            const uint32_t incl = block_inclusive_scan(h, wave_tot);
-            if (incl >= remaining && incl - h < remaining) {
-                s_digit = 255 - tid;
-                s_remaining = remaining - (incl - h);
-            }
-            __syncthreads();
-            prefix |= (u64)s_digit << shift;
-            mask |= 0xffull << shift;
-            remaining = s_remaining;
-            __syncthreads();
-        }
-        kth = prefix;
+    if (n < (uint32_t)k_prime) {    // fewer than k' candidates exist so far: keep admitting everything
+        if (tid == 0) tau[q] = 0ull;
+        return;
     }
-    if (tid == 0) tau[q] = kth;
 
-    if (sel) {
-        if (tid == 0) s_out = 0;
+    u64 prefix = 0, mask = 0;
+    uint32_t remaining = (uint32_t)k_prime;
+    for (int shift = 56; shift >= 0; shift -= 8) {
+        hist[tid] = 0;
         __syncthreads();
-        u64 *out = sel + q * (int64_t)k_prime;
         for (uint32_t i = tid; i < n; i += 256) {
             const u64 key = c[i];
-            if (key >= kth) {
-                const uint32_t at = atomicAdd(&s_out, 1u);
-                if (at < (uint32_t)k_prime) out[at] = key;
-            }
+            if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
         }
         __syncthreads();
-        if (tid == 0) sel_cnt[q] = s_out < (uint32_t)k_prime ? s_out : (uint32_t)k_prime;
+        // thread t looks at digit 255 - t: walk digits from the best downwards
+        const uint32_t h = hist[255 - tid];
+        const uint32_t incl = block_inclusive_scan(h, wave_tot);
+        if (incl >= remaining && incl - h < remaining) {
+            s_digit = 255 - tid;
+            s_remaining = remaining - (incl - h);
+        }
+        __syncthreads();
+        prefix |= (u64)s_digit << shift;
+        mask |= 0xffull << shift;
+        remaining = s_remaining;
+        __syncthreads();
+    }
+    const u64 kth = prefix;   // keys are distinct: exactly k' of them are >= kth
+
+    // cut the list down to those k' keys, in place (via tmp)
+    if (tid == 0) s_out = 0;
+    __syncthreads();
+    u64 *t = tmp + q * (int64_t)k_prime;
+    for (uint32_t i = tid; i < n; i += 256) {
+        const u64 key = c[i];
+        if (key >= kth) {
+            const uint32_t at = atomicAdd(&s_out, 1u);
+            if (at < (uint32_t)k_prime) t[at] = key;
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < k_prime; i += 256) c[i] = t[i];
+    if (tid == 0) {
+        tau[q] = kth;
+        cnt[q] = (uint32_t)k_prime;
     }
 }
 
@@ -109,9 +111,9 @@ __device__ __forceinline__ double wave_sum(double x)
 }
 
 template <int EX>   // DT_F32 or DT_F16 exact rows
-__global__ __launch_bounds__(256) void rescore_kernel(const u64 *__restrict__ sel,
-                                                      const uint32_t *__restrict__ sel_cnt, int k_prime,
-                                                      int kp2, const float *__restrict__ queries,
+__global__ __launch_bounds__(256) void rescore_kernel(const u64 *__restrict__ cand,
+                                                      const uint32_t *__restrict__ cnt, uint32_t cap,
+                                                      int k_prime, int kp2, const float *__restrict__ queries,
                                                       const void *__restrict__ exact, int64_t ld, int d,
                                                       int k, int32_t *__restrict__ out_ids,
                                                       float *__restrict__ out_scores,
@@ -123,10 +125,10 @@ __global__ __launch_bounds__(256) void rescore_kernel(const u64 *__restrict__ se
 
     const int64_t q = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t n_raw = sel_cnt[q];
+    const uint32_t n_raw = cnt[q];
     const bool overflow = n_raw == 0xffffffffu;
-    const int n = overflow ? 0 : (int)n_raw;
-    const u64 *mine = sel + q * (int64_t)k_prime;
+    const int n = overflow ? 0 : (int)(n_raw < (uint32_t)k_prime ? n_raw : (uint32_t)k_prime);
+    const u64 *mine = cand + q * (int64_t)cap;
     const float *qv = queries + q * (int64_t)d;
 
     u64 min_scan = ~0ull;
@@ -207,30 +209,28 @@ __global__ __launch_bounds__(256) void rescore_kernel(const u64 *__restrict__ se
 
 }  // namespace
 
-hipError_t launch_select(const u64 *cand, const uint32_t *cnt, uint32_t cap, int32_t k_prime, int64_t Q,
-                         u64 *tau, u64 *sel, uint32_t *sel_cnt, int32_t *overflow_count,
-                         hipStream_t stream)
+hipError_t launch_select(u64 *cand, uint32_t *cnt, uint32_t cap, int32_t k_prime, int64_t Q, u64 *tau, u64 *tmp,
+                         int32_t *overflow_count, hipStream_t stream)
 {
     if (Q <= 0) return hipSuccess;
-    hipLaunchKernelGGL(select_kernel, dim3((unsigned)Q), dim3(256), 0, stream, cand, cnt, cap, k_prime,
-                       tau, sel, sel_cnt, overflow_count);
+    hipLaunchKernelGGL(select_kernel, dim3((unsigned)Q), dim3(256), 0, stream, cand, cnt, cap, k_prime, tau, tmp,
+                       overflow_count);
     return hipGetLastError();
 }
 
-hipError_t launch_rescore(const u64 *sel, const uint32_t *sel_cnt, int32_t k_prime, const float *queries,
-                          int64_t Q, const void *exact, int32_t exact_dtype, int64_t ld, int32_t d,
-                          int32_t k, int32_t *out_ids, float *out_scores, float *out_margin,
-                          hipStream_t stream)
+hipError_t launch_rescore(const u64 *cand, const uint32_t *cnt, uint32_t cap, int32_t k_prime, const float *queries,
+                          int64_t Q, const void *exact, int32_t exact_dtype, int64_t ld, int32_t d, int32_t k,
+                          int32_t *out_ids, float *out_scores, float *out_margin, hipStream_t stream)
 {
     if (Q <= 0) return hipSuccess;
     int kp2 = 2;
     while (kp2 < k_prime) kp2 <<= 1;
     const size_t smem = (size_t)kp2 * sizeof(u64);
     if (exact_dtype == DT_F16)
-        hipLaunchKernelGGL(rescore_kernel<DT_F16>, dim3((unsigned)Q), dim3(256), smem, stream, sel, sel_cnt,
+        hipLaunchKernelGGL(rescore_kernel<DT_F16>, dim3((unsigned)Q), dim3(256), smem, stream, cand, cnt, cap,
                            k_prime, kp2, queries, exact, ld, d, k, out_ids, out_scores, out_margin);
     else
-        hipLaunchKernelGGL(rescore_kernel<DT_F32>, dim3((unsigned)Q), dim3(256), smem, stream, sel, sel_cnt,
+        hipLaunchKernelGGL(rescore_kernel<DT_F32>, dim3((unsigned)Q), dim3(256), smem, stream, cand, cnt, cap,
                            k_prime, kp2, queries, exact, ld, d, k, out_ids, out_scores, out_margin);
     return hipGetLastError();
 }
