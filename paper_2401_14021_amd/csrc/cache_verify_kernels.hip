@@ -28,9 +28,11 @@ __device__ __forceinline__ void clamp_range(const int64_t *off, int64_t r, int64
     hi = hi < lo ? lo : (hi > Qt ? Qt : hi);
 }
 
-// NCH = float4 chunks of a row held by one lane (row element (c*CL_GS + sub)*4 .. +4)
-template <int EX, int NCH>
-__global__ __launch_bounds__(256) void cache_lookup_kernel(
+// NCH = float4 chunks of a row held by one lane (row element (c*CL_GS + sub)*4 .. +4).
+// One block of NW waves per request: every wave step gathers CL_ROWS cached rows, so a block
+// has NW*CL_ROWS random row reads in flight; the other waves' arithmetic hides their latency.
+template <int EX, int NCH, int NW>
+__global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
     const int32_t *__restrict__ cache_ids, const int32_t *__restrict__ cache_len, int C,
     const float *__restrict__ queries, int64_t Qt, const int64_t *__restrict__ q_offsets,
     const void *__restrict__ exact, int64_t ld, int64_t N, int d, int qgroup,
@@ -38,7 +40,7 @@ __global__ __launch_bounds__(256) void cache_lookup_kernel(
 {
     extern __shared__ __align__(16) unsigned char smem[];
     float *qs = reinterpret_cast<float *>(smem);                   // [qgroup][d]
-    u64 *best = reinterpret_cast<u64 *>(qs + (size_t)qgroup * d);   // [4 waves][CL_ROWS][qgroup]
+    u64 *best = reinterpret_cast<u64 *>(qs + (size_t)qgroup * d);   // [NW waves][CL_ROWS][qgroup]
 
     const int64_t r = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -52,13 +54,13 @@ __global__ __launch_bounds__(256) void cache_lookup_kernel(
     for (int64_t g0 = q_lo; g0 < q_hi; g0 += qgroup) {
         const int nq = (int)((q_hi - g0) < qgroup ? (q_hi - g0) : qgroup);
         __syncthreads();
-        for (int i = tid * 4; i < nq * d; i += 1024)
+        for (int i = tid * 4; i < nq * d; i += NW * 256)
             *reinterpret_cast<float4 *>(qs + i) = *reinterpret_cast<const float4 *>(queries + g0 * d + i);
-        for (int i = tid; i < 4 * CL_ROWS * qgroup; i += 256) best[i] = 0ull;
+        for (int i = tid; i < NW * CL_ROWS * qgroup; i += NW * 64) best[i] = 0ull;
         __syncthreads();
         u64 *my_best = best + (wave * CL_ROWS + slot) * qgroup;
 
-        for (int e0 = wave * CL_ROWS; e0 < len; e0 += 4 * CL_ROWS) {
+        for (int e0 = wave * CL_ROWS; e0 < len; e0 += NW * CL_ROWS) {
             const int e = e0 + slot;
             const int32_t id = e < len ? ids[e] : -1;
             const bool ok = id >= 0 && (int64_t)id < N;
@@ -102,9 +104,9 @@ __global__ __launch_bounds__(256) void cache_lookup_kernel(
             }
         }
         __syncthreads();
-        for (int qi = tid; qi < nq; qi += 256) {
+        for (int qi = tid; qi < nq; qi += NW * 64) {
             u64 b = 0ull;
-            for (int w = 0; w < 4 * CL_ROWS; ++w) {
+            for (int w = 0; w < NW * CL_ROWS; ++w) {
                 const u64 v = best[w * qgroup + qi];
                 b = v > b ? v : b;
             }
@@ -198,17 +200,18 @@ hipError_t launch_cache_ex(const int32_t *cache_ids, const int32_t *cache_len, i
     int qgroup = CL_LDS_BYTES / (d * 4);
     if (qgroup > 16) qgroup = 16;
     if (qgroup < 1) return hipErrorInvalidValue;
-    const size_t smem = (size_t)qgroup * d * 4 + (size_t)4 * CL_ROWS * qgroup * sizeof(u64);
     const int nch = (d + CL_GS * 4 - 1) / (CL_GS * 4);
-#define RALM_CL(NCHV)                                                                                      \
-    hipLaunchKernelGGL((cache_lookup_kernel<EX, NCHV>), dim3((unsigned)R), dim3(256), smem, stream,        \
-                       cache_ids, cache_len, C, queries, Qt, q_offsets, exact, ld, N, d, qgroup, spec_ids, \
+    // a lane keeps its NCH chunks in registers, which bounds the waves a block can hold
+#define RALM_CL(NCHV, NWV)                                                                                  \
+    hipLaunchKernelGGL((cache_lookup_kernel<EX, NCHV, NWV>), dim3((unsigned)R), dim3(NWV * 64),             \
+                       (size_t)qgroup * d * 4 + (size_t)NWV * CL_ROWS * qgroup * sizeof(u64), stream,       \
+                       cache_ids, cache_len, C, queries, Qt, q_offsets, exact, ld, N, d, qgroup, spec_ids,  \
                        spec_scores)
-    if (nch <= 4) RALM_CL(4);
-    else if (nch <= 8) RALM_CL(8);
-    else if (nch <= 12) RALM_CL(12);
-    else if (nch <= 16) RALM_CL(16);
-    else if (nch <= 32) RALM_CL(32);
+    if (nch <= 4) RALM_CL(4, 16);
+    else if (nch <= 8) RALM_CL(8, 16);
+    else if (nch <= 12) RALM_CL(12, 16);
+    else if (nch <= 16) RALM_CL(16, 8);
+    else if (nch <= 32) RALM_CL(32, 4);
     else return hipErrorInvalidValue;
 #undef RALM_CL
     return hipGetLastError();

@@ -15,33 +15,24 @@ namespace ralm {
 
 namespace {
 
-// inclusive prefix sum over the 256 threads of a block
-__device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t x, uint32_t *wave_tot /*[4] LDS*/)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        uint32_t y = __shfl_up(x, o, 64);
-        if (lane >= o) x += y;
-    }
-    if (lane == 63) wave_tot[wave] = x;
-    __syncthreads();
-    uint32_t add = 0;
-    for (int w = 0; w < wave; ++w) add += wave_tot[w];
-    __syncthreads();
-    return x + add;
-}
+constexpr int SEL_THREADS = 1024;
 
-__global__ __launch_bounds__(256) void select_kernel(u64 *__restrict__ cand, uint32_t *__restrict__ cnt,
-                                                     uint32_t cap, int k_prime, u64 *__restrict__ tau,
-                                                     u64 *__restrict__ tmp, int32_t *__restrict__ overflow_count)
+// Exact k'-th best key of a list by a radix descent, 8 bits of the key per pass, from the top.
+// A pass histograms the digit of the keys that match the prefix found so far; wave 0 walks the
+// 256 bins from the best digit down to the one that holds the k'-th key.  As soon as that bin
+// holds a single key the descent stops and one more pass over the list fetches that key
+// (scores are mostly distinct, so this usually happens before the id bits are reached).
+__global__ __launch_bounds__(SEL_THREADS) void select_kernel(u64 *__restrict__ cand, uint32_t *__restrict__ cnt,
+                                                             uint32_t cap, int k_prime, u64 *__restrict__ tau,
+                                                             u64 *__restrict__ tmp,
+                                                             int32_t *__restrict__ overflow_count)
 {
     __shared__ uint32_t hist[256];
-    __shared__ uint32_t wave_tot[4];
-    __shared__ uint32_t s_digit, s_remaining, s_out;
+    __shared__ uint32_t s_digit, s_remaining, s_bin, s_out;
+    __shared__ u64 s_kth;
 
     const int64_t q = blockIdx.x;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
     const uint32_t n = cnt[q];
     u64 *c = cand + q * (int64_t)cap;
 
@@ -61,34 +52,65 @@ __global__ __launch_bounds__(256) void select_kernel(u64 *__restrict__ cand, uin
 
     u64 prefix = 0, mask = 0;
     uint32_t remaining = (uint32_t)k_prime;
+    bool single = false;
     for (int shift = 56; shift >= 0; shift -= 8) {
-        hist[tid] = 0;
+        if (tid < 256) hist[tid] = 0;
         __syncthreads();
-        for (uint32_t i = tid; i < n; i += 256) {
+        for (uint32_t i = tid; i < n; i += SEL_THREADS) {
             const u64 key = c[i];
             if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
         }
         __syncthreads();
-        // thread t looks at digit 255 - t: walk digits from the best downwards
-        const uint32_t h = hist[255 - tid];
-        const uint32_t incl = block_inclusive_scan(h, wave_tot);
-        if (incl >= remaining && incl - h < remaining) {
-            s_digit = 255 - tid;
-            s_remaining = remaining - (incl - h);
+        if (tid < 64) {
+            // lane l owns digits 255-4l .. 252-4l, best first
+            uint32_t h[4], tot = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                h[j] = hist[255 - 4 * lane - j];
+                tot += h[j];
+            }
+            uint32_t incl = tot;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t y = __shfl_up(incl, o, 64);
+                if (lane >= o) incl += y;
+            }
+            uint32_t run = incl - tot;   // keys in better digits than this lane's
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (run < remaining && run + h[j] >= remaining) {
+                    s_digit = 255 - 4 * lane - j;
+                    s_remaining = remaining - run;
+                    s_bin = h[j];
+                }
+                run += h[j];
+            }
         }
         __syncthreads();
         prefix |= (u64)s_digit << shift;
         mask |= 0xffull << shift;
         remaining = s_remaining;
-        __syncthreads();
+        if (s_bin == 1) {
+            single = shift > 0;
+            break;
+        }
     }
-    const u64 kth = prefix;   // keys are distinct: exactly k' of them are >= kth
+    u64 kth = prefix;
+    if (single) {   // the only key under the prefix is the k'-th
+        for (uint32_t i = tid; i < n; i += SEL_THREADS) {
+            const u64 key = c[i];
+            if ((key & mask) == prefix) s_kth = key;
+        }
+        __syncthreads();
+        kth = s_kth;
+    }
+    // keys are distinct: exactly k' of them are >= kth
 
     // cut the list down to those k' keys, in place (via tmp)
     if (tid == 0) s_out = 0;
     __syncthreads();
     u64 *t = tmp + q * (int64_t)k_prime;
-    for (uint32_t i = tid; i < n; i += 256) {
+    for (uint32_t i = tid; i < n; i += SEL_THREADS) {
         const u64 key = c[i];
         if (key >= kth) {
             const uint32_t at = atomicAdd(&s_out, 1u);
@@ -96,7 +118,7 @@ __global__ __launch_bounds__(256) void select_kernel(u64 *__restrict__ cand, uin
         }
     }
     __syncthreads();
-    for (int i = tid; i < k_prime; i += 256) c[i] = t[i];
+    for (int i = tid; i < k_prime; i += SEL_THREADS) c[i] = t[i];
     if (tid == 0) {
         tau[q] = kth;
         cnt[q] = (uint32_t)k_prime;
@@ -110,8 +132,10 @@ __device__ __forceinline__ double wave_sum(double x)
     return x;
 }
 
+constexpr int RS_THREADS = 1024, RS_WAVES = RS_THREADS / 64;
+
 template <int EX>   // DT_F32 or DT_F16 exact rows
-__global__ __launch_bounds__(256) void rescore_kernel(const u64 *__restrict__ cand,
+__global__ __launch_bounds__(RS_THREADS) void rescore_kernel(const u64 *__restrict__ cand,
                                                       const uint32_t *__restrict__ cnt, uint32_t cap,
                                                       int k_prime, int kp2, const float *__restrict__ queries,
                                                       const void *__restrict__ exact, int64_t ld, int d,
@@ -121,7 +145,7 @@ __global__ __launch_bounds__(256) void rescore_kernel(const u64 *__restrict__ ca
 {
     extern __shared__ __align__(16) unsigned char smem[];
     u64 *keys = reinterpret_cast<u64 *>(smem);   // [kp2]
-    __shared__ u64 s_min_scan[4];
+    __shared__ u64 s_min_scan[RS_WAVES];
 
     const int64_t q = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -132,7 +156,7 @@ __global__ __launch_bounds__(256) void rescore_kernel(const u64 *__restrict__ ca
     const float *qv = queries + q * (int64_t)d;
 
     u64 min_scan = ~0ull;
-    for (int c = wave; c < n; c += 4) {
+    for (int c = wave; c < n; c += RS_WAVES) {
         const u64 skey = mine[c];
         min_scan = skey < min_scan ? skey : min_scan;
         const int32_t id = key_id(skey);
@@ -166,14 +190,14 @@ __global__ __launch_bounds__(256) void rescore_kernel(const u64 *__restrict__ ca
         sum = wave_sum(sum);
         if (lane == 0) keys[c] = make_key((float)sum, id);
     }
-    for (int c = n + tid; c < kp2; c += 256) keys[c] = 0ull;
+    for (int c = n + tid; c < kp2; c += RS_THREADS) keys[c] = 0ull;
     if (lane == 0) s_min_scan[wave] = min_scan;
     __syncthreads();
 
     // bitonic sort, descending by key
     for (int size = 2; size <= kp2; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int t = tid; t < kp2 / 2; t += 256) {
+            for (int t = tid; t < kp2 / 2; t += RS_THREADS) {
                 const int lo = 2 * t - (t & (stride - 1));
                 const int hi = lo + stride;
                 const bool desc = (lo & size) == 0;
@@ -187,7 +211,7 @@ __global__ __launch_bounds__(256) void rescore_kernel(const u64 *__restrict__ ca
         }
     }
 
-    for (int r = tid; r < k; r += 256) {
+    for (int r = tid; r < k; r += RS_THREADS) {
         const u64 key = keys[r];
         const bool have = r < n;
         out_ids[q * k + r] = have ? key_id(key) : -1;
@@ -195,7 +219,7 @@ __global__ __launch_bounds__(256) void rescore_kernel(const u64 *__restrict__ ca
     }
     if (out_margin && tid == 0) {
         u64 ms = s_min_scan[0];
-        for (int w = 1; w < 4; ++w) ms = s_min_scan[w] < ms ? s_min_scan[w] : ms;
+        for (int w = 1; w < RS_WAVES; ++w) ms = s_min_scan[w] < ms ? s_min_scan[w] : ms;
         float margin;
         if (overflow || n < k)
             margin = __builtin_nanf("");
@@ -213,7 +237,7 @@ hipError_t launch_select(u64 *cand, uint32_t *cnt, uint32_t cap, int32_t k_prime
                          int32_t *overflow_count, hipStream_t stream)
 {
     if (Q <= 0) return hipSuccess;
-    hipLaunchKernelGGL(select_kernel, dim3((unsigned)Q), dim3(256), 0, stream, cand, cnt, cap, k_prime, tau, tmp,
+    hipLaunchKernelGGL(select_kernel, dim3((unsigned)Q), dim3(SEL_THREADS), 0, stream, cand, cnt, cap, k_prime, tau, tmp,
                        overflow_count);
     return hipGetLastError();
 }
@@ -227,10 +251,10 @@ hipError_t launch_rescore(const u64 *cand, const uint32_t *cnt, uint32_t cap, in
     while (kp2 < k_prime) kp2 <<= 1;
     const size_t smem = (size_t)kp2 * sizeof(u64);
     if (exact_dtype == DT_F16)
-        hipLaunchKernelGGL(rescore_kernel<DT_F16>, dim3((unsigned)Q), dim3(256), smem, stream, cand, cnt, cap,
+        hipLaunchKernelGGL(rescore_kernel<DT_F16>, dim3((unsigned)Q), dim3(RS_THREADS), smem, stream, cand, cnt, cap,
                            k_prime, kp2, queries, exact, ld, d, k, out_ids, out_scores, out_margin);
     else
-        hipLaunchKernelGGL(rescore_kernel<DT_F32>, dim3((unsigned)Q), dim3(256), smem, stream, cand, cnt, cap,
+        hipLaunchKernelGGL(rescore_kernel<DT_F32>, dim3((unsigned)Q), dim3(RS_THREADS), smem, stream, cand, cnt, cap,
                            k_prime, kp2, queries, exact, ld, d, k, out_ids, out_scores, out_margin);
     return hipGetLastError();
 }
