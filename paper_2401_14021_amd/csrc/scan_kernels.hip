@@ -367,6 +367,8 @@ __device__ __forceinline__ void wait_vmcnt()
 }
 
 constexpr int TAU_LDS_MAX_Q = 2560;   // admission keys of up to this many queries are kept in LDS
+// ... by the widest query tile; the narrower tiles serve only batches of at most one tile
+constexpr int tau_lds_q(int BN) { return BN <= 128 ? BN : TAU_LDS_MAX_Q; }
 constexpr int PARK_CAP = 672;         // parked admitted scores per workgroup (12 bytes each)
 
 #define RALM_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -393,14 +395,14 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     constexpr int LAG = NM > 2 ? 2 : NM - 1;     // selection runs this many MFMAs behind
     constexpr int RV = NR - 1;                   // k-step 0 slot after which the stage rendezvous sits
     static_assert((NW == 4 || NW == 8) && BM == SCAN_BM && NA >= 1 && NB >= 1, "tile shape");
-    static_assert(S >= 3 && S <= 4 && KS % 2 == 0, "ring depth / k-steps per stage");
+    static_assert(S >= 3 && KS % 2 == 0, "ring depth / k-steps per stage");
     static_assert(LPS * (S - 2) < 64, "vmcnt range");
 
     extern __shared__ __align__(16) unsigned char smem[];
     const uint32_t lds0 = (uint32_t)(size_t)(RALM_LDS unsigned char *)smem;
     RALM_LDS u64 *tau_lds = (RALM_LDS u64 *)(smem + S * STAGE);
     PushList pl;
-    pl.keys = tau_lds + TAU_LDS_MAX_Q;
+    pl.keys = tau_lds + tau_lds_q(BN);
     pl.qs = (RALM_LDS uint32_t *)(pl.keys + PARK_CAP);
     pl.count = pl.qs + PARK_CAP;
     pl.cap = PARK_CAP;
@@ -675,10 +677,10 @@ hipError_t launch_dma_variant(const ScanParams &p, int n_cu, hipStream_t stream)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t ring = (size_t)S * (BM + BN) * BK * 2;
-    constexpr size_t smem = ring + (size_t)TAU_LDS_MAX_Q * 8 + (size_t)PARK_CAP * 12 + 16 + WM * WN * SLOW_SLOTS * 64;
+    constexpr size_t smem = ring + (size_t)tau_lds_q(BN) * 8 + (size_t)PARK_CAP * 12 + 16 + WM * WN * SLOW_SLOTS * 64;
     static_assert(smem <= 160 * 1024, "LDS budget");
     auto kern = scan_dma_kernel<F16, WM, WN, TM, TN, BK, S>;
-    const int tau_in_lds = p.Q <= TAU_LDS_MAX_Q ? 1 : 0;
+    const int tau_in_lds = p.Q <= tau_lds_q(BN) ? 1 : 0;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -703,9 +705,9 @@ hipError_t launch_dma(const ScanParams &p, int n_cu, hipStream_t stream)
 {
     const int bn = scan_bn_for(p.Q);
     switch (bn) {
-        case 32: return launch_dma_variant<F16, 4, 1, 2, 1, 64, 3>(p, n_cu, stream);
-        case 64: return launch_dma_variant<F16, 4, 1, 2, 2, 64, 3>(p, n_cu, stream);
-        case 128: return launch_dma_variant<F16, 2, 2, 4, 2, 32, 4>(p, n_cu, stream);
+        case 32: return launch_dma_variant<F16, 4, 1, 2, 1, 64, 4>(p, n_cu, stream);
+        case 64: return launch_dma_variant<F16, 4, 1, 2, 2, 32, 7>(p, n_cu, stream);
+        case 128: return launch_dma_variant<F16, 2, 2, 4, 2, 32, 6>(p, n_cu, stream);
         default: return launch_dma_variant<F16, 2, 4, 4, 2, 32, 4>(p, n_cu, stream);
     }
 }
