@@ -93,7 +93,9 @@ typedef struct {
  *              ranked best first.
  *
  * Runs on the default stream, allocates and frees its own workspace, and
- * synchronises before returning (so RALM_ERR_OVERFLOW can be reported).
+ * synchronises before returning.  If a candidate list overflows (see
+ * ralm_retrieve_topk_ex) the call is redone by ralm_retrieve_topk_seq, so the
+ * result is exact for rows in any order.
  */
 ralm_status ralm_retrieve_topk(const float *queries, int64_t Q, const float *datastore, int64_t N,
                                int32_t d, int32_t k, int32_t *out_ids, float *out_scores);
@@ -122,10 +124,14 @@ size_t ralm_workspace_bytes(int64_t Q, const ralm_datastore_t *ds, int32_t k, in
  *               in time must not share it.
  *   stream      hipStream_t
  *
- * Does not synchronise.  If the thresholded candidate buffer of some query
- * overflows (only for inputs with enormous numbers of equal scores, or rows
- * ordered adversarially), that query's outputs are set to id -1 / score NaN
- * and the overflow is counted; read it with ralm_workspace_overflows().
+ * The rows are visited in a fixed strided order, coarse samples first, and a
+ * query's candidate list (a fixed number of slots in the workspace) takes only
+ * scores that beat the k'-th best of the rows visited before.  Does not
+ * synchronise.  If the list of some query overflows (only when the order of
+ * the rows is correlated with that stride pattern, e.g. every other 256-row
+ * tile holding the best matches), that query's outputs are set to id -1 /
+ * score NaN and the overflow is counted; read it with
+ * ralm_workspace_overflows() and redo the call with ralm_retrieve_topk_seq.
  */
 ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_datastore_t *ds,
                                   int32_t k, int32_t k_prime, int32_t *out_ids, float *out_scores,
@@ -133,7 +139,19 @@ ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_da
                                   void *stream);
 
 /*
- * Number of queries of the LAST ralm_retrieve_topk_ex call on this workspace
+ * Same arguments, same result as ralm_retrieve_topk_ex, computed block by
+ * block over consecutive rows: every block is small enough that a list holds
+ * its k' best so far plus every row of the block, so no list can overflow
+ * whatever the order of the rows.  About N / 16000 small launches instead of a
+ * dozen large ones (21M rows: ~50 ms); meant as the retry after an overflow.
+ */
+ralm_status ralm_retrieve_topk_seq(const float *queries, int64_t Q, const ralm_datastore_t *ds,
+                                   int32_t k, int32_t k_prime, int32_t *out_ids, float *out_scores,
+                                   float *out_margin, void *workspace, size_t workspace_bytes,
+                                   void *stream);
+
+/*
+ * Number of queries of the LAST ralm_retrieve_topk_ex / _seq call on this workspace
  * whose candidate buffer overflowed.  Synchronises `stream` and copies one
  * int to the host (*count is a host pointer).
  */
@@ -193,11 +211,12 @@ ralm_status ralm_verify(const int32_t *spec_ids, const int32_t *true_ids, int64_
 
 /*
  * Timing aid for benchmarks.  While enabled, ralm_retrieve_topk_ex brackets
- * each launch of its full-datastore scan pass (one launch, or four segment
- * launches for large batches) with HIP events on the call's stream.
- * ralm_profile_scan_ms synchronises those events and returns the total
- * milliseconds and the number of bracketed launches since the last reset
- * (host pointers), then resets.  Not thread-safe; off by default.
+ * each launch of its scan kernel (a call makes several: together they read
+ * every row of the datastore exactly once) with HIP events on the call's
+ * stream.  ralm_profile_scan_ms synchronises those events and returns the
+ * total milliseconds and the number of bracketed launches since the last
+ * reset (host pointers), then resets.  At most 2048 launches are recorded
+ * between resets.  Not thread-safe; off by default.
  */
 void ralm_profile_enable(int32_t on);
 ralm_status ralm_profile_scan_ms(float *total_ms, int32_t *launches);

@@ -56,6 +56,7 @@ def lib() -> ctypes.CDLL:
         L.ralm_workspace_bytes.argtypes = [i64, dsp, i32, i32]
         L.ralm_workspace_bytes.restype = ctypes.c_size_t
         L.ralm_retrieve_topk_ex.argtypes = [vp, i64, dsp, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ralm_retrieve_topk_seq.argtypes = L.ralm_retrieve_topk_ex.argtypes
         L.ralm_workspace_overflows.argtypes = [vp, vp, ctypes.POINTER(i32)]
         L.ralm_build_scan_copy.argtypes = [vp, i64, vp, i32, i64, i64, i32, vp]
         L.ralm_cache_lookup.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, vp, vp, vp]
@@ -63,7 +64,7 @@ def lib() -> ctypes.CDLL:
         L.ralm_profile_enable.argtypes = [i32]
         L.ralm_profile_enable.restype = None
         L.ralm_profile_scan_ms.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
-        for name in ("ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_workspace_overflows",
+        for name in ("ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_retrieve_topk_seq", "ralm_workspace_overflows",
                      "ralm_build_scan_copy", "ralm_cache_lookup", "ralm_verify", "ralm_profile_scan_ms"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -142,8 +143,9 @@ def _ws_view(ws: torch.Tensor) -> Tuple[int, int]:
 def ralm_retrieve_topk_ex(queries: torch.Tensor, ds: Datastore, k: int, k_prime: int = 0,
                           workspace: Optional[torch.Tensor] = None,
                           out_ids: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None,
-                          out_margin: Optional[torch.Tensor] = None
+                          out_margin: Optional[torch.Tensor] = None, sequential: bool = False
                           ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """sequential=True calls ralm_retrieve_topk_seq (same arguments, block-by-block ladder)."""
     assert queries.dtype == torch.float32 and queries.is_contiguous()
     Q = queries.shape[0]
     dev = queries.device
@@ -154,9 +156,9 @@ def ralm_retrieve_topk_ex(queries: torch.Tensor, ds: Datastore, k: int, k_prime:
     if out_scores is None:
         out_scores = torch.empty(Q, k, dtype=torch.float32, device=dev)
     ws_ptr, ws_bytes = _ws_view(workspace)
-    _check(lib().ralm_retrieve_topk_ex(queries.data_ptr(), Q, ctypes.byref(ds.desc), k, k_prime,
-                                       out_ids.data_ptr(), out_scores.data_ptr(), _ptr(out_margin),
-                                       ws_ptr, ws_bytes, _stream()))
+    fn = lib().ralm_retrieve_topk_seq if sequential else lib().ralm_retrieve_topk_ex
+    _check(fn(queries.data_ptr(), Q, ctypes.byref(ds.desc), k, k_prime, out_ids.data_ptr(), out_scores.data_ptr(),
+              _ptr(out_margin), ws_ptr, ws_bytes, _stream()))
     return out_ids, out_scores
 
 

@@ -178,9 +178,17 @@ size_t ralm_workspace_bytes(int64_t Q, const ralm_datastore_t *ds, int32_t k, in
     return pl.total;
 }
 
-ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_datastore_t *ds, int32_t k,
-                                  int32_t k_prime, int32_t *out_ids, float *out_scores, float *out_margin,
-                                  void *workspace, size_t workspace_bytes, void *stream_)
+}  // extern "C"
+
+namespace {
+
+// sequential == false: the strided ladder described at the top of this file.
+// sequential == true: consecutive blocks of tiles, each small enough that a list holds its k'
+// best so far plus every row of the block, so that no list can overflow whatever the order of
+// the rows; about N / cap launches.
+ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_t *ds, int32_t k, int32_t k_prime,
+                          int32_t *out_ids, float *out_scores, float *out_margin, void *workspace,
+                          size_t workspace_bytes, void *stream_, bool sequential)
 {
     if (!queries || !out_ids || !out_scores) return fail(RALM_ERR_NULL, "queries/out_ids/out_scores is NULL");
     if (Q < 1 || Q > (1 << 20)) return fail(RALM_ERR_SHAPE, "Q=%lld out of [1, 2^20]", (long long)Q);
@@ -214,28 +222,15 @@ ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_da
     RALM_HIP(launch_query_prep(queries, Q, ds->d, qs, pl.Qpad, pl.dpad, mma_dt, stream));
     RALM_HIP(launch_fill_u64(tau, 0ull, pl.Qpad, stream));
     RALM_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(flags), 0u, 64, stream));
-
-    const int64_t tiles = (ds->N + SCAN_BM - 1) / SCAN_BM;
     RALM_HIP(launch_fill_u32(cnt, 0u, pl.Qpad, stream));
-    for (int s = 0; s < pl.n_stages; ++s) {
-        const int64_t stride = pl.stride[s];
-        ScanParams sp;
-        sp.X = scan; sp.ldx = scan_ld; sp.N = ds->N; sp.d = ds->d; sp.in_dtype = scan_dt;
-        sp.Qs = qs; sp.dpad = pl.dpad; sp.Q = (int32_t)Q;
-        sp.tau = tau; sp.cand = cand; sp.cnt = cnt; sp.cap = pl.cap;
-        sp.tile_stride = stride;
-        if (s == 0) {
-            sp.tile_skip = 0;                                   // every multiple of the stride
-            sp.n_row_tiles = (tiles + stride - 1) / stride;
-            sp.park_pushes = 0;                                 // admits everything
-        } else {
-            const int64_t m_max = (tiles + stride - 1) / stride - 1;   // multiples m >= 1 with m*stride < tiles
-            const int64_t g = pl.stride[s - 1] / stride;        // ... that no earlier stage visited
-            sp.tile_skip = (int32_t)g;
-            sp.n_row_tiles = m_max - m_max / g;
-            sp.park_pushes = 1;
-        }
-        if (sp.n_row_tiles <= 0) continue;
+
+    ScanParams sp;
+    sp.X = scan; sp.ldx = scan_ld; sp.N = ds->N; sp.d = ds->d; sp.in_dtype = scan_dt;
+    sp.Qs = qs; sp.dpad = pl.dpad; sp.Q = (int32_t)Q;
+    sp.tau = tau; sp.cand = cand; sp.cnt = cnt; sp.cap = pl.cap;
+    // one stage: scan the tiles sp describes, then cut every list down to its k' best
+    auto run_stage = [&]() -> ralm_status {
+        if (sp.n_row_tiles <= 0) return RALM_OK;
         const bool prof = g_prof_on && g_prof_n < MAX_PROF;
         if (prof) {
             while (g_prof_made <= g_prof_n) {
@@ -251,11 +246,65 @@ ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_da
             ++g_prof_n;
         }
         RALM_HIP(launch_select(cand, cnt, pl.cap, pl.k_prime, Q, tau, sel, flags, stream));
+        return RALM_OK;
+    };
+
+    const int64_t tiles = (ds->N + SCAN_BM - 1) / SCAN_BM;
+    if (sequential) {
+        const int64_t block = ((int64_t)pl.cap - pl.k_prime) / SCAN_BM;   // >= 1: cap >= 16384, k' <= 4096
+        sp.tile_stride = 1;
+        sp.tile_skip = 0;
+        sp.park_pushes = 0;
+        for (int64_t t0 = 0; t0 < tiles; t0 += block) {
+            sp.tile_begin = t0;
+            sp.n_row_tiles = tiles - t0 < block ? tiles - t0 : block;
+            st = run_stage();
+            if (st != RALM_OK) return st;
+        }
+    } else {
+        sp.tile_begin = 0;
+        for (int s = 0; s < pl.n_stages; ++s) {
+            const int64_t stride = pl.stride[s];
+            sp.tile_stride = stride;
+            if (s == 0) {
+                sp.tile_skip = 0;                                   // every multiple of the stride
+                sp.n_row_tiles = (tiles + stride - 1) / stride;
+                sp.park_pushes = 0;                                 // admits everything
+            } else {
+                const int64_t m_max = (tiles + stride - 1) / stride - 1;   // multiples m >= 1 with m*stride < tiles
+                const int64_t g = pl.stride[s - 1] / stride;        // ... that no earlier stage visited
+                sp.tile_skip = (int32_t)g;
+                sp.n_row_tiles = m_max - m_max / g;
+                sp.park_pushes = 1;
+            }
+            st = run_stage();
+            if (st != RALM_OK) return st;
+        }
     }
     const int64_t exact_ld = ds->exact_stride ? ds->exact_stride : ds->d;
     RALM_HIP(launch_rescore(cand, cnt, pl.cap, pl.k_prime, queries, Q, ds->exact, ds->exact_dtype, exact_ld, ds->d, k,
                             out_ids, out_scores, out_margin, stream));
     return RALM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_datastore_t *ds, int32_t k,
+                                  int32_t k_prime, int32_t *out_ids, float *out_scores, float *out_margin,
+                                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    return retrieve_impl(queries, Q, ds, k, k_prime, out_ids, out_scores, out_margin, workspace, workspace_bytes,
+                         stream, false);
+}
+
+ralm_status ralm_retrieve_topk_seq(const float *queries, int64_t Q, const ralm_datastore_t *ds, int32_t k,
+                                   int32_t k_prime, int32_t *out_ids, float *out_scores, float *out_margin,
+                                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    return retrieve_impl(queries, Q, ds, k, k_prime, out_ids, out_scores, out_margin, workspace, workspace_bytes,
+                         stream, true);
 }
 
 ralm_status ralm_workspace_overflows(const void *workspace, void *stream_, int32_t *count)
@@ -289,6 +338,11 @@ ralm_status ralm_retrieve_topk(const float *queries, int64_t Q, const float *dat
     st = ralm_retrieve_topk_ex(queries, Q, &ds, k, 0, out_ids, out_scores, nullptr, ws, pl.total, nullptr);
     int32_t overflows = 0;
     if (st == RALM_OK) st = ralm_workspace_overflows(ws, nullptr, &overflows);
+    if (st == RALM_OK && overflows > 0) {
+        // rows in an order that defeats the strided samples: redo the call block by block
+        st = ralm_retrieve_topk_seq(queries, Q, &ds, k, 0, out_ids, out_scores, nullptr, ws, pl.total, nullptr);
+        if (st == RALM_OK) st = ralm_workspace_overflows(ws, nullptr, &overflows);
+    }
     hipError_t e = hipFree(ws);
     if (st == RALM_OK && e != hipSuccess) return fail(RALM_ERR_DEVICE, "hipFree failed: %s", hipGetErrorString(e));
     if (st == RALM_OK && overflows > 0)

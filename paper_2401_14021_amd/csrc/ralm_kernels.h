@@ -26,8 +26,9 @@ struct ScanParams {
     uint32_t *cnt;          // [Q]
     uint32_t cap;
     int64_t n_row_tiles;    // tiles visited in this stage
-    int64_t tile_stride;    // visited tile t is datastore tile m(t) * tile_stride, where m(t) = t if
-    int32_t tile_skip;      // tile_skip == 0, else the t-th positive integer that is no multiple of tile_skip
+    int64_t tile_stride;    // visited tile t is datastore tile (tile_begin + m(t)) * tile_stride, where m(t) = t
+    int32_t tile_skip;      // if tile_skip == 0, else the t-th positive integer that is no multiple of tile_skip
+    int64_t tile_begin;
     int32_t park_pushes;    // 1: thresholds are selective, collect admitted scores in LDS first
 };
 

@@ -93,7 +93,7 @@ __device__ __forceinline__ int64_t visited_tile(const ScanParams &p, int64_t t)
         const int64_t g1 = p.tile_skip - 1;
         t = (t / g1) * p.tile_skip + t % g1 + 1;
     }
-    return t * p.tile_stride;
+    return (p.tile_begin + t) * p.tile_stride;
 }
 
 // acc[i][j][v] of a wave is the score of datastore row

@@ -149,6 +149,58 @@ def test_tile_admitting_more_than_the_parking_list(B, oracle, Q):
     assert ids[1].tolist() == list(range(20000, 20020))
 
 
+def _rows_against_the_strides(N=200000, d=32):
+    """The rows of the 256-row tiles whose index is a prime above 64 outscore all others for the
+    test queries.  No strided sample (stride > 1, at most 64) contains such a tile, so the ladder
+    meets them only in its last stage, whose admission key then comes from the other tiles and
+    lets all of their ~30000 rows through: more than a candidate list holds."""
+    g = torch.Generator().manual_seed(29)
+    j = torch.arange(N)
+    t = np.arange((N + 255) // 256)
+    prime = np.array([ti > 64 and all(ti % p for p in range(2, int(ti ** 0.5) + 1)) for ti in t])
+    best = torch.from_numpy(prime)[j // 256].float()
+    assert int(best.sum()) > 20000
+    X = torch.randint(-1, 2, (N, d), generator=g).float()
+    X[:, 0] = 8 * best + (j % 7).float() * 0.25          # exact in bf16; 7 values: ties everywhere
+    Qm = torch.zeros(3, d)
+    Qm[0, 0] = 1
+    Qm[1, 0] = 2
+    Qm[2, 0] = 1
+    Qm[2, 1] = 0.5
+    return X, Qm
+
+
+def test_list_overflow_is_flagged_and_the_sequential_ladder_is_exact(B, oracle):
+    X, Qm = _rows_against_the_strides()
+    k = 20
+    ds = B.Datastore.from_fp32(X.cuda())
+    qd = Qm.cuda()
+    ws = B.alloc_workspace(3, ds, k)
+    ids, sc = B.ralm_retrieve_topk_ex(qd, ds, k, workspace=ws)
+    assert B.ralm_workspace_overflows(ws) == 3
+    assert bool((ids == -1).all()) and bool(torch.isnan(sc).all())
+    wi, wsc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), k)
+    ids, sc = B.ralm_retrieve_topk_ex(qd, ds, k, workspace=ws, sequential=True)
+    assert B.ralm_workspace_overflows(ws) == 0
+    assert np.array_equal(ids.cpu().numpy(), wi) and np.array_equal(sc.cpu().numpy(), wsc)
+    # the simple form retries by itself
+    ids, sc = B.ralm_retrieve_topk(qd, X.cuda(), k)
+    assert np.array_equal(ids.cpu().numpy(), wi) and np.array_equal(sc.cpu().numpy(), wsc)
+
+
+@pytest.mark.parametrize("Q,k", [(4, 20), (150, 100)])
+def test_sequential_ladder_equals_the_strided_one(B, oracle, Q, k):
+    from paper_2401_14021_amd import inputs
+    X, _ = inputs.clustered_datastore(70001, 136, 64, seed=31)
+    Qm = inputs.queries_near_rows(X, inputs.pick_rows(70001, Q, seed=5), seed=6)
+    ds = B.Datastore.from_fp32(X.cuda())
+    a_ids, a_sc = B.ralm_retrieve_topk_ex(Qm.cuda(), ds, k)
+    b_ids, b_sc = B.ralm_retrieve_topk_ex(Qm.cuda(), ds, k, sequential=True)
+    assert torch.equal(a_ids, b_ids) and torch.equal(a_sc, b_sc)
+    wi, wsc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), k)
+    check_topk(b_ids.cpu().numpy(), b_sc.cpu().numpy(), wi, wsc, _score_fn(oracle, Qm.numpy(), X.numpy()))
+
+
 def test_batched_equals_sequential_and_is_deterministic(B, oracle):
     """A query's result does not depend on what else is in the batch (the property that makes
     batched verification output-preserving), nor on the run."""
