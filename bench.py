@@ -128,10 +128,10 @@ def main():
         dt = time.perf_counter() - t
         scan_ms, launches = B.ralm_profile_scan_ms()
         B.ralm_profile_enable(False)
-        assert launches > 0 and launches % steps == 0     # the full-datastore pass may be 1 or 4 launches
+        assert launches > 0 and launches % steps == 0     # one datastore pass = the ladder's 3..7 scan launches
         assert B.ralm_workspace_overflows(b["ws"]) == 0, "candidate buffer overflow"
         ms = dt / steps * 1e3
-        scan = scan_ms / steps                            # all launches of one full-datastore pass
+        scan = scan_ms / steps                            # all scan launches of one call: every row read once
         bytes_scan = N * w.d * 2
         flops = 2.0 * b["Q"] * N * w.d
         hit = float((b["spec"] == b["ids"][:, 0]).float().mean().item())
@@ -154,7 +154,7 @@ def main():
     else:
         roof = {"bound": "mfma", "achieved": round(head["scan_TFLOPs"], 1), "peak": MFMA_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(head["scan_TFLOPs"] / MFMA_PEAK_TFLOPS, 4), "traffic": None}
-    roof["kernel"] = "scan kernel, full-datastore pass (sum of its launches)"
+    roof["kernel"] = "scan kernel, one pass over the datastore (sum of the call's scan launches)"
     roof["kernel_ms"] = round(head["scan_ms"], 4)
     roof["algorithmic_bytes"] = N * w.d * 2
     roof["algorithmic_flops"] = 2.0 * head["Q"] * N * w.d

@@ -4,7 +4,7 @@
       <dir> holds *_kernel_trace.csv from `rocprofv3 --kernel-trace --stats --output-format csv`.
       Prints per-kernel call counts and average durations; launches of the scan kernels are
       grouped into duration classes, because one retrieval call launches the same kernel
-      several times (sampling stages, then the full datastore in one or four segments).
+      several times (the stages of its ladder, which differ in size by the growth factors).
 
   python -m paper_2401_14021_amd.prof_summary pmc <dir>
       <dir> holds *_counter_collection.csv from `rocprofv3 --pmc ... --output-format csv`.
