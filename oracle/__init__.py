@@ -51,6 +51,8 @@ def _load():
         L.ralm_oracle_cache_lookup.restype = ctypes.c_int
         L.ralm_oracle_verify.argtypes = [vp, vp, i64, vp, i64, vp]
         L.ralm_oracle_verify.restype = None
+        L.ralm_oracle_cache_insert.argtypes = [vp, vp, vp, i32, i64, vp, i64, vp, vp, i32, i32, i64]
+        L.ralm_oracle_cache_insert.restype = None
         _lib = L
     return _lib
 
@@ -168,3 +170,26 @@ def verify(spec_ids: np.ndarray, true_ids: np.ndarray, q_offsets: np.ndarray,
     out = np.empty(R, dtype=np.int32)
     _load().ralm_oracle_verify(_ptr(spec_ids), _ptr(true_ids), true_stride, _ptr(q_offsets), R, _ptr(out))
     return out
+
+
+def cache_insert(cache_ids: np.ndarray, cache_len: np.ndarray, cache_head: np.ndarray,
+                 true_ids: np.ndarray, q_offsets: np.ndarray, N: int, p: int = 1, n_next: int = 0,
+                 first_mismatch=None, true_stride: int = None):
+    """Cache update after a verification step; returns new (cache_ids, cache_len, cache_head).
+
+    ``true_ids`` is [Qt, k] (or flat with ``true_stride``); ranks 0..p-1 of every taken step are
+    inserted (their n_next successors instead when n_next > 0)."""
+    cache_ids = np.array(cache_ids, dtype=np.int32, order="C", copy=True)
+    cache_len = np.array(cache_len, dtype=np.int32, copy=True)
+    cache_head = np.array(cache_head, dtype=np.int32, copy=True)
+    R, C = cache_ids.shape
+    true_ids = np.ascontiguousarray(true_ids, dtype=np.int32)
+    if true_stride is None:
+        true_stride = true_ids.shape[1] if true_ids.ndim == 2 else 1
+    assert 1 <= p <= true_stride
+    q_offsets = np.ascontiguousarray(q_offsets, dtype=np.int64)
+    assert q_offsets.shape[0] == R + 1
+    fm = None if first_mismatch is None else np.ascontiguousarray(first_mismatch, dtype=np.int32)
+    _load().ralm_oracle_cache_insert(_ptr(cache_ids), _ptr(cache_len), _ptr(cache_head), C, R, _ptr(true_ids),
+                                     true_stride, _ptr(q_offsets), None if fm is None else _ptr(fm), p, n_next, N)
+    return cache_ids, cache_len, cache_head

@@ -16,6 +16,10 @@
  *    same metric, restricted to the entries of the request's local cache
  *    (Section 3, "Speculative retrieval", and the caption of Fig. 2), top-1.
  *  - the verification compare m = argmin_i (d^_i != d_i) of Alg. 1, per request.
+ *  - the cache update Q.insert(C.retrieve(..)) of Alg. 1: the documents that a
+ *    verification step retrieved go into the request's local cache (Section 3,
+ *    "Batched verification": top-1 update, or top-k update = prefetching,
+ *    Fig. 2; Section 5.3: for KNN-LM the next n entries after a retrieved one).
  *
  * Readings where the paper is silent:
  *  - metric: inner product (dense passage retrieval scores, raw inner product
@@ -26,7 +30,13 @@
  *    double, and the sum is rounded once to fp32.  Comparisons are made on
  *    that fp32 value;
  *  - first mismatch is reported 0-based, and equals the request's stride when
- *    every speculated id matches.
+ *    every speculated id matches;
+ *  - the paper's cache has no stated capacity; here it has C slots, an id that
+ *    is already cached is not inserted again, and when the slots are full the
+ *    oldest inserted id is overwritten (first in, first out).  Results of the
+ *    steps after the first mis-speculated one belong to a context that is
+ *    rolled back, so they are not inserted when the caller passes the first
+ *    mismatch.
  *
  * Threads (OpenMP, if compiled in) only split independent rows between cores;
  * no blocking, no reordering of any sum.
@@ -203,5 +213,59 @@ void ralm_oracle_verify(const int32_t *spec, const int32_t *truth, int64_t true_
             if (spec[at] != truth[at * true_stride]) { m = i; break; }
         }
         first_mismatch[r] = (int32_t)m;
+    }
+}
+
+/*
+ * Cache update after a verification step (Alg. 1, Q.insert; Section 3, "Batched
+ * verification": top-1 / top-k update; Section 5.3: next-n update for KNN-LM).
+ *
+ * Request r holds cache_len[r] ids in cache_ids[r*C ..]; cache_head[r] is the
+ * slot that the next insertion into a FULL cache overwrites.  The knowledge
+ * base returned truth[(q_offsets[r] + i) * true_stride + j] as the rank-j id of
+ * the request's step i.  Steps i = 0 .. n_r - 1 are taken, in order, where
+ * n_r = s_r, or min(first_mismatch[r] + 1, s_r) when first_mismatch is given
+ * (the steps up to and including the first mis-speculated one: Appendix A.2
+ * counts exactly these as verified).  Of each step the ranks j = 0 .. p-1 are
+ * taken, in order.  A taken id t stands for the candidates
+ *     t                       when n_next == 0   (the document itself)
+ *     t+1, t+2, .., t+n_next  when n_next > 0    (its successors in the datastore)
+ * Candidates outside [0, N) are dropped.  Each candidate, in that order: if it
+ * is in the cache now, nothing happens; else it is written to slot len (and
+ * len grows) while len < C, else to slot head, and head moves on cyclically.
+ */
+void ralm_oracle_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *cache_head, int32_t C,
+                              int64_t R, const int32_t *truth, int64_t true_stride,
+                              const int64_t *q_offsets, const int32_t *first_mismatch, int32_t p,
+                              int32_t n_next, int64_t N)
+{
+    for (int64_t r = 0; r < R; ++r) {
+        int32_t *c = cache_ids + r * (int64_t)C;
+        int32_t len = cache_len[r], head = cache_head[r];
+        int64_t s = q_offsets[r + 1] - q_offsets[r];
+        int64_t n = s;
+        if (first_mismatch && (int64_t)first_mismatch[r] + 1 < s) n = (int64_t)first_mismatch[r] + 1;
+        for (int64_t i = 0; i < n; ++i) {
+            for (int32_t j = 0; j < p; ++j) {
+                int64_t t = truth[(q_offsets[r] + i) * true_stride + j];
+                int32_t first = n_next > 0 ? 1 : 0, last = n_next > 0 ? n_next : 0;
+                for (int32_t o = first; o <= last; ++o) {
+                    int64_t e = t + o;
+                    if (t < 0 || e < 0 || e >= N) continue;
+                    int found = 0;
+                    for (int32_t x = 0; x < len; ++x)
+                        if (c[x] == (int32_t)e) { found = 1; break; }
+                    if (found) continue;
+                    if (len < C) {
+                        c[len++] = (int32_t)e;
+                    } else {
+                        c[head] = (int32_t)e;
+                        head = head + 1 == C ? 0 : head + 1;
+                    }
+                }
+            }
+        }
+        cache_len[r] = len;
+        cache_head[r] = head;
     }
 }

@@ -300,3 +300,122 @@ def test_clustered_generator_statistics():
     ids, lens = inputs.speculation_caches(20000, 3, 64, off, rows, assign, seed=5)
     assert ids.shape == (3, 64) and lens.tolist() == [64, 64, 64]
     assert int(ids.min()) >= 0 and int(ids.max()) < 20000
+
+
+# ----------------------------------------------------------------------------------------
+# cache update (Alg. 1, Q.insert)
+# ----------------------------------------------------------------------------------------
+def _read_insert_cases():
+    for line in open(os.path.join(GOLDEN, "cache_insert_hand.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, C, N, p, n_next, fm, init, truth, ids, ln, head = [f.strip() for f in line.split("|")]
+        steps = [[int(v) for v in st.split()] for st in truth.split(";")]
+        yield dict(name=name, C=int(C), N=int(N), p=int(p), n_next=int(n_next),
+                   fm=None if fm == "-" else int(fm), init=[int(v) for v in init.split()],
+                   truth=np.array(steps, dtype=np.int32), ids=[int(v) for v in ids.split()],
+                   len=int(ln), head=int(head))
+
+
+def test_cache_insert_hand_worked_cases(oracle):
+    n = 0
+    for c in _read_insert_cases():
+        cache = np.full((1, c["C"]), -1, dtype=np.int32)
+        cache[0, :len(c["init"])] = c["init"]
+        ids, ln, head = oracle.cache_insert(cache, [len(c["init"])], [0], c["truth"], [0, len(c["truth"])],
+                                            N=c["N"], p=c["p"], n_next=c["n_next"],
+                                            first_mismatch=None if c["fm"] is None else [c["fm"]])
+        assert ids[0, :ln[0]].tolist() == c["ids"] and ln[0] == c["len"] and head[0] == c["head"], c["name"]
+        n += 1
+    assert n == 5
+
+
+def _fifo_model(init_ids, init_head, C, candidates):
+    """Independent model of the same policy: a queue ordered by age plus a set."""
+    import collections
+    age = list(init_ids) if len(init_ids) < C else list(init_ids[init_head:]) + list(init_ids[:init_head])
+    fifo, member = collections.deque(age), set(age)
+    for e in candidates:
+        if e in member:
+            continue
+        if len(fifo) == C:
+            member.discard(fifo.popleft())
+        fifo.append(e)
+        member.add(e)
+    return list(fifo)
+
+
+def _age_order(ids, ln, head, C):
+    ids = list(ids[:ln])
+    return ids if ln < C else ids[head:] + ids[:head]
+
+
+def test_cache_insert_against_a_queue_model(oracle):
+    rng = np.random.default_rng(17)
+    for trial in range(300):
+        C = int(rng.integers(1, 12))
+        R = int(rng.integers(1, 4))
+        N = int(rng.integers(5, 40))
+        k = int(rng.integers(1, 5))
+        p = int(rng.integers(1, k + 1))
+        n_next = int(rng.integers(0, 4))
+        strides = rng.integers(0, 5, size=R)
+        off = np.concatenate([[0], np.cumsum(strides)]).astype(np.int64)
+        truth = rng.integers(0, N, size=(int(off[-1]), k)).astype(np.int32)
+        lens = rng.integers(0, C + 1, size=R).astype(np.int32)
+        heads = np.array([rng.integers(0, C) if l == C else 0 for l in lens], dtype=np.int32)
+        cache = np.full((R, C), -1, dtype=np.int32)
+        for r in range(R):
+            cache[r, :lens[r]] = rng.choice(N + 50, size=lens[r], replace=False)   # distinct, some >= N
+        fm = rng.integers(0, 6, size=R).astype(np.int32) if trial % 2 else None
+        ids, ln, head = oracle.cache_insert(cache, lens, heads, truth, off, N=N, p=p, n_next=n_next,
+                                            first_mismatch=fm)
+        for r in range(R):
+            s = int(strides[r])
+            n = s if fm is None else min(int(fm[r]) + 1, s)
+            cands = []
+            for i in range(n):
+                for j in range(p):
+                    t = int(truth[off[r] + i, j])
+                    cands += [t] if n_next == 0 else [t + o for o in range(1, n_next + 1)]
+            cands = [e for e in cands if 0 <= e < N]
+            want = _fifo_model(cache[r, :lens[r]].tolist(), int(heads[r]), C, cands)
+            assert _age_order(ids[r].tolist(), int(ln[r]), int(head[r]), C) == want
+            assert len(set(ids[r, :ln[r]].tolist())) == ln[r]
+
+
+def test_cache_insert_without_eviction_is_an_ordered_union(oracle):
+    rng = np.random.default_rng(23)
+    truth = rng.integers(0, 50, size=(12, 4)).astype(np.int32)
+    init = [7, 3, 11]
+    cache = np.full((1, 64), -1, dtype=np.int32)
+    cache[0, :3] = init
+    ids, ln, head = oracle.cache_insert(cache, [3], [0], truth, [0, 12], N=50, p=4)
+    assert ids[0, :ln[0]].tolist() == list(dict.fromkeys(init + truth.reshape(-1).tolist()))
+    assert head[0] == 0
+
+
+def test_prefetch_then_speculate_returns_the_knowledge_base_top1(oracle):
+    """Alg. 1: after Q.insert(C.retrieve(q)), Q.retrieve(q) is the top-1 of C.retrieve(q); with the
+    top-k update the same holds for nearby queries whose top-1 is among the prefetched k."""
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((400, 16)).astype(np.float32)
+    Qm = rng.standard_normal((6, 16)).astype(np.float32)
+    off = np.array([0, 2, 6], dtype=np.int64)                   # two requests: 2 and 4 steps
+    top, _ = oracle.retrieve_topk(Qm, X, 5)
+    cache = np.full((2, 32), -1, dtype=np.int32)
+    ids, ln, head = oracle.cache_insert(cache, [0, 0], [0, 0], top, off, N=400, p=1)
+    spec, _ = oracle.cache_lookup(ids, ln, Qm, off, X)
+    assert spec.tolist() == top[:, 0].tolist()
+    assert ln.tolist() == [len(set(top[0:2, 0])), len(set(top[2:6, 0]))]
+    # top-5 update: a perturbed query whose knowledge-base top-1 is one of the 5 prefetched ids
+    # gets that id from the cache (rank preservation, Section 3)
+    ids5, ln5, _ = oracle.cache_insert(cache, [0, 0], [0, 0], top, off, N=400, p=5)
+    Q2 = Qm + 0.05 * rng.standard_normal(Qm.shape).astype(np.float32)
+    top2, _ = oracle.retrieve_topk(Q2, X, 1)
+    spec2, _ = oracle.cache_lookup(ids5, ln5, Q2, off, X)
+    for r in range(2):
+        for q in range(off[r], off[r + 1]):
+            if top2[q, 0] in ids5[r, :ln5[r]]:
+                assert spec2[q] == top2[q, 0]
