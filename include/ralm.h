@@ -3,13 +3,14 @@
  * (arXiv 2401.14021, "Accelerating Retrieval-augmented Language Model Serving
  * with Speculation").
  *
- * Three operations of the paper's serving loop (Alg. 1) are implemented:
+ * Four operations of the paper's serving loop (Alg. 1) are implemented:
  *
  *   C.retrieve(q_1..q_s)   batched exact knowledge-base retrieval, the
  *                          verification step        -> ralm_retrieve_topk[_ex]
  *   Q.retrieve(q_i)        speculative retrieval from the request's local
  *                          cache, top-1             -> ralm_cache_lookup
  *   m = argmin_i d^_i!=d_i first mis-speculated step -> ralm_verify
+ *   Q.insert(C.retrieve(..)) cache update after verification -> ralm_cache_insert
  *
  * General conventions
  *   - Unless a parameter says "host", every data pointer is a DEVICE pointer
@@ -208,6 +209,41 @@ ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len
 ralm_status ralm_verify(const int32_t *spec_ids, const int32_t *true_ids, int64_t true_stride,
                         int64_t Qt, const int64_t *q_offsets, int64_t R, int32_t *first_mismatch,
                         void *stream);
+
+/*
+ * Cache update after a verification step (Alg. 1, Q.insert(C.retrieve(..));
+ * Section 3 "Batched verification": top-1 update and top-k update =
+ * prefetching, Fig. 2; Section 5.3: for KNN-LM the next n entries after a
+ * retrieved one).  The paper's cache has no stated capacity; here a request's
+ * cache is a ring of C ids: an id that is already cached is not inserted
+ * again, and once all C slots are used the oldest inserted id is overwritten.
+ *
+ *   cache_ids / cache_len   device int32 [R, C] / [R], as in ralm_cache_lookup;
+ *                           updated in place.  Owned ids must be distinct.
+ *   cache_head  device int32 [R]: the slot that the next insertion into a FULL
+ *               cache overwrites; start with zeros; updated in place.
+ *   true_ids    device int32: rank-j id of query q at true_ids[q * true_stride
+ *               + j] (the out_ids of a retrieval with k = true_stride)
+ *   q_offsets   device int64 [R+1] (clamped as in ralm_cache_lookup)
+ *   first_mismatch  device int32 [R] from ralm_verify, or NULL.  Given: only
+ *               the steps 0 .. min(first_mismatch[r], s_r - 1) of request r are
+ *               taken (the later ones were retrieved for a context that is
+ *               rolled back).  NULL: all s_r steps.
+ *   p           ranks 0 .. p-1 of each taken step are taken (1 = top-1 update,
+ *               20 = the paper's prefetch size); 1 <= p <= true_stride
+ *   n_next      0: a taken id t is itself the candidate; n > 0: its successors
+ *               t+1 .. t+n are (spatial locality of KNN-LM datastores)
+ *   N           candidates outside [0, N) are dropped, as are negative ids
+ *
+ * Candidates are inserted in the order step, rank, successor; the result is
+ * that of doing so one at a time.  Requests are independent (one wave each).
+ * Cost per candidate grows with the number of cached ids (linear membership
+ * test over the row in LDS); C <= 16384.
+ */
+ralm_status ralm_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *cache_head, int32_t C,
+                              int64_t R, const int32_t *true_ids, int64_t true_stride, int64_t Qt,
+                              const int64_t *q_offsets, const int32_t *first_mismatch, int32_t p,
+                              int32_t n_next, int64_t N, void *stream);
 
 /*
  * Timing aid for benchmarks.  While enabled, ralm_retrieve_topk_ex brackets

@@ -61,11 +61,13 @@ def lib() -> ctypes.CDLL:
         L.ralm_build_scan_copy.argtypes = [vp, i64, vp, i32, i64, i64, i32, vp]
         L.ralm_cache_lookup.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, vp, vp, vp]
         L.ralm_verify.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp]
+        L.ralm_cache_insert.argtypes = [vp, vp, vp, i32, i64, vp, i64, i64, vp, vp, i32, i32, i64, vp]
         L.ralm_profile_enable.argtypes = [i32]
         L.ralm_profile_enable.restype = None
         L.ralm_profile_scan_ms.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         for name in ("ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_retrieve_topk_seq", "ralm_workspace_overflows",
-                     "ralm_build_scan_copy", "ralm_cache_lookup", "ralm_verify", "ralm_profile_scan_ms"):
+                     "ralm_build_scan_copy", "ralm_cache_lookup", "ralm_verify", "ralm_cache_insert",
+                     "ralm_profile_scan_ms"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -213,6 +215,23 @@ def ralm_verify(spec_ids: torch.Tensor, true_ids: torch.Tensor, q_offsets: torch
     _check(lib().ralm_verify(spec_ids.data_ptr(), true_ids.data_ptr(), true_stride, Qt, q_offsets.data_ptr(), R,
                              first_mismatch.data_ptr(), _stream()))
     return first_mismatch
+
+
+def ralm_cache_insert(cache_ids: torch.Tensor, cache_len: torch.Tensor, cache_head: torch.Tensor,
+                      true_ids: torch.Tensor, q_offsets: torch.Tensor, N: int, p: int = 1, n_next: int = 0,
+                      first_mismatch: Optional[torch.Tensor] = None, true_stride: Optional[int] = None) -> None:
+    """In-place cache update; ``true_ids`` is the [Qt, k] out_ids of a retrieval (or flat with true_stride)."""
+    assert cache_ids.dtype == torch.int32 and cache_ids.is_contiguous() and cache_ids.dim() == 2
+    assert cache_len.dtype == torch.int32 and cache_head.dtype == torch.int32
+    assert true_ids.dtype == torch.int32 and true_ids.is_contiguous() and q_offsets.dtype == torch.int64
+    R, C = cache_ids.shape
+    if true_stride is None:
+        true_stride = true_ids.shape[1] if true_ids.dim() == 2 else 1
+    Qt = true_ids.numel() // true_stride
+    assert first_mismatch is None or first_mismatch.dtype == torch.int32
+    _check(lib().ralm_cache_insert(cache_ids.data_ptr(), cache_len.data_ptr(), cache_head.data_ptr(), C, R,
+                                   true_ids.data_ptr(), true_stride, Qt, q_offsets.data_ptr(),
+                                   _ptr(first_mismatch), p, n_next, N, _stream()))
 
 
 def ralm_profile_enable(on: bool) -> None:

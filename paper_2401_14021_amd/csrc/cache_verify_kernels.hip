@@ -9,6 +9,11 @@
 //                       both and "top-1 of the knowledge base is cached => it is the cache's
 //                       top-1" holds bit for bit.
 //  verify_kernel        m = argmin_i (d^_i != d_i) of Alg. 1, per request.
+//  cache_insert_kernel  Q.insert(C.retrieve(..)) of Alg. 1: the ids a verification step
+//                       retrieved go into the request's cache (Section 3 "Batched
+//                       verification": top-1 or top-k update; Section 5.3: the next n rows
+//                       after a retrieved one), skipping ids already cached, first in first
+//                       out once the cache is full.
 #include "ralm_common.h"
 #include "ralm_kernels.h"
 
@@ -142,6 +147,69 @@ __global__ __launch_bounds__(256) void verify_kernel(const int32_t *__restrict__
     if (lane == 0) first_mismatch[r] = (int32_t)m;
 }
 
+// One wave per request; the request's cache row sits in LDS while it is updated.  Candidates
+// are taken one at a time in the defined order (the outcome depends on it once the cache is
+// full); the membership test of a candidate is spread over the 64 lanes, 4 ids per LDS read.
+__global__ __launch_bounds__(64) void cache_insert_kernel(
+    int32_t *__restrict__ cache_ids, int32_t *__restrict__ cache_len, int32_t *__restrict__ cache_head, int C,
+    const int32_t *__restrict__ truth, int64_t true_stride, int64_t Qt, const int64_t *__restrict__ q_offsets,
+    const int32_t *__restrict__ first_mismatch, int p, int n_next, int64_t N)
+{
+    extern __shared__ __align__(16) int32_t cs[];   // [C rounded up to 256]; slots >= len hold -1
+    const int64_t r = blockIdx.x;
+    const int lane = threadIdx.x;
+    int64_t q_lo, q_hi;
+    clamp_range(q_offsets, r, Qt, q_lo, q_hi);
+    int64_t n = q_hi - q_lo;
+    if (first_mismatch) {
+        int64_t fm = first_mismatch[r];
+        fm = fm < 0 ? 0 : fm;
+        if (fm + 1 < n) n = fm + 1;        // steps up to and including the first mis-speculated one
+    }
+    if (n <= 0) return;
+    int len = cache_len[r];
+    len = len < 0 ? 0 : (len > C ? C : len);
+    int head = cache_head[r];
+    head = head < 0 || head >= C ? 0 : head;
+    int32_t *ids = cache_ids + r * (int64_t)C;
+    const int cpad = (C + 255) & ~255;
+    for (int x = lane; x < cpad; x += 64) cs[x] = x < len ? ids[x] : -1;
+    __syncthreads();
+
+    const int first = n_next > 0 ? 1 : 0, last = n_next > 0 ? n_next : 0;
+    for (int64_t i = 0; i < n; ++i) {
+        for (int j = 0; j < p; ++j) {
+            const int64_t t = truth[(q_lo + i) * true_stride + j];
+            if (t < 0) continue;
+            for (int o = first; o <= last; ++o) {
+                const int64_t e64 = t + o;
+                if (e64 >= N) break;
+                const int32_t e = (int32_t)e64;
+                bool found = false;
+                for (int x = lane * 4; x < len; x += 256) {
+                    const int4 v = *reinterpret_cast<const int4 *>(cs + x);
+                    found |= v.x == e || v.y == e || v.z == e || v.w == e;
+                }
+                if (__any(found)) continue;
+                int slot;
+                if (len < C) {
+                    slot = len++;
+                } else {
+                    slot = head;
+                    head = head + 1 == C ? 0 : head + 1;
+                }
+                if (lane == 0) cs[slot] = e;
+                __syncthreads();   // one wave: orders the LDS write before the next candidate's reads
+            }
+        }
+    }
+    for (int x = lane; x < len; x += 64) ids[x] = cs[x];
+    if (lane == 0) {
+        cache_len[r] = len;
+        cache_head[r] = head;
+    }
+}
+
 __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
@@ -238,6 +306,25 @@ hipError_t launch_verify(const int32_t *spec, const int32_t *truth, int64_t true
     if (R <= 0) return hipSuccess;
     hipLaunchKernelGGL(verify_kernel, dim3((unsigned)((R + 3) / 4)), dim3(256), 0, stream, spec, truth,
                        true_stride, Qt, q_offsets, R, first_mismatch);
+    return hipGetLastError();
+}
+
+hipError_t launch_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *cache_head, int32_t C, int64_t R,
+                               const int32_t *truth, int64_t true_stride, int64_t Qt, const int64_t *q_offsets,
+                               const int32_t *first_mismatch, int32_t p, int32_t n_next, int64_t N,
+                               hipStream_t stream)
+{
+    if (R <= 0) return hipSuccess;
+    const size_t smem = (size_t)((C + 255) & ~255) * sizeof(int32_t);
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(cache_insert_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, CACHE_INSERT_MAX_C * 4);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(cache_insert_kernel, dim3((unsigned)R), dim3(64), smem, stream, cache_ids, cache_len,
+                       cache_head, C, truth, true_stride, Qt, q_offsets, first_mismatch, p, n_next, N);
     return hipGetLastError();
 }
 

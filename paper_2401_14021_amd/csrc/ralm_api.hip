@@ -383,6 +383,23 @@ ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len
     return RALM_OK;
 }
 
+ralm_status ralm_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *cache_head, int32_t C, int64_t R,
+                              const int32_t *true_ids, int64_t true_stride, int64_t Qt, const int64_t *q_offsets,
+                              const int32_t *first_mismatch, int32_t p, int32_t n_next, int64_t N, void *stream)
+{
+    if (!cache_ids || !cache_len || !cache_head || !true_ids || !q_offsets)
+        return fail(RALM_ERR_NULL, "a pointer is NULL");
+    if (R < 0 || R > 0x7fffffffLL || C < 1 || C > CACHE_INSERT_MAX_C)
+        return fail(RALM_ERR_SHAPE, "R=%lld, C=%d out of range (C <= %d)", (long long)R, C, CACHE_INSERT_MAX_C);
+    if (N < 1 || N > 0x7fffffffLL) return fail(RALM_ERR_SHAPE, "N=%lld out of [1, 2^31)", (long long)N);
+    if (Qt < 0 || true_stride < 1) return fail(RALM_ERR_RANGE, "Qt >= 0 and true_stride >= 1 required");
+    if (p < 1 || (int64_t)p > true_stride) return fail(RALM_ERR_K, "p=%d must be in [1, true_stride]", p);
+    if (n_next < 0 || n_next > 65536) return fail(RALM_ERR_RANGE, "n_next=%d out of [0, 65536]", n_next);
+    RALM_HIP(launch_cache_insert(cache_ids, cache_len, cache_head, C, R, true_ids, true_stride, Qt, q_offsets,
+                                 first_mismatch, p, n_next, N, static_cast<hipStream_t>(stream)));
+    return RALM_OK;
+}
+
 ralm_status ralm_verify(const int32_t *spec_ids, const int32_t *true_ids, int64_t true_stride, int64_t Qt,
                         const int64_t *q_offsets, int64_t R, int32_t *first_mismatch, void *stream)
 {

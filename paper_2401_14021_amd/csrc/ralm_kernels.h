@@ -63,6 +63,11 @@ hipError_t launch_cache_lookup(const int32_t *cache_ids, const int32_t *cache_le
                                const void *exact, int32_t exact_dtype, int64_t ld, int64_t N, int32_t d,
                                int32_t *spec_ids, float *spec_scores, hipStream_t stream);
 
+constexpr int CACHE_INSERT_MAX_C = 16384;   // a request's cache row is held in LDS during an update
+hipError_t launch_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *cache_head, int32_t C, int64_t R,
+                               const int32_t *truth, int64_t true_stride, int64_t Qt, const int64_t *q_offsets,
+                               const int32_t *first_mismatch, int32_t p, int32_t n_next, int64_t N,
+                               hipStream_t stream);
 hipError_t launch_verify(const int32_t *spec, const int32_t *truth, int64_t true_stride, int64_t Qt,
                          const int64_t *q_offsets, int64_t R, int32_t *first_mismatch,
                          hipStream_t stream);

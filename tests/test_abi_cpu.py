@@ -22,7 +22,8 @@ def test_every_declared_symbol_is_exported(L):
     text = open(os.path.join(ROOT, "include", "ralm.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(ralm_[a-z0-9_]+)\s*\(", text))
-    assert {"ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_cache_lookup", "ralm_verify",
+    assert {"ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_retrieve_topk_seq", "ralm_cache_lookup",
+            "ralm_verify", "ralm_cache_insert",
             "ralm_workspace_bytes", "ralm_build_scan_copy", "ralm_last_error"} <= names
     for n in names:
         assert hasattr(L, n), n
@@ -70,6 +71,15 @@ def test_argument_errors_return_status_without_a_device(L):
     assert L.ralm_cache_lookup(None, P, 4, 2, P, 6, P, ref(ds), P, P, None) == 1
     assert L.ralm_cache_lookup(P, P, 0, 2, P, 6, P, ref(ds), P, P, None) == 2
     assert L.ralm_cache_lookup(P, P, 4, 2, P, -1, P, ref(ds), P, P, None) == 7
+    ins = L.ralm_cache_insert
+    assert ins(P, P, None, 4, 2, P, 5, 6, P, None, 1, 0, 1000, None) == 1         # no head array
+    assert ins(P, P, P, 0, 2, P, 5, 6, P, None, 1, 0, 1000, None) == 2            # C < 1
+    assert ins(P, P, P, 20000, 2, P, 5, 6, P, None, 1, 0, 1000, None) == 2        # C above the LDS limit
+    assert ins(P, P, P, 4, 2, P, 5, 6, P, None, 6, 0, 1000, None) == 3            # p > true_stride
+    assert ins(P, P, P, 4, 2, P, 5, 6, P, None, 0, 0, 1000, None) == 3            # p < 1
+    assert ins(P, P, P, 4, 2, P, 5, -1, P, None, 1, 0, 1000, None) == 7           # Qt < 0
+    assert ins(P, P, P, 4, 2, P, 5, 6, P, None, 1, -1, 1000, None) == 7           # n_next < 0
+    assert ins(P, P, P, 4, 2, P, 5, 6, P, None, 1, 0, 0, None) == 2               # N < 1
     assert L.ralm_verify(P, None, 1, 6, P, 2, P, None) == 1
     assert L.ralm_verify(P, P, 0, 6, P, 2, P, None) == 7
     assert L.ralm_verify(P, P, 1, 6, P, -1, P, None) == 2

@@ -302,3 +302,102 @@ def test_tiny_config_whole_path(B, oracle):
     check_topk(ids.cpu().numpy(), sc.cpu().numpy(), wi, wsc, _score_fn(oracle, Qm.numpy(), X.numpy()))
     assert np.array_equal(spec.cpu().numpy(), ws_ids) and np.array_equal(spec_sc.cpu().numpy(), ws_sc)
     assert np.array_equal(m.cpu().numpy(), wm)
+
+
+# ----------------------------------------------------------------------------------------
+# cache update (integer work: bit-exact against the oracle)
+# ----------------------------------------------------------------------------------------
+def _insert_both(B, oracle, cache, lens, heads, truth, off, N, p, n_next, fm):
+    want = oracle.cache_insert(cache, lens, heads, truth, off, N=N, p=p, n_next=n_next, first_mismatch=fm)
+    dc = torch.from_numpy(np.ascontiguousarray(cache)).cuda()
+    dl = torch.from_numpy(np.asarray(lens, dtype=np.int32)).cuda()
+    dh = torch.from_numpy(np.asarray(heads, dtype=np.int32)).cuda()
+    B.ralm_cache_insert(dc, dl, dh, torch.from_numpy(np.ascontiguousarray(truth)).cuda(),
+                        torch.from_numpy(np.asarray(off, dtype=np.int64)).cuda(), N, p=p, n_next=n_next,
+                        first_mismatch=None if fm is None else torch.from_numpy(np.asarray(fm, dtype=np.int32)).cuda())
+    return (dc.cpu().numpy(), dl.cpu().numpy(), dh.cpu().numpy()), want
+
+
+def _same_cache(got, want):
+    gi, gl, gh = got
+    wi, wl, wh = want
+    assert np.array_equal(gl, wl) and np.array_equal(gh, wh)
+    for r in range(gi.shape[0]):
+        assert np.array_equal(gi[r, :gl[r]], wi[r, :wl[r]]), r
+
+
+def test_cache_insert_hand_cases_on_gpu(B, oracle):
+    from test_oracle_pins import _read_insert_cases
+    for c in _read_insert_cases():
+        cache = np.full((1, c["C"]), -1, dtype=np.int32)
+        cache[0, :len(c["init"])] = c["init"]
+        got, want = _insert_both(B, oracle, cache, [len(c["init"])], [0], c["truth"], [0, len(c["truth"])],
+                                 c["N"], c["p"], c["n_next"], None if c["fm"] is None else [c["fm"]])
+        assert got[0][0, :got[1][0]].tolist() == c["ids"] and got[1][0] == c["len"] and got[2][0] == c["head"]
+        _same_cache(got, want)
+
+
+@pytest.mark.parametrize("C,R,k,p,n_next,smax", [
+    (1, 5, 3, 2, 0, 4), (7, 40, 5, 5, 0, 8), (64, 300, 20, 20, 0, 8), (1024, 64, 20, 1, 0, 8),
+    (1000, 33, 8, 4, 3, 6), (4096, 20, 32, 32, 10, 8), (16384, 3, 64, 64, 10, 8), (300, 50, 4, 2, 1, 0),
+])
+def test_cache_insert_matches_oracle(B, oracle, C, R, k, p, n_next, smax):
+    """Random retrieval results with many repeats (ids drawn from a small range), caches that start
+    empty, partly filled or full with the ring pointer anywhere, with and without first-mismatch
+    truncation, so that insertion, de-duplication and eviction inside one call all occur."""
+    rng = np.random.default_rng(C * 131 + R)
+    N = max(50, 3 * C)
+    strides = rng.integers(0, smax + 1, size=R)
+    off = np.concatenate([[0], np.cumsum(strides)]).astype(np.int64)
+    Qt = int(off[-1])
+    truth = rng.integers(0, N, size=(max(Qt, 1), k)).astype(np.int32)
+    truth[rng.random(truth.shape) < 0.02] = -1                   # unfilled ranks are skipped
+    lens = rng.choice([0, C // 2, C], size=R).astype(np.int32)
+    heads = np.array([rng.integers(0, C) if l == C else 0 for l in lens], dtype=np.int32)
+    cache = np.full((R, C), -1, dtype=np.int32)
+    for r in range(R):
+        cache[r, :lens[r]] = rng.choice(N, size=lens[r], replace=False)
+    for fm in (None, rng.integers(0, smax + 2, size=R).astype(np.int32)):
+        got, want = _insert_both(B, oracle, cache, lens, heads, truth, off, N, p, n_next, fm)
+        _same_cache(got, want)
+        for r in range(R):
+            assert len(set(got[0][r, :got[1][r]].tolist())) == got[1][r]
+
+
+def test_speculation_loop_closed_by_cache_insert(B, oracle):
+    """Alg. 1 as a loop on the GPU entry points: speculate from the cache, verify with a batched
+    retrieval, find the first mismatch, insert the verified results (top-5 update); the queries
+    drift between rounds.  Every round's caches, speculated ids and first mismatches equal the
+    oracle's, and the hit rate grows from zero as the caches fill."""
+    from paper_2401_14021_amd import inputs
+    N, d, R, C, k = 30000, 64, 24, 24, 5        # 24 slots: the ring starts evicting after a few rounds
+    X, _ = inputs.clustered_datastore(N, d, 32, seed=41)
+    Xn = X.numpy()
+    ds = B.Datastore.from_fp32(X.cuda())
+    strides = inputs.uniform_strides(R, 1, 6, seed=42)
+    off = inputs.stride_offsets(strides)
+    Q = int(off[-1])
+    qcur = inputs.queries_near_rows(X, inputs.pick_rows(N, Q, seed=43), seed=44)
+    cache = torch.full((R, C), -1, dtype=torch.int32).cuda()
+    clen = torch.zeros(R, dtype=torch.int32).cuda()
+    head = torch.zeros(R, dtype=torch.int32).cuda()
+    o_cache, o_len, o_head = cache.cpu().numpy(), clen.cpu().numpy(), head.cpu().numpy()
+    hits = []
+    for rnd in range(8):
+        qd = qcur.cuda()
+        spec, _ = B.ralm_cache_lookup(cache, clen, qd, off.cuda(), ds)
+        ids, _ = B.ralm_retrieve_topk_ex(qd, ds, k)
+        fm = B.ralm_verify(spec, ids, off.cuda(), true_stride=k)
+        B.ralm_cache_insert(cache, clen, head, ids, off.cuda(), N, p=k, first_mismatch=fm)
+        # the oracle, fed with its own state
+        o_spec, _ = oracle.cache_lookup(o_cache, o_len, qcur.numpy(), off.numpy(), Xn)
+        o_ids, _ = oracle.retrieve_topk(qcur.numpy(), Xn, k)
+        o_fm = oracle.verify(o_spec, o_ids, off.numpy(), true_stride=k)
+        o_cache, o_len, o_head = oracle.cache_insert(o_cache, o_len, o_head, o_ids, off.numpy(), N=N, p=k,
+                                                     first_mismatch=o_fm)
+        assert np.array_equal(ids.cpu().numpy(), o_ids)
+        assert np.array_equal(spec.cpu().numpy(), o_spec) and np.array_equal(fm.cpu().numpy(), o_fm)
+        _same_cache((cache.cpu().numpy(), clen.cpu().numpy(), head.cpu().numpy()), (o_cache, o_len, o_head))
+        hits.append(float((spec[:, None] == ids[:, :1]).float().mean().item()))
+        qcur = inputs.drift_queries(qcur, seed=50 + rnd)
+    assert hits[0] == 0.0 and max(hits[2:]) > 0.3
