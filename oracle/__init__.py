@@ -53,6 +53,15 @@ def _load():
         L.ralm_oracle_verify.restype = None
         L.ralm_oracle_cache_insert.argtypes = [vp, vp, vp, i32, i64, vp, i64, vp, vp, i32, i32, i64]
         L.ralm_oracle_cache_insert.restype = None
+        dbl = ctypes.c_double
+        L.ralm_oracle_os3_expected_verified.argtypes = [dbl, i32]
+        L.ralm_oracle_os3_expected_verified.restype = dbl
+        L.ralm_oracle_os3_objective.argtypes = [dbl, dbl, dbl, i32, i32]
+        L.ralm_oracle_os3_objective.restype = dbl
+        L.ralm_oracle_os3_stride.argtypes = [dbl, dbl, dbl, i32, i32]
+        L.ralm_oracle_os3_stride.restype = i32
+        L.ralm_oracle_os3_gamma.argtypes = [vp, vp, i32, dbl]
+        L.ralm_oracle_os3_gamma.restype = dbl
         _lib = L
     return _lib
 
@@ -193,3 +202,22 @@ def cache_insert(cache_ids: np.ndarray, cache_len: np.ndarray, cache_head: np.nd
     _load().ralm_oracle_cache_insert(_ptr(cache_ids), _ptr(cache_len), _ptr(cache_head), C, R, _ptr(true_ids),
                                      true_stride, _ptr(q_offsets), None if fm is None else _ptr(fm), p, n_next, N)
     return cache_ids, cache_len, cache_head
+
+
+def os3_expected_verified(gamma: float, s: int) -> float:
+    return float(_load().ralm_oracle_os3_expected_verified(gamma, s))
+
+
+def os3_objective(gamma: float, a: float, b: float, s: int, asynchronous: bool = False) -> float:
+    return float(_load().ralm_oracle_os3_objective(gamma, a, b, s, 1 if asynchronous else 0))
+
+
+def os3_stride(gamma: float, a: float, b: float, s_max: int, asynchronous: bool = False) -> int:
+    return int(_load().ralm_oracle_os3_stride(gamma, a, b, s_max, 1 if asynchronous else 0))
+
+
+def os3_gamma(strides, matched, gamma_max: float = 0.6) -> float:
+    st = np.ascontiguousarray(strides, dtype=np.int32)
+    m = np.ascontiguousarray(matched, dtype=np.int32)
+    assert st.shape == m.shape
+    return float(_load().ralm_oracle_os3_gamma(_ptr(st), _ptr(m), st.shape[0], gamma_max))

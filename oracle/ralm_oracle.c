@@ -20,6 +20,9 @@
  *    verification step retrieved go into the request's local cache (Section 3,
  *    "Batched verification": top-1 update, or top-k update = prefetching,
  *    Fig. 2; Section 5.3: for KNN-LM the next n entries after a retrieved one).
+ *  - the stride scheduler OS^3 (Section 4, Appendix A.2): the objective as the
+ *    expectation over the distribution of the first mismatch, divided by the
+ *    expected latency; the accuracy estimate; the best stride by trying all.
  *
  * Readings where the paper is silent:
  *  - metric: inner product (dense passage retrieval scores, raw inner product
@@ -268,4 +271,65 @@ void ralm_oracle_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *c
         cache_len[r] = len;
         cache_head[r] = head;
     }
+}
+
+/*
+ * OS^3 (Section 4; Appendix A.2).  A speculation step matches with probability
+ * gamma, independently.  With stride s the first mismatch is at step i (0-based)
+ * with probability gamma^i (1 - gamma), i < s, and there is none with
+ * probability gamma^s.  A mismatch at step i verifies i + 1 documents (the i
+ * matches and the corrected one); no mismatch verifies s.  The expected number
+ * of verified documents is the sum over these s + 1 outcomes.
+ */
+double ralm_oracle_os3_expected_verified(double gamma, int32_t s)
+{
+    double e = 0.0;
+    for (int32_t i = 0; i < s; ++i) e += (double)(i + 1) * pow(gamma, (double)i) * (1.0 - gamma);
+    e += (double)s * pow(gamma, (double)s);
+    return e;
+}
+
+/*
+ * Objective: expected verified documents per unit time.  a = latency of one
+ * speculation step, b = latency of one verification step.  Synchronous
+ * verification always takes s a + b.  Asynchronous verification overlaps the
+ * verification with one more speculation step, (s-1) a + max(a, b), but only
+ * when all s steps matched (probability gamma^s); otherwise s a + b.
+ */
+double ralm_oracle_os3_objective(double gamma, double a, double b, int32_t s, int32_t async)
+{
+    double all_match = pow(gamma, (double)s);
+    double latency = (double)s * a + b;
+    if (async)
+        latency = all_match * ((double)(s - 1) * a + (a > b ? a : b)) + (1.0 - all_match) * ((double)s * a + b);
+    return ralm_oracle_os3_expected_verified(gamma, s) / latency;
+}
+
+/* Best stride in [1, s_max] by trying each; the smallest on exact ties. */
+int32_t ralm_oracle_os3_stride(double gamma, double a, double b, int32_t s_max, int32_t async)
+{
+    int32_t best = 1;
+    for (int32_t s = 2; s <= s_max; ++s)
+        if (ralm_oracle_os3_objective(gamma, a, b, s, async) > ralm_oracle_os3_objective(gamma, a, b, best, async))
+            best = s;
+    return best;
+}
+
+/*
+ * Accuracy estimate (Appendix A.2, "Parameter estimation"): over the w most
+ * recent verification steps, matched documents / (matched documents + number of
+ * steps that ended in a mismatch), truncated at gamma_max.  This is the maximum
+ * likelihood estimate for independent trials: every matched document is a
+ * success, every step that stopped early contributes exactly one failure.
+ */
+double ralm_oracle_os3_gamma(const int32_t *strides, const int32_t *matched, int32_t w, double gamma_max)
+{
+    int64_t successes = 0, failures = 0;
+    for (int32_t t = 0; t < w; ++t) {
+        successes += matched[t];
+        if (matched[t] < strides[t]) failures += 1;
+    }
+    if (successes + failures == 0) return 0.0;
+    double g = (double)successes / (double)(successes + failures);
+    return g > gamma_max ? gamma_max : g;
 }

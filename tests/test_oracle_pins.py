@@ -419,3 +419,85 @@ def test_prefetch_then_speculate_returns_the_knowledge_base_top1(oracle):
         for q in range(off[r], off[r + 1]):
             if top2[q, 0] in ids5[r, :ln5[r]]:
                 assert spec2[q] == top2[q, 0]
+
+
+# ----------------------------------------------------------------------------------------
+# stride scheduler OS^3 (Section 4, Appendix A.2)
+# ----------------------------------------------------------------------------------------
+def _read_os3_cases():
+    objective, gamma = [], []
+    for line in open(os.path.join(GOLDEN, "os3_hand.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        if line.startswith("gamma_case"):
+            _, st, m, gmax, est = [f.strip() for f in line.split("|")]
+            gamma.append(([int(v) for v in st.split()], [int(v) for v in m.split()], float(gmax), float(est)))
+        else:
+            g, a, b, s, asy, val = line.split()
+            objective.append((float(g), float(a), float(b), int(s), bool(int(asy)), float(val)))
+    return objective, gamma
+
+
+def test_os3_hand_values(oracle):
+    objective, gamma = _read_os3_cases()
+    assert len(objective) == 10 and len(gamma) == 4
+    for g, a, b, s, asy, val in objective:
+        assert oracle.os3_objective(g, a, b, s, asy) == pytest.approx(val, rel=1e-14)
+    for st, m, gmax, est in gamma:
+        assert oracle.os3_gamma(st, m, gmax) == pytest.approx(est, rel=1e-15, abs=0)
+    assert oracle.os3_stride(0.5, 1, 4, 16) == 2            # first of two equal maxima
+    assert oracle.os3_stride(0.6, 1, 100, 8) == 8
+    for a, b in ((1, 1), (0.1, 5), (7, 0.5)):
+        assert oracle.os3_stride(0.0, a, b, 16) == 1 and oracle.os3_stride(0.0, a, b, 16, True) == 1
+
+
+def test_os3_expected_verified_equals_the_closed_form(oracle):
+    """Section 4 / Appendix A.2: the expectation over first-mismatch outcomes equals
+    (1 - g^s)/(1 - g) = sum of g^i; at g = 1 every step matches and s documents are verified."""
+    for g in (0.0, 0.1, 0.37, 0.5, 0.6, 0.9, 0.999):
+        for s in range(1, 40):
+            assert oracle.os3_expected_verified(g, s) == pytest.approx((1 - g ** s) / (1 - g), rel=1e-12)
+    for s in range(1, 10):
+        assert oracle.os3_expected_verified(1.0, s) == s
+
+
+def test_os3_objective_is_verified_documents_per_unit_time_monte_carlo(oracle):
+    """Simulate rounds of the serving loop with iid match probability g and stride s: the ratio of
+    total verified documents to total time converges to the objective (renewal reward), for both
+    latency models."""
+    rng = np.random.default_rng(3)
+    a, b = 1.0, 3.5
+    for g, s in ((0.3, 2), (0.6, 4), (0.8, 6)):
+        match = rng.random((200000, s)) < g
+        first = np.where(match.all(axis=1), s, np.argmin(match, axis=1))
+        verified = np.minimum(first + 1, s)
+        t_sync = np.full(first.shape, s * a + b)
+        t_async = np.where(first == s, (s - 1) * a + max(a, b), s * a + b)
+        assert verified.sum() / t_sync.sum() == pytest.approx(oracle.os3_objective(g, a, b, s), rel=1e-2)
+        assert verified.sum() / t_async.sum() == pytest.approx(oracle.os3_objective(g, a, b, s, True), rel=1e-2)
+
+
+def test_os3_stride_behaviour_and_estimator_consistency(oracle):
+    # dearer verification (larger b/a) and better speculation (larger g) never shorten the stride
+    for asy in (False, True):
+        prev = 1
+        for b in (0.5, 1, 2, 4, 8, 16, 64):
+            s = oracle.os3_stride(0.6, 1.0, b, 32, asy)
+            assert s >= prev
+            prev = s
+        prev = 1
+        for g in (0.0, 0.2, 0.4, 0.6, 0.8, 0.95):
+            s = oracle.os3_stride(g, 1.0, 8.0, 32, asy)
+            assert s >= prev
+            prev = s
+        # the chosen stride is the brute-force argmax
+        for g, a, b in ((0.55, 1.0, 6.0), (0.3, 2.0, 1.0), (0.9, 0.2, 3.0)):
+            vals = [oracle.os3_objective(g, a, b, s, asy) for s in range(1, 33)]
+            assert oracle.os3_stride(g, a, b, 32, asy) == int(np.argmax(vals)) + 1
+    # the estimator recovers the match probability of simulated geometric trials
+    rng = np.random.default_rng(9)
+    for g in (0.2, 0.5, 0.85):
+        strides = rng.integers(1, 9, size=4000)
+        matched = np.array([min(int(rng.geometric(1 - g)) - 1, s) for s in strides])
+        assert oracle.os3_gamma(strides, matched, 1.0) == pytest.approx(g, abs=0.02)
