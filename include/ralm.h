@@ -246,6 +246,32 @@ ralm_status ralm_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *c
                               int32_t n_next, int64_t N, void *stream);
 
 /*
+ * Optimal speculation stride scheduler, OS^3 (Section 4; estimation of its
+ * parameters: Appendix A.2, "Parameter estimation").  Host-only scalar
+ * functions; every pointer is a HOST pointer; nothing is launched.
+ *
+ * ralm_os3_gamma: estimate of the speculation accuracy gamma from the w most
+ *   recent verification steps of a request: strides[t] = s(t), matched[t] =
+ *   M(s(t)) = number of speculated documents that matched before the first
+ *   mismatch (the first_mismatch of ralm_verify):
+ *       gamma^ = sum_t M(t) / ( sum_t M(t) + #{t : M(t) < s(t)} ),
+ *   truncated at gamma_max (the paper uses w = 5, gamma_max = 0.6).  0 when
+ *   there is no history (w <= 0) or nothing matched.
+ * ralm_os3_objective: expected verified documents per unit time for stride s,
+ *       (1 - gamma^s) / (1 - gamma) / latency(s),
+ *   latency(s) = s a + b (synchronous verification; async == 0), or
+ *   gamma^s ((s-1) a + max(a, b)) + (1 - gamma^s)(s a + b) (asynchronous),
+ *   with a = latency of a speculation step, b = latency of a verification
+ *   step.  The expectation is formed as the sum of gamma^i, i < s, so gamma = 1
+ *   needs no special case.  NaN for s < 1, negative a or b, gamma outside [0, 1].
+ * ralm_os3_stride: the s in [1, s_max] with the largest objective; the
+ *   smallest such s on ties.
+ */
+double ralm_os3_gamma(const int32_t *strides, const int32_t *matched, int32_t w, double gamma_max);
+double ralm_os3_objective(double gamma, double a, double b, int32_t s, int32_t async);
+int32_t ralm_os3_stride(double gamma, double a, double b, int32_t s_max, int32_t async);
+
+/*
  * Timing aid for benchmarks.  While enabled, ralm_retrieve_topk_ex brackets
  * each launch of its scan kernel (a call makes several: together they read
  * every row of the datastore exactly once) with HIP events on the call's

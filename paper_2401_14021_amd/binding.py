@@ -62,6 +62,12 @@ def lib() -> ctypes.CDLL:
         L.ralm_cache_lookup.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, vp, vp, vp]
         L.ralm_verify.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp]
         L.ralm_cache_insert.argtypes = [vp, vp, vp, i32, i64, vp, i64, i64, vp, vp, i32, i32, i64, vp]
+        L.ralm_os3_gamma.argtypes = [vp, vp, i32, ctypes.c_double]
+        L.ralm_os3_gamma.restype = ctypes.c_double
+        L.ralm_os3_objective.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_double, i32, i32]
+        L.ralm_os3_objective.restype = ctypes.c_double
+        L.ralm_os3_stride.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_double, i32, i32]
+        L.ralm_os3_stride.restype = i32
         L.ralm_profile_enable.argtypes = [i32]
         L.ralm_profile_enable.restype = None
         L.ralm_profile_scan_ms.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
@@ -232,6 +238,23 @@ def ralm_cache_insert(cache_ids: torch.Tensor, cache_len: torch.Tensor, cache_he
     _check(lib().ralm_cache_insert(cache_ids.data_ptr(), cache_len.data_ptr(), cache_head.data_ptr(), C, R,
                                    true_ids.data_ptr(), true_stride, Qt, q_offsets.data_ptr(),
                                    _ptr(first_mismatch), p, n_next, N, _stream()))
+
+
+def ralm_os3_gamma(strides, matched, gamma_max: float = 0.6) -> float:
+    """Host-side: speculation accuracy estimate from the recent (stride, matched) history."""
+    w = len(strides)
+    assert len(matched) == w
+    s = (ctypes.c_int32 * max(w, 1))(*[int(v) for v in strides])
+    m = (ctypes.c_int32 * max(w, 1))(*[int(v) for v in matched])
+    return float(lib().ralm_os3_gamma(s, m, w, gamma_max))
+
+
+def ralm_os3_objective(gamma: float, a: float, b: float, s: int, asynchronous: bool = False) -> float:
+    return float(lib().ralm_os3_objective(gamma, a, b, s, 1 if asynchronous else 0))
+
+
+def ralm_os3_stride(gamma: float, a: float, b: float, s_max: int, asynchronous: bool = False) -> int:
+    return int(lib().ralm_os3_stride(gamma, a, b, s_max, 1 if asynchronous else 0))
 
 
 def ralm_profile_enable(on: bool) -> None:

@@ -94,3 +94,34 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libralm.so")
     with pytest.raises(FileNotFoundError):
         binding.lib()
+
+
+# ---- stride scheduler: host-only functions of the library against the oracle (no GPU involved) ----
+def test_os3_matches_oracle(L, oracle):
+    from paper_2401_14021_amd import binding as b
+    import numpy as np
+    from test_oracle_pins import _read_os3_cases
+    objective, gamma = _read_os3_cases()
+    for g, a, bb, s, asy, val in objective:
+        assert b.ralm_os3_objective(g, a, bb, s, asy) == pytest.approx(val, rel=1e-14)
+    for st, m, gmax, est in gamma:
+        assert b.ralm_os3_gamma(st, m, gmax) == est
+    rng = np.random.default_rng(12)
+    for _ in range(400):
+        g = float(rng.choice([0.0, 1.0, rng.random()]))
+        a, bb = float(rng.random() * 5 + 1e-3), float(rng.random() * 50)
+        asy = bool(rng.integers(0, 2))
+        for s in (1, 2, 3, 7, 32):
+            assert b.ralm_os3_objective(g, a, bb, s, asy) == pytest.approx(oracle.os3_objective(g, a, bb, s, asy), rel=1e-12)
+        s_lib = b.ralm_os3_stride(g, a, bb, 32, asy)
+        s_or = oracle.os3_stride(g, a, bb, 32, asy)
+        # equal, or tied within rounding (the two sum the expectation in different orders)
+        assert s_lib == s_or or oracle.os3_objective(g, a, bb, s_lib, asy) == pytest.approx(
+            oracle.os3_objective(g, a, bb, s_or, asy), rel=1e-12)
+        w = int(rng.integers(0, 8))
+        st = rng.integers(1, 9, size=w)
+        m = np.minimum(rng.integers(0, 10, size=w), st)
+        assert b.ralm_os3_gamma(st, m, 0.6) == oracle.os3_gamma(st, m, 0.6) if w else b.ralm_os3_gamma(st, m) == 0.0
+    assert b.ralm_os3_stride(0.5, 1, 4, 16) == 2 and b.ralm_os3_stride(0.0, 1, 4, 16) == 1
+    assert b.ralm_os3_objective(0.5, 1, 4, 0) != b.ralm_os3_objective(0.5, 1, 4, 0)      # NaN for s < 1
+    assert b.ralm_os3_objective(1.5, 1, 4, 2) != b.ralm_os3_objective(1.5, 1, 4, 2)      # NaN for gamma > 1
