@@ -401,3 +401,45 @@ def test_speculation_loop_closed_by_cache_insert(B, oracle):
         hits.append(float((spec[:, None] == ids[:, :1]).float().mean().item()))
         qcur = inputs.drift_queries(qcur, seed=50 + rnd)
     assert hits[0] == 0.0 and max(hits[2:]) > 0.3
+
+
+def test_asynchronous_verification_on_two_streams(B, oracle):
+    """Section 3 "Asynchronous verification": while the knowledge base verifies the steps of one
+    stride, the next speculation step already runs.  Here: the batched retrieval of round t on one
+    stream, the cache lookup of the extra speculation step on another (separate outputs, the
+    retrieval's own workspace), then the compare after both.  Results must equal the calls made
+    one after the other, and the oracle's."""
+    from paper_2401_14021_amd import inputs
+    N, d, R, C, k = 60000, 128, 40, 64, 5
+    X, _ = inputs.clustered_datastore(N, d, 64, seed=61)
+    ds = B.Datastore.from_fp32(X.cuda())
+    strides = inputs.uniform_strides(R, 1, 5, seed=62)
+    off = inputs.stride_offsets(strides)
+    Q = int(off[-1])
+    rows = inputs.pick_rows(N, Q, seed=63)
+    q_verify = inputs.queries_near_rows(X, rows, seed=64).cuda()
+    q_next = inputs.drift_queries(q_verify, seed=65)                   # the extra speculation step
+    cids, clen = inputs.speculation_caches(N, R, C, off, rows, None, seed=66)
+    cids, clen, offd = cids.cuda(), clen.cuda(), off.cuda()
+    ws = B.alloc_workspace(Q, ds, k)
+    # serial reference on the current stream
+    ids0, sc0 = B.ralm_retrieve_topk_ex(q_verify, ds, k, workspace=ws)
+    spec0, ssc0 = B.ralm_cache_lookup(cids, clen, q_next, offd, ds)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    ids1 = torch.empty_like(ids0)
+    sc1 = torch.empty_like(sc0)
+    spec1 = torch.full_like(spec0, -7)
+    ssc1 = torch.zeros_like(ssc0)
+    for rep in range(3):
+        with torch.cuda.stream(s1):
+            B.ralm_retrieve_topk_ex(q_verify, ds, k, workspace=ws, out_ids=ids1, out_scores=sc1)
+        with torch.cuda.stream(s2):
+            B.ralm_cache_lookup(cids, clen, q_next, offd, ds, spec1, ssc1)
+        s1.synchronize()
+        s2.synchronize()
+        assert torch.equal(ids1, ids0) and torch.equal(sc1, sc0)
+        assert torch.equal(spec1, spec0) and torch.equal(ssc1, ssc0)
+    want_spec, _ = oracle.cache_lookup(cids.cpu().numpy(), clen.cpu().numpy(), q_next.cpu().numpy(), off.numpy(),
+                                       X.numpy())
+    assert np.array_equal(spec1.cpu().numpy(), want_spec)
