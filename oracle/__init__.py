@@ -62,6 +62,8 @@ def _load():
         L.ralm_oracle_os3_stride.restype = i32
         L.ralm_oracle_os3_gamma.argtypes = [vp, vp, i32, dbl]
         L.ralm_oracle_os3_gamma.restype = dbl
+        L.ralm_oracle_knnlm_probs.argtypes = [vp, vp, i64, i32, vp, dbl, vp, vp, vp, vp]
+        L.ralm_oracle_knnlm_probs.restype = None
         _lib = L
     return _lib
 
@@ -221,3 +223,19 @@ def os3_gamma(strides, matched, gamma_max: float = 0.6) -> float:
     m = np.ascontiguousarray(matched, dtype=np.int32)
     assert st.shape == m.shape
     return float(_load().ralm_oracle_os3_gamma(_ptr(st), _ptr(m), st.shape[0], gamma_max))
+
+
+def knnlm_probs(ids: np.ndarray, scores: np.ndarray, values: np.ndarray, temperature: float = 1.0):
+    """Neighbour distribution of KNN-LM: (tokens [Q,k], weights [Q,k], top_token [Q], top_prob [Q])."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    scores = np.ascontiguousarray(scores, dtype=np.float32)
+    values = np.ascontiguousarray(values, dtype=np.int32)
+    Q, k = ids.shape
+    assert scores.shape == (Q, k) and temperature > 0
+    tokens = np.empty((Q, k), dtype=np.int32)
+    weights = np.empty((Q, k), dtype=np.float32)
+    top_token = np.empty(Q, dtype=np.int32)
+    top_prob = np.empty(Q, dtype=np.float32)
+    _load().ralm_oracle_knnlm_probs(_ptr(ids), _ptr(scores), Q, k, _ptr(values), float(temperature),
+                                    _ptr(tokens), _ptr(weights), _ptr(top_token), _ptr(top_prob))
+    return tokens, weights, top_token, top_prob

@@ -23,6 +23,8 @@
  *  - the stride scheduler OS^3 (Section 4, Appendix A.2): the objective as the
  *    expectation over the distribution of the first mismatch, divided by the
  *    expected latency; the accuracy estimate; the best stride by trying all.
+ *  - the KNN-LM neighbour distribution (Section 5.3): weights over the k
+ *    retrieved entries from their scores, summed per target token.
  *
  * Readings where the paper is silent:
  *  - metric: inner product (dense passage retrieval scores, raw inner product
@@ -332,4 +334,61 @@ double ralm_oracle_os3_gamma(const int32_t *strides, const int32_t *matched, int
     if (successes + failures == 0) return 0.0;
     double g = (double)successes / (double)(successes + failures);
     return g > gamma_max ? gamma_max : g;
+}
+
+/*
+ * KNN-LM neighbour distribution (Section 5.3: "a distribution over these k
+ * target tokens is computed based on their distance with respect to the current
+ * context embedding").  Entry i of a query has retrieval score s_i (larger =
+ * closer: the inner product, or minus the squared distance) and target token
+ * values[ids_i].  Its weight is exp(s_i / T) / sum_j exp(s_j / T); the
+ * probability of a token is the sum of the weights of the entries that carry
+ * it.  Unfilled entries (id < 0) get token -1 and weight 0.
+ *
+ * Arithmetic: double; the largest score is subtracted before exp (this changes
+ * nothing mathematically); sums run left to right in rank order; weights and
+ * the top probability are rounded once to fp32.  top_token is the token with
+ * the largest probability (compared in double), the smallest token id on ties;
+ * -1 / 0 when the query has no filled entry.
+ */
+void ralm_oracle_knnlm_probs(const int32_t *ids, const float *scores, int64_t Q, int32_t k,
+                             const int32_t *values, double T, int32_t *tokens, float *weights,
+                             int32_t *top_token, float *top_prob)
+{
+    double *e = (double *)malloc(sizeof(double) * (size_t)(k > 0 ? k : 1));
+    for (int64_t q = 0; q < Q; ++q) {
+        const int32_t *id = ids + q * k;
+        const float *sc = scores + q * k;
+        int32_t *tok = tokens + q * k;
+        float *w = weights + q * k;
+        double best = -INFINITY;
+        for (int32_t i = 0; i < k; ++i)
+            if (id[i] >= 0 && (double)sc[i] > best) best = (double)sc[i];
+        double Z = 0.0;
+        for (int32_t i = 0; i < k; ++i) {
+            e[i] = id[i] >= 0 ? exp(((double)sc[i] - best) / T) : 0.0;
+            Z += e[i];
+        }
+        for (int32_t i = 0; i < k; ++i) {
+            tok[i] = id[i] >= 0 ? values[id[i]] : -1;
+            e[i] = Z > 0.0 ? e[i] / Z : 0.0;
+            w[i] = (float)e[i];
+        }
+        int32_t arg = -1;
+        double argp = 0.0;
+        for (int32_t i = 0; i < k; ++i) {
+            if (id[i] < 0) continue;
+            int seen = 0;
+            for (int32_t j = 0; j < i; ++j)
+                if (id[j] >= 0 && tok[j] == tok[i]) { seen = 1; break; }
+            if (seen) continue;
+            double p = 0.0;
+            for (int32_t j = i; j < k; ++j)
+                if (id[j] >= 0 && tok[j] == tok[i]) p += e[j];
+            if (arg < 0 || p > argp || (p == argp && tok[i] < arg)) { arg = tok[i]; argp = p; }
+        }
+        top_token[q] = arg;
+        top_prob[q] = (float)argp;
+    }
+    free(e);
 }

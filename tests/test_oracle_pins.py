@@ -501,3 +501,54 @@ def test_os3_stride_behaviour_and_estimator_consistency(oracle):
         strides = rng.integers(1, 9, size=4000)
         matched = np.array([min(int(rng.geometric(1 - g)) - 1, s) for s in strides])
         assert oracle.os3_gamma(strides, matched, 1.0) == pytest.approx(g, abs=0.02)
+
+
+# ----------------------------------------------------------------------------------------
+# KNN-LM neighbour distribution (Section 5.3)
+# ----------------------------------------------------------------------------------------
+def test_knnlm_probs_hand_case(oracle):
+    """Scores 0, ln 2, ln 2 give weights 1/5, 2/5, 2/5; tokens 7, 3, 7 give P(7) = 3/5, P(3) = 2/5.
+    With temperature 2 the weights are 1, sqrt 2, sqrt 2 over 1 + 2 sqrt 2."""
+    ln2 = float(np.log(2.0))
+    values = np.array([7, 3, 7, 9], dtype=np.int32)
+    ids = np.array([[0, 1, 2]], dtype=np.int32)
+    sc = np.array([[0.0, ln2, ln2]], dtype=np.float32)
+    tok, w, top, tp = oracle.knnlm_probs(ids, sc, values, 1.0)
+    assert tok.tolist() == [[7, 3, 7]]
+    assert w[0] == pytest.approx([0.2, 0.4, 0.4], rel=1e-6)
+    assert top.tolist() == [7] and tp[0] == pytest.approx(0.6, rel=1e-6)
+    tok, w, top, tp = oracle.knnlm_probs(ids, sc, values, 2.0)
+    r2 = 2 ** 0.5
+    assert w[0] == pytest.approx([1 / (1 + 2 * r2), r2 / (1 + 2 * r2), r2 / (1 + 2 * r2)], rel=1e-6)
+    # equal probabilities: the smaller token id wins; an unfilled entry carries nothing
+    ids = np.array([[3, 1, -1]], dtype=np.int32)            # tokens 9, 3, none
+    sc = np.array([[1.5, 1.5, 99.0]], dtype=np.float32)
+    tok, w, top, tp = oracle.knnlm_probs(ids, sc, values, 1.0)
+    assert tok.tolist() == [[9, 3, -1]] and w.tolist() == [[0.5, 0.5, 0.0]]
+    assert top.tolist() == [3] and tp.tolist() == [0.5]
+    tok, w, top, tp = oracle.knnlm_probs(np.array([[-1, -1]], dtype=np.int32), np.zeros((1, 2), np.float32), values)
+    assert top.tolist() == [-1] and tp.tolist() == [0.0] and w.tolist() == [[0.0, 0.0]]
+
+
+def test_knnlm_probs_against_library_softmax_and_bincount(oracle):
+    from scipy.special import softmax
+    rng = np.random.default_rng(31)
+    for k, T in ((1, 1.0), (8, 1.0), (100, 0.7), (1024, 10.0)):
+        Q, N, V = 5, 5000, 37
+        values = rng.integers(0, V, size=N).astype(np.int32)
+        ids = np.stack([rng.choice(N, size=k, replace=False) for _ in range(Q)]).astype(np.int32)
+        sc = (rng.standard_normal((Q, k)) * 3 - 1000).astype(np.float32)      # KNN-LM scores are large negatives
+        tok, w, top, tp = oracle.knnlm_probs(ids, sc, values, T)
+        want = softmax(sc.astype(np.float64) / T, axis=1)
+        assert np.array_equal(tok, values[ids])
+        assert w == pytest.approx(want, rel=1e-6)
+        assert w.sum(axis=1) == pytest.approx(1.0, rel=1e-5)
+        for q in range(Q):
+            P = np.bincount(tok[q], weights=want[q], minlength=V)
+            assert top[q] == int(np.argmax(P)) and tp[q] == pytest.approx(P.max(), rel=1e-6)
+        # adding a constant to all scores changes nothing
+        tok2, w2, top2, tp2 = oracle.knnlm_probs(ids, sc + np.float32(512.0), values, T)
+        assert w2 == pytest.approx(w, rel=1e-5) and np.array_equal(top2, top)
+    # a very high temperature flattens the weights
+    _, w, _, _ = oracle.knnlm_probs(ids, sc, values, 1e9)
+    assert w == pytest.approx(1.0 / k, rel=1e-6)
