@@ -246,6 +246,27 @@ ralm_status ralm_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *c
                               int32_t n_next, int64_t N, void *stream);
 
 /*
+ * KNN-LM neighbour distribution (Section 5.3: a distribution over the target
+ * tokens of the k retrieved entries, computed from their distances).  Input is
+ * the output of a retrieval: ids / scores device [Q, k], a larger score being a
+ * closer entry.
+ *
+ *   values       device int32 [N]: target token of every datastore entry
+ *   temperature  T > 0; weight_i = exp(score_i / T) / sum_j exp(score_j / T)
+ *   out_tokens   device int32 [Q, k]: values[ids]  (-1 for an unfilled entry:
+ *                id < 0 or >= N; its weight is 0)
+ *   out_weights  device fp32 [Q, k], each row sums to 1
+ *   out_top_token / out_top_prob  optional device [Q] (either may be NULL): the
+ *                token with the largest summed weight and that sum; the smaller
+ *                token id on ties; -1 / 0 for a query without filled entries.
+ * Sums and exponentials are formed in double and rounded once to fp32.
+ */
+ralm_status ralm_knnlm_probs(const int32_t *ids, const float *scores, int64_t Q, int32_t k,
+                             const int32_t *values, int64_t N, float temperature, int32_t *out_tokens,
+                             float *out_weights, int32_t *out_top_token, float *out_top_prob,
+                             void *stream);
+
+/*
  * Optimal speculation stride scheduler, OS^3 (Section 4; estimation of its
  * parameters: Appendix A.2, "Parameter estimation").  Host-only scalar
  * functions; every pointer is a HOST pointer; nothing is launched.

@@ -62,6 +62,7 @@ def lib() -> ctypes.CDLL:
         L.ralm_cache_lookup.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, vp, vp, vp]
         L.ralm_verify.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp]
         L.ralm_cache_insert.argtypes = [vp, vp, vp, i32, i64, vp, i64, i64, vp, vp, i32, i32, i64, vp]
+        L.ralm_knnlm_probs.argtypes = [vp, vp, i64, i32, vp, i64, ctypes.c_float, vp, vp, vp, vp, vp]
         L.ralm_os3_gamma.argtypes = [vp, vp, i32, ctypes.c_double]
         L.ralm_os3_gamma.restype = ctypes.c_double
         L.ralm_os3_objective.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_double, i32, i32]
@@ -72,7 +73,7 @@ def lib() -> ctypes.CDLL:
         L.ralm_profile_enable.restype = None
         L.ralm_profile_scan_ms.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         for name in ("ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_retrieve_topk_seq", "ralm_workspace_overflows",
-                     "ralm_build_scan_copy", "ralm_cache_lookup", "ralm_verify", "ralm_cache_insert",
+                     "ralm_build_scan_copy", "ralm_cache_lookup", "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs",
                      "ralm_profile_scan_ms"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -238,6 +239,23 @@ def ralm_cache_insert(cache_ids: torch.Tensor, cache_len: torch.Tensor, cache_he
     _check(lib().ralm_cache_insert(cache_ids.data_ptr(), cache_len.data_ptr(), cache_head.data_ptr(), C, R,
                                    true_ids.data_ptr(), true_stride, Qt, q_offsets.data_ptr(),
                                    _ptr(first_mismatch), p, n_next, N, _stream()))
+
+
+def ralm_knnlm_probs(ids: torch.Tensor, scores: torch.Tensor, values: torch.Tensor, temperature: float = 1.0,
+                     want_top: bool = True):
+    """Neighbour distribution of a retrieval result: (tokens, weights, top_token, top_prob)."""
+    assert ids.dtype == torch.int32 and scores.dtype == torch.float32 and values.dtype == torch.int32
+    assert ids.is_contiguous() and scores.is_contiguous() and values.is_contiguous() and ids.shape == scores.shape
+    Q, k = ids.shape
+    dev = ids.device
+    tokens = torch.empty(Q, k, dtype=torch.int32, device=dev)
+    weights = torch.empty(Q, k, dtype=torch.float32, device=dev)
+    top_token = torch.empty(Q, dtype=torch.int32, device=dev) if want_top else None
+    top_prob = torch.empty(Q, dtype=torch.float32, device=dev) if want_top else None
+    _check(lib().ralm_knnlm_probs(ids.data_ptr(), scores.data_ptr(), Q, k, values.data_ptr(), values.shape[0],
+                                  float(temperature), tokens.data_ptr(), weights.data_ptr(), _ptr(top_token),
+                                  _ptr(top_prob), _stream()))
+    return tokens, weights, top_token, top_prob
 
 
 def ralm_os3_gamma(strides, matched, gamma_max: float = 0.6) -> float:

@@ -14,7 +14,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libralm.so")
-SOURCES = ["ralm_api.hip", "scan_kernels.hip", "select_kernels.hip", "cache_verify_kernels.hip", "os3_host.hip"]
+SOURCES = ["ralm_api.hip", "scan_kernels.hip", "select_kernels.hip", "cache_verify_kernels.hip", "knnlm_kernels.hip",
+           "os3_host.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          # the scan kernel's stage bodies are fully unrolled by design (static register indices)

@@ -400,6 +400,21 @@ ralm_status ralm_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *c
     return RALM_OK;
 }
 
+ralm_status ralm_knnlm_probs(const int32_t *ids, const float *scores, int64_t Q, int32_t k, const int32_t *values,
+                             int64_t N, float temperature, int32_t *out_tokens, float *out_weights,
+                             int32_t *out_top_token, float *out_top_prob, void *stream)
+{
+    if (!ids || !scores || !values || !out_tokens || !out_weights) return fail(RALM_ERR_NULL, "a pointer is NULL");
+    if (Q < 0 || Q > 0x7fffffffLL) return fail(RALM_ERR_SHAPE, "Q=%lld out of range", (long long)Q);
+    if (N < 1 || N > 0x7fffffffLL) return fail(RALM_ERR_SHAPE, "N=%lld out of [1, 2^31)", (long long)N);
+    if (k < 1 || k > RALM_MAX_K) return fail(RALM_ERR_K, "k=%d must be in [1, %d]", k, RALM_MAX_K);
+    if (!(temperature > 0.f) || !(temperature < __builtin_inff()))
+        return fail(RALM_ERR_RANGE, "temperature must be positive and finite");
+    RALM_HIP(launch_knnlm_probs(ids, scores, Q, k, values, N, (double)temperature, out_tokens, out_weights,
+                                out_top_token, out_top_prob, static_cast<hipStream_t>(stream)));
+    return RALM_OK;
+}
+
 ralm_status ralm_verify(const int32_t *spec_ids, const int32_t *true_ids, int64_t true_stride, int64_t Qt,
                         const int64_t *q_offsets, int64_t R, int32_t *first_mismatch, void *stream)
 {

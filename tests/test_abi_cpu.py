@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported(L):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(ralm_[a-z0-9_]+)\s*\(", text))
     assert {"ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_retrieve_topk_seq", "ralm_cache_lookup",
-            "ralm_verify", "ralm_cache_insert",
+            "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs", "ralm_os3_stride",
             "ralm_workspace_bytes", "ralm_build_scan_copy", "ralm_last_error"} <= names
     for n in names:
         assert hasattr(L, n), n
@@ -80,6 +80,12 @@ def test_argument_errors_return_status_without_a_device(L):
     assert ins(P, P, P, 4, 2, P, 5, -1, P, None, 1, 0, 1000, None) == 7           # Qt < 0
     assert ins(P, P, P, 4, 2, P, 5, 6, P, None, 1, -1, 1000, None) == 7           # n_next < 0
     assert ins(P, P, P, 4, 2, P, 5, 6, P, None, 1, 0, 0, None) == 2               # N < 1
+    kp = L.ralm_knnlm_probs
+    assert kp(P, P, 4, 8, None, 100, 1.0, P, P, P, P, None) == 1                  # no values array
+    assert kp(P, P, 4, 0, P, 100, 1.0, P, P, P, P, None) == 3                     # k < 1
+    assert kp(P, P, 4, 2000, P, 100, 1.0, P, P, P, P, None) == 3                  # k > max
+    assert kp(P, P, 4, 8, P, 100, 0.0, P, P, P, P, None) == 7                     # temperature not positive
+    assert kp(P, P, 4, 8, P, 0, 1.0, P, P, P, P, None) == 2                       # N < 1
     assert L.ralm_verify(P, None, 1, 6, P, 2, P, None) == 1
     assert L.ralm_verify(P, P, 0, 6, P, 2, P, None) == 7
     assert L.ralm_verify(P, P, 1, 6, P, -1, P, None) == 2

@@ -443,3 +443,55 @@ def test_asynchronous_verification_on_two_streams(B, oracle):
     want_spec, _ = oracle.cache_lookup(cids.cpu().numpy(), clen.cpu().numpy(), q_next.cpu().numpy(), off.numpy(),
                                        X.numpy())
     assert np.array_equal(spec1.cpu().numpy(), want_spec)
+
+
+# ----------------------------------------------------------------------------------------
+# KNN-LM neighbour distribution
+# ----------------------------------------------------------------------------------------
+def _check_probs(got, want, oracle_probs=None):
+    tok, w, top, tp = [t.cpu().numpy() for t in got]
+    wtok, ww, wtop, wtp = want
+    assert np.array_equal(tok, wtok)
+    assert np.allclose(w, ww, rtol=1e-6, atol=1e-30)
+    assert np.allclose(tp, wtp, rtol=1e-6, atol=0)
+    assert np.array_equal(top, wtop)
+
+
+@pytest.mark.parametrize("Q,k,T,V", [(1, 1, 1.0, 5), (7, 8, 1.0, 3), (33, 100, 0.5, 50), (16, 1024, 10.0, 2000),
+                                     (5, 1000, 1.0, 4)])
+def test_knnlm_probs_matches_oracle(B, oracle, Q, k, T, V):
+    rng = np.random.default_rng(Q * 1000 + k)
+    N = 20000
+    values = rng.integers(0, V, size=N).astype(np.int32)
+    ids = np.stack([rng.choice(N, size=k, replace=False) for _ in range(Q)]).astype(np.int32)
+    sc = np.sort((rng.standard_normal((Q, k)) * 4 - 900).astype(np.float32), axis=1)[:, ::-1].copy()
+    if k > 4:
+        ids[0, -3:] = -1                                       # a row with unfilled ranks
+        sc[1, :] = sc[1, 0]                                    # a row of equal scores
+    want = oracle.knnlm_probs(ids, sc, values, T)
+    got = B.ralm_knnlm_probs(torch.from_numpy(ids).cuda(), torch.from_numpy(sc).cuda(),
+                             torch.from_numpy(values).cuda(), T)
+    _check_probs(got, want)
+    assert np.allclose(got[1].sum(dim=1).cpu().numpy(), 1.0, rtol=1e-5)
+
+
+def test_knnlm_probs_hand_case_and_retrieval_output(B, oracle):
+    ln2 = float(np.log(2.0))
+    values = torch.tensor([7, 3, 7, 9], dtype=torch.int32).cuda()
+    tok, w, top, tp = B.ralm_knnlm_probs(torch.tensor([[0, 1, 2]], dtype=torch.int32).cuda(),
+                                         torch.tensor([[0.0, ln2, ln2]]).cuda(), values)
+    assert tok.tolist() == [[7, 3, 7]] and top.tolist() == [7]
+    assert np.allclose(w.cpu().numpy(), [[0.2, 0.4, 0.4]], rtol=1e-6) and abs(float(tp[0]) - 0.6) < 1e-6
+    tok, w, top, tp = B.ralm_knnlm_probs(torch.tensor([[3, 1, -1]], dtype=torch.int32).cuda(),
+                                         torch.tensor([[1.5, 1.5, 99.0]]).cuda(), values)
+    assert tok.tolist() == [[9, 3, -1]] and w.tolist() == [[0.5, 0.5, 0.0]] and top.tolist() == [3]
+    # on the output of a retrieval over fp16 keys (the KNN-LM shape, small): ids and scores feed it as they are
+    from paper_2401_14021_amd import inputs
+    keys, vals = inputs.knnlm_datastore(30000, 128, 16, seed=71)     # keys fp16, target tokens int32
+    Qm = inputs.queries_near_rows(keys, inputs.pick_rows(30000, 12, seed=72), seed=73, sigma=0.5)
+    ds = B.Datastore(keys.cuda(), None)
+    ids, sc = B.ralm_retrieve_topk_ex(Qm.cuda(), ds, 64)
+    vals = (vals % 40).to(torch.int32)                                # few distinct tokens: they repeat among the 64
+    got = B.ralm_knnlm_probs(ids, sc, vals.cuda(), 1.0)
+    want = oracle.knnlm_probs(ids.cpu().numpy(), sc.cpu().numpy(), vals.numpy(), 1.0)
+    _check_probs(got, want)
