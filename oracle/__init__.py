@@ -24,6 +24,7 @@ _SRC = os.path.join(_HERE, "ralm_oracle.c")
 _LIB = os.path.join(_HERE, "libralm_oracle.so")
 
 F32, BF16, F16 = 0, 1, 2
+METRICS = {"ip": 0, "l2": 1}   # inner product; minus the squared Euclidean distance
 _lib = None
 
 
@@ -49,6 +50,14 @@ def _load():
         L.ralm_oracle_cache_lookup.argtypes = [vp, vp, i32, i64, vp, vp, vp, ctypes.c_int, i64, i32,
                                                i64, vp, vp]
         L.ralm_oracle_cache_lookup.restype = ctypes.c_int
+        L.ralm_oracle_scores_metric.argtypes = [vp, vp, ctypes.c_int, i64, i32, i64, ctypes.c_int, vp]
+        L.ralm_oracle_scores_metric.restype = None
+        L.ralm_oracle_retrieve_topk_metric.argtypes = [vp, i64, vp, ctypes.c_int, i64, i32, i64, i32, ctypes.c_int,
+                                                       vp, vp]
+        L.ralm_oracle_retrieve_topk_metric.restype = ctypes.c_int
+        L.ralm_oracle_cache_lookup_metric.argtypes = [vp, vp, i32, i64, vp, vp, vp, ctypes.c_int, i64, i32, i64,
+                                                      ctypes.c_int, vp, vp]
+        L.ralm_oracle_cache_lookup_metric.restype = ctypes.c_int
         L.ralm_oracle_verify.argtypes = [vp, vp, i64, vp, i64, vp]
         L.ralm_oracle_verify.restype = None
         L.ralm_oracle_cache_insert.argtypes = [vp, vp, vp, i32, i64, vp, i64, vp, vp, i32, i32, i64]
@@ -99,18 +108,18 @@ def _ptr(a: np.ndarray):
     return a.ctypes.data_as(ctypes.c_void_p)
 
 
-def scores(q: np.ndarray, X) -> np.ndarray:
-    """All inner products of ONE query with the rows of X; fp32 [n]."""
+def scores(q: np.ndarray, X, metric: str = "ip") -> np.ndarray:
+    """All scores of ONE query with the rows of X; fp32 [n]."""
     Xa, tag = _store_any(X)
     q = np.ascontiguousarray(q, dtype=np.float32)
     n, d = Xa.shape
     assert q.shape == (d,)
     out = np.empty(n, dtype=np.float32)
-    _load().ralm_oracle_scores(_ptr(q), _ptr(Xa), tag, n, d, d, _ptr(out))
+    _load().ralm_oracle_scores_metric(_ptr(q), _ptr(Xa), tag, n, d, d, METRICS[metric], _ptr(out))
     return out
 
 
-def retrieve_topk(queries: np.ndarray, X, k: int) -> Tuple[np.ndarray, np.ndarray]:
+def retrieve_topk(queries: np.ndarray, X, k: int, metric: str = "ip") -> Tuple[np.ndarray, np.ndarray]:
     """Exact top-k of every query over the whole datastore: (ids int32 [Q,k], scores fp32 [Q,k])."""
     Xa, tag = _store_any(X)
     queries = np.ascontiguousarray(queries, dtype=np.float32)
@@ -119,14 +128,15 @@ def retrieve_topk(queries: np.ndarray, X, k: int) -> Tuple[np.ndarray, np.ndarra
     assert d == d2
     ids = np.empty((Q, k), dtype=np.int32)
     sc = np.empty((Q, k), dtype=np.float32)
-    rc = _load().ralm_oracle_retrieve_topk(_ptr(queries), Q, _ptr(Xa), tag, N, d, d, k, _ptr(ids), _ptr(sc))
+    rc = _load().ralm_oracle_retrieve_topk_metric(_ptr(queries), Q, _ptr(Xa), tag, N, d, d, k, METRICS[metric],
+                                                  _ptr(ids), _ptr(sc))
     if rc != 0:
         raise ValueError("oracle retrieve_topk: bad arguments")
     return ids, sc
 
 
-def retrieve_topk_stream(queries: np.ndarray, chunks: Iterable[Tuple[int, object]], k: int
-                         ) -> Tuple[np.ndarray, np.ndarray]:
+def retrieve_topk_stream(queries: np.ndarray, chunks: Iterable[Tuple[int, object]], k: int,
+                         metric: str = "ip") -> Tuple[np.ndarray, np.ndarray]:
     """Same result as ``retrieve_topk`` for a datastore delivered as (base_row, rows) chunks.
 
     Per query a carry list of the best k (score, id) pairs so far is kept; for
@@ -141,7 +151,7 @@ def retrieve_topk_stream(queries: np.ndarray, chunks: Iterable[Tuple[int, object
         n = (rows.bits if isinstance(rows, bf16_store) else rows).shape[0]
         ids_here = np.arange(base, base + n, dtype=np.int64)
         for i in range(Q):
-            s = np.concatenate([carry_s[i], scores(queries[i], rows)])
+            s = np.concatenate([carry_s[i], scores(queries[i], rows, metric)])
             j = np.concatenate([carry_i[i], ids_here])
             order = np.lexsort((j, -s.astype(np.float64)))[:k]
             carry_s[i], carry_i[i] = s[order], j[order]
@@ -151,7 +161,7 @@ def retrieve_topk_stream(queries: np.ndarray, chunks: Iterable[Tuple[int, object
 
 
 def cache_lookup(cache_ids: np.ndarray, cache_len: np.ndarray, queries: np.ndarray,
-                 q_offsets: np.ndarray, X) -> Tuple[np.ndarray, np.ndarray]:
+                 q_offsets: np.ndarray, X, metric: str = "ip") -> Tuple[np.ndarray, np.ndarray]:
     """Speculative top-1 of each query over its request's cached row ids."""
     Xa, tag = _store_any(X)
     cache_ids = np.ascontiguousarray(cache_ids, dtype=np.int32)
@@ -164,8 +174,9 @@ def cache_lookup(cache_ids: np.ndarray, cache_len: np.ndarray, queries: np.ndarr
     assert queries.shape == (Qt, d) and q_offsets.shape == (R + 1,)
     ids = np.empty(Qt, dtype=np.int32)
     sc = np.empty(Qt, dtype=np.float32)
-    rc = _load().ralm_oracle_cache_lookup(_ptr(cache_ids), _ptr(cache_len), C, R, _ptr(queries),
-                                          _ptr(q_offsets), _ptr(Xa), tag, N, d, d, _ptr(ids), _ptr(sc))
+    rc = _load().ralm_oracle_cache_lookup_metric(_ptr(cache_ids), _ptr(cache_len), C, R, _ptr(queries),
+                                                 _ptr(q_offsets), _ptr(Xa), tag, N, d, d, METRICS[metric],
+                                                 _ptr(ids), _ptr(sc))
     if rc != 0:
         raise ValueError("oracle cache_lookup: bad arguments")
     return ids, sc

@@ -108,6 +108,33 @@ static float inner_product(const float *q, const void *X, int dtype, int64_t row
     return (float)sum;
 }
 
+/*
+ * The squared-distance metric of KNN-LM datastores (Section 5.3: entries are
+ * ranked by their distance to the context embedding): the score of a row is
+ * minus its squared Euclidean distance to the query, so that "larger score =
+ * better" holds for both metrics.  Differences of fp32 values are exact in
+ * double; squares and sum in double, left to right, one rounding to fp32.
+ */
+static float neg_sq_distance(const float *q, const void *X, int dtype, int64_t row, int64_t ld,
+                             int32_t d)
+{
+    double sum = 0.0;
+    for (int32_t c = 0; c < d; ++c) {
+        double diff = (double)q[c] - (double)element(X, dtype, row * ld + c);
+        sum += diff * diff;
+    }
+    return (float)(-sum);
+}
+
+enum { ORACLE_IP = 0, ORACLE_L2 = 1 };
+
+static float score_of(int metric, const float *q, const void *X, int dtype, int64_t row, int64_t ld,
+                      int32_t d)
+{
+    return metric == ORACLE_L2 ? neg_sq_distance(q, X, dtype, row, ld, d)
+                               : inner_product(q, X, dtype, row, ld, d);
+}
+
 /* (score descending, id ascending) */
 static int by_score_then_id(const void *pa, const void *pb)
 {
@@ -128,13 +155,19 @@ int ralm_oracle_threads(void)
 #endif
 }
 
-/* scores[j] = <q, X[j]> for j in [0, n): one query against a block of rows */
-void ralm_oracle_scores(const float *q, const void *X, int dtype, int64_t n, int32_t d,
-                        int64_t ld, float *scores)
+/* scores[j] = score of X[j] for j in [0, n): one query against a block of rows */
+void ralm_oracle_scores_metric(const float *q, const void *X, int dtype, int64_t n, int32_t d,
+                               int64_t ld, int metric, float *scores)
 {
 #pragma omp parallel for schedule(static)
     for (int64_t j = 0; j < n; ++j)
-        scores[j] = inner_product(q, X, dtype, j, ld, d);
+        scores[j] = score_of(metric, q, X, dtype, j, ld, d);
+}
+
+void ralm_oracle_scores(const float *q, const void *X, int dtype, int64_t n, int32_t d,
+                        int64_t ld, float *scores)
+{
+    ralm_oracle_scores_metric(q, X, dtype, n, d, ld, ORACLE_IP, scores);
 }
 
 /*
@@ -142,9 +175,9 @@ void ralm_oracle_scores(const float *q, const void *X, int dtype, int64_t n, int
  * the first k.  out_ids/out_scores are [Q, k] row-major.  Returns 0, or -1 on
  * bad arguments / allocation failure.
  */
-int ralm_oracle_retrieve_topk(const float *queries, int64_t Q, const void *X, int dtype,
-                              int64_t N, int32_t d, int64_t ld, int32_t k, int32_t *out_ids,
-                              float *out_scores)
+int ralm_oracle_retrieve_topk_metric(const float *queries, int64_t Q, const void *X, int dtype,
+                                     int64_t N, int32_t d, int64_t ld, int32_t k, int metric,
+                                     int32_t *out_ids, float *out_scores)
 {
     if (Q < 0 || N < 1 || d < 1 || k < 1 || k > N || ld < d) return -1;
     scored_t *all = (scored_t *)malloc((size_t)N * sizeof(scored_t));
@@ -153,7 +186,7 @@ int ralm_oracle_retrieve_topk(const float *queries, int64_t Q, const void *X, in
         const float *q = queries + i * (int64_t)d;
 #pragma omp parallel for schedule(static)
         for (int64_t j = 0; j < N; ++j) {
-            all[j].score = inner_product(q, X, dtype, j, ld, d);
+            all[j].score = score_of(metric, q, X, dtype, j, ld, d);
             all[j].id = (int32_t)j;
         }
         qsort(all, (size_t)N, sizeof(scored_t), by_score_then_id);
@@ -166,6 +199,13 @@ int ralm_oracle_retrieve_topk(const float *queries, int64_t Q, const void *X, in
     return 0;
 }
 
+int ralm_oracle_retrieve_topk(const float *queries, int64_t Q, const void *X, int dtype,
+                              int64_t N, int32_t d, int64_t ld, int32_t k, int32_t *out_ids,
+                              float *out_scores)
+{
+    return ralm_oracle_retrieve_topk_metric(queries, Q, X, dtype, N, d, ld, k, ORACLE_IP, out_ids, out_scores);
+}
+
 /*
  * Speculative retrieval from the per-request local cache.  Request r owns the
  * row ids cache_ids[r*C .. r*C + cache_len[r]) and the queries
@@ -173,10 +213,10 @@ int ralm_oracle_retrieve_topk(const float *queries, int64_t Q, const void *X, in
  * the retriever's own metric and take the first.  An empty cache gives id -1
  * and score -inf.
  */
-int ralm_oracle_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C,
-                             int64_t R, const float *queries, const int64_t *q_offsets,
-                             const void *X, int dtype, int64_t N, int32_t d, int64_t ld,
-                             int32_t *spec_ids, float *spec_scores)
+int ralm_oracle_cache_lookup_metric(const int32_t *cache_ids, const int32_t *cache_len, int32_t C,
+                                    int64_t R, const float *queries, const int64_t *q_offsets,
+                                    const void *X, int dtype, int64_t N, int32_t d, int64_t ld,
+                                    int metric, int32_t *spec_ids, float *spec_scores)
 {
     if (R < 0 || C < 0 || d < 1 || ld < d) return -1;
     scored_t *ranked = (scored_t *)malloc((size_t)(C > 0 ? C : 1) * sizeof(scored_t));
@@ -189,7 +229,7 @@ int ralm_oracle_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len,
             for (int32_t e = 0; e < len; ++e) {
                 int32_t id = cache_ids[r * (int64_t)C + e];
                 if (id < 0 || id >= N) { free(ranked); return -1; }
-                ranked[e].score = inner_product(q, X, dtype, id, ld, d);
+                ranked[e].score = score_of(metric, q, X, dtype, id, ld, d);
                 ranked[e].id = id;
             }
             qsort(ranked, (size_t)len, sizeof(scored_t), by_score_then_id);
@@ -199,6 +239,15 @@ int ralm_oracle_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len,
     }
     free(ranked);
     return 0;
+}
+
+int ralm_oracle_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C,
+                             int64_t R, const float *queries, const int64_t *q_offsets,
+                             const void *X, int dtype, int64_t N, int32_t d, int64_t ld,
+                             int32_t *spec_ids, float *spec_scores)
+{
+    return ralm_oracle_cache_lookup_metric(cache_ids, cache_len, C, R, queries, q_offsets, X, dtype, N, d, ld,
+                                           ORACLE_IP, spec_ids, spec_scores);
 }
 
 /*

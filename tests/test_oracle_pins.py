@@ -552,3 +552,57 @@ def test_knnlm_probs_against_library_softmax_and_bincount(oracle):
     # a very high temperature flattens the weights
     _, w, _, _ = oracle.knnlm_probs(ids, sc, values, 1e9)
     assert w == pytest.approx(1.0 / k, rel=1e-6)
+
+
+# ----------------------------------------------------------------------------------------
+# squared-distance metric (KNN-LM datastores rank by distance, Section 5.3)
+# ----------------------------------------------------------------------------------------
+def test_l2_metric_hand_case_and_integer_grid(oracle):
+    """Rows (0,0) (3,4) (1,1) (3,4) (-1,2), query (1,2): squared distances 5, 8, 1, 8, 4, so the
+    ranking is 2, 4, 0, 1, 3 (the equal pair by id) with scores -1, -4, -5, -8, -8."""
+    X = np.array([[0, 0], [3, 4], [1, 1], [3, 4], [-1, 2]], dtype=np.float32)
+    q = np.array([[1, 2]], dtype=np.float32)
+    ids, sc = oracle.retrieve_topk(q, X, 5, metric="l2")
+    assert ids.tolist() == [[2, 4, 0, 1, 3]] and sc.tolist() == [[-1, -4, -5, -8, -8]]
+    assert oracle.scores(q[0], X, "l2").tolist() == [-5, -8, -1, -8, -4]
+    # exhaustive on a small integer grid against integer arithmetic
+    pts = np.array(list(itertools.product(range(-2, 3), repeat=3)), dtype=np.float32)
+    for qv in ([0, 0, 0], [1, -2, 2], [3, 3, -3]):
+        want = sorted(range(len(pts)), key=lambda j: (sum((int(a) - b) ** 2 for a, b in zip(pts[j], qv)), j))
+        ids, sc = oracle.retrieve_topk(np.array([qv], dtype=np.float32), pts, len(pts), metric="l2")
+        assert ids[0].tolist() == want
+        assert sc[0].tolist() == [-float(sum((int(a) - b) ** 2 for a, b in zip(pts[j], qv))) for j in want]
+
+
+def test_l2_metric_against_float64_and_inner_product_on_unit_rows(oracle):
+    rng = np.random.default_rng(41)
+    X = rng.standard_normal((3000, 24)).astype(np.float32)
+    Qm = rng.standard_normal((4, 24)).astype(np.float32)
+    ids, sc = oracle.retrieve_topk(Qm, X, 50, metric="l2")
+    d2 = ((Qm[:, None, :].astype(np.float64) - X[None].astype(np.float64)) ** 2).sum(axis=2)
+    for i in range(4):
+        order = np.lexsort((np.arange(3000), d2[i]))[:50]
+        got = d2[i][ids[i]]
+        assert np.allclose(got, d2[i][order], rtol=1e-6)          # same distances rank by rank
+        assert sc[i] == pytest.approx(-d2[i][ids[i]], rel=1e-6)
+        # fp16 keys are widened exactly before the subtraction
+    Xh = X.astype(np.float16)
+    ids_h, sc_h = oracle.retrieve_topk(Qm, Xh, 5, metric="l2")
+    d2h = ((Qm[:, None, :].astype(np.float64) - Xh[None].astype(np.float64)) ** 2).sum(axis=2)
+    assert np.array_equal(ids_h, np.argsort(d2h, axis=1, kind="stable")[:, :5])
+    # rows of equal norm: the distance ranking is the inner-product ranking,
+    # -|q - x|^2 = 2 <q, x> - |x|^2 - |q|^2
+    U = X / np.linalg.norm(X, axis=1, keepdims=True)
+    U = (U * 4).astype(np.float32)                      # norm 4 up to fp32 rounding
+    a, _ = oracle.retrieve_topk(Qm, U, 10, metric="l2")
+    b, _ = oracle.retrieve_topk(Qm, U, 10, metric="ip")
+    assert np.array_equal(a, b)
+    # a query that is a row: distance zero, that row first
+    ids, sc = oracle.retrieve_topk(X[77:78], X, 1, metric="l2")
+    assert ids.tolist() == [[77]] and sc.tolist() == [[0.0]]
+    # cache lookup uses the same metric: it is the retrieval on the gathered rows
+    cache = np.array([[5, 900, 77, 13]], dtype=np.int32)
+    spec, ssc = oracle.cache_lookup(cache, [4], X[77:78] + 0.01, [0, 1], X, metric="l2")
+    assert spec.tolist() == [77]
+    sub_ids, sub_sc = oracle.retrieve_topk(X[77:78] + 0.01, X[cache[0]], 1, metric="l2")
+    assert cache[0][sub_ids[0, 0]] == spec[0] and sub_sc[0, 0] == ssc[0]
