@@ -24,9 +24,9 @@
  *   - The ranking is always (score descending, row id ascending): equal scores
  *     go to the lower id.  The paper does not define ties; this is this
  *     library's rule, at every stage.
- *   - The score is the inner product.  Final scores (outputs) are the fp32
- *     rounding of a sum formed in double from fp32 (or exactly widened
- *     fp16/bf16) inputs.
+ *   - The score is the inner product, or minus the squared distance (see
+ *     ralm_metric).  Final scores (outputs) are the fp32 rounding of a sum
+ *     formed in double from fp32 (or exactly widened fp16/bf16) inputs.
  *   - Argument errors are detected on the host before anything is launched and
  *     are reported as a status; ralm_last_error() gives the text.  Inputs are
  *     assumed finite (NaN/Inf: behaviour unspecified).
@@ -56,6 +56,14 @@ typedef enum {
 
 typedef enum { RALM_F32 = 0, RALM_BF16 = 1, RALM_F16 = 2 } ralm_dtype;
 
+/*
+ * Score of a row x for a query q.  RALM_METRIC_IP: the inner product <q, x>
+ * (dense passage retrieval).  RALM_METRIC_L2: minus the squared Euclidean
+ * distance, -|q - x|^2 (KNN-LM datastores rank their entries by distance,
+ * Section 5.3), so that a larger score is a better match under both.
+ */
+typedef enum { RALM_METRIC_IP = 0, RALM_METRIC_L2 = 1 } ralm_metric;
+
 #define RALM_MAX_K 1024
 #define RALM_MAX_K_PRIME 4096
 
@@ -72,6 +80,13 @@ typedef enum { RALM_F32 = 0, RALM_BF16 = 1, RALM_F16 = 2 } ralm_dtype;
  *          NULL means "use the exact copy".
  *   *_stride  row pitch in ELEMENTS (0 = d).  Pitch in bytes and both base
  *          pointers must be multiples of 16.  d must be a multiple of 8.
+ *   metric RALM_METRIC_IP (0) or RALM_METRIC_L2.  With RALM_METRIC_L2 the scan
+ *          copy is mandatory, bf16 or fp16, and its rows have d + 8 columns:
+ *          the d rounded elements, then the row's squared norm as the sum of
+ *          two scan-dtype numbers, then six zeros (ralm_build_scan_copy_l2
+ *          writes this layout; scan_stride 0 = d + 8).  The scan then scores a
+ *          row as 2<q, x> - |x|^2 on the matrix cores with no change to its
+ *          kernels; final scores are -|q - x|^2 from the exact copy.
  */
 typedef struct {
     const void *exact;
@@ -82,6 +97,7 @@ typedef struct {
     int32_t d;
     int64_t exact_stride;
     int64_t scan_stride;
+    int32_t metric;         /* RALM_METRIC_IP or RALM_METRIC_L2 */
 } ralm_datastore_t;
 
 /*
@@ -117,7 +133,7 @@ size_t ralm_workspace_bytes(int64_t Q, const ralm_datastore_t *ds, int32_t k, in
  *   out_ids / out_scores  device [Q, k] as above
  *   out_margin  optional device fp32 [Q] (may be NULL): exact score of the
  *               returned rank-k row minus the scan score of the k'-th kept
- *               candidate.  A positive margin larger than the scan's rounding
+ *               candidate (brought to the same scale under RALM_METRIC_L2).  A positive margin larger than the scan's rounding
  *               error proves that no row outside the candidates can belong in
  *               the top k.
  *   workspace   device scratch, 256-byte aligned, >= ralm_workspace_bytes();
@@ -166,6 +182,19 @@ ralm_status ralm_workspace_overflows(const void *workspace, void *stream, int32_
  */
 ralm_status ralm_build_scan_copy(const float *src, int64_t src_stride, void *dst, int32_t dst_dtype,
                                  int64_t dst_stride, int64_t N, int32_t d, void *stream);
+
+/*
+ * Scan copy for RALM_METRIC_L2: dst[j, 0..d) = round-to-nearest-even(src[j, c])
+ * in dst_dtype; dst[j, d] + dst[j, d+1] = |src_j|^2 (summed in double, split
+ * into a rounded head and the rounded remainder); dst[j, d+2 .. d+8) = 0.
+ * src is device fp32 or fp16 [N, d] (src_dtype), dst device [N, d + 8] bf16 or
+ * fp16; strides in elements (0 = d, d + 8).  src == dst is allowed for fp16
+ * keys stored with a pitch of at least d + 8 that serve as their own scan
+ * copy: then only the 8 extra columns are written.
+ */
+ralm_status ralm_build_scan_copy_l2(const void *src, int32_t src_dtype, int64_t src_stride, void *dst,
+                                    int32_t dst_dtype, int64_t dst_stride, int64_t N, int32_t d,
+                                    void *stream);
 
 /*
  * Speculative retrieval from the per-request local caches (Alg. 1, the

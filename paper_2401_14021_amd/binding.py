@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("RALM_LIB_PATH") or os.path.join(_HERE, "libralm.so")
 
 RALM_F32, RALM_BF16, RALM_F16 = 0, 1, 2
+RALM_METRIC_IP, RALM_METRIC_L2 = 0, 1
 _DT = {torch.float32: RALM_F32, torch.bfloat16: RALM_BF16, torch.float16: RALM_F16}
 
 STATUS = {0: "RALM_OK", 1: "RALM_ERR_NULL", 2: "RALM_ERR_SHAPE", 3: "RALM_ERR_K", 4: "RALM_ERR_DTYPE",
@@ -28,7 +29,8 @@ class ralm_datastore_t(ctypes.Structure):
     _fields_ = [("exact", ctypes.c_void_p), ("exact_dtype", ctypes.c_int32),
                 ("scan", ctypes.c_void_p), ("scan_dtype", ctypes.c_int32),
                 ("N", ctypes.c_int64), ("d", ctypes.c_int32),
-                ("exact_stride", ctypes.c_int64), ("scan_stride", ctypes.c_int64)]
+                ("exact_stride", ctypes.c_int64), ("scan_stride", ctypes.c_int64),
+                ("metric", ctypes.c_int32)]
 
 
 class RalmError(RuntimeError):
@@ -59,6 +61,7 @@ def lib() -> ctypes.CDLL:
         L.ralm_retrieve_topk_seq.argtypes = L.ralm_retrieve_topk_ex.argtypes
         L.ralm_workspace_overflows.argtypes = [vp, vp, ctypes.POINTER(i32)]
         L.ralm_build_scan_copy.argtypes = [vp, i64, vp, i32, i64, i64, i32, vp]
+        L.ralm_build_scan_copy_l2.argtypes = [vp, i32, i64, vp, i32, i64, i64, i32, vp]
         L.ralm_cache_lookup.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, vp, vp, vp]
         L.ralm_verify.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp]
         L.ralm_cache_insert.argtypes = [vp, vp, vp, i32, i64, vp, i64, i64, vp, vp, i32, i32, i64, vp]
@@ -73,7 +76,7 @@ def lib() -> ctypes.CDLL:
         L.ralm_profile_enable.restype = None
         L.ralm_profile_scan_ms.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         for name in ("ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_retrieve_topk_seq", "ralm_workspace_overflows",
-                     "ralm_build_scan_copy", "ralm_cache_lookup", "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs",
+                     "ralm_build_scan_copy", "ralm_build_scan_copy_l2", "ralm_cache_lookup", "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs",
                      "ralm_profile_scan_ms"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -96,17 +99,19 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
 class Datastore:
     """Holds the exact copy and (optionally) the low-precision scan copy of the keys."""
 
-    def __init__(self, exact: torch.Tensor, scan: Optional[torch.Tensor] = None):
+    def __init__(self, exact: torch.Tensor, scan: Optional[torch.Tensor] = None, metric: int = RALM_METRIC_IP):
         assert exact.dim() == 2 and exact.stride(1) == 1
         self.exact, self.scan = exact, scan
         self.N, self.d = exact.shape
         self.desc = ralm_datastore_t()
+        self.desc.metric = metric
         self.desc.exact = exact.data_ptr()
         self.desc.exact_dtype = _DT[exact.dtype]
         self.desc.exact_stride = exact.stride(0)
         self.desc.N, self.desc.d = self.N, self.d
         if scan is not None:
-            assert scan.shape == exact.shape and scan.stride(1) == 1
+            extra = 8 if metric == RALM_METRIC_L2 else 0
+            assert scan.shape == (self.N, self.d + extra) and scan.stride(1) == 1
             self.desc.scan = scan.data_ptr()
             self.desc.scan_dtype = _DT[scan.dtype]
             self.desc.scan_stride = scan.stride(0)
@@ -122,6 +127,18 @@ class Datastore:
         scan = torch.empty(exact.shape, dtype=scan_dtype, device=exact.device)
         ralm_build_scan_copy(exact, scan)
         return cls(exact, scan)
+
+
+    @classmethod
+    def for_l2(cls, exact: torch.Tensor, scan_dtype: Optional[torch.dtype] = None) -> "Datastore":
+        """Squared-distance metric: builds the [N, d + 8] scan copy (rounded row + its squared norm)."""
+        if scan_dtype is None:
+            scan_dtype = torch.float16 if exact.dtype == torch.float16 else torch.bfloat16
+        N, d = exact.shape
+        scan = torch.empty(N, d + 8, dtype=scan_dtype, device=exact.device)
+        _check(lib().ralm_build_scan_copy_l2(exact.data_ptr(), _DT[exact.dtype], exact.stride(0), scan.data_ptr(),
+                                             _DT[scan_dtype], scan.stride(0), N, d, _stream()))
+        return cls(exact, scan, RALM_METRIC_L2)
 
 
 def ralm_build_scan_copy(src: torch.Tensor, dst: torch.Tensor) -> None:

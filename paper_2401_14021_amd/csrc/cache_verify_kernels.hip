@@ -36,7 +36,8 @@ __device__ __forceinline__ void clamp_range(const int64_t *off, int64_t r, int64
 // NCH = float4 chunks of a row held by one lane (row element (c*CL_GS + sub)*4 .. +4).
 // One block of NW waves per request: every wave step gathers CL_ROWS cached rows, so a block
 // has NW*CL_ROWS random row reads in flight; the other waves' arithmetic hides their latency.
-template <int EX, int NCH, int NW>
+// L2: the score is minus the squared distance (KNN-LM datastores) instead of the inner product.
+template <int EX, int NCH, int NW, bool L2>
 __global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
     const int32_t *__restrict__ cache_ids, const int32_t *__restrict__ cache_len, int C,
     const float *__restrict__ queries, int64_t Qt, const int64_t *__restrict__ q_offsets,
@@ -94,16 +95,25 @@ __global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
                     const int j = (c * CL_GS + sub) * 4;
                     if (j < d) {
                         const float4 y = *reinterpret_cast<const float4 *>(qv + j);
-                        sum += (double)x[c].x * (double)y.x;
-                        sum += (double)x[c].y * (double)y.y;
-                        sum += (double)x[c].z * (double)y.z;
-                        sum += (double)x[c].w * (double)y.w;
+                        if constexpr (L2) {
+                            const double d0 = (double)y.x - (double)x[c].x, d1 = (double)y.y - (double)x[c].y;
+                            const double d2 = (double)y.z - (double)x[c].z, d3 = (double)y.w - (double)x[c].w;
+                            sum += d0 * d0;
+                            sum += d1 * d1;
+                            sum += d2 * d2;
+                            sum += d3 * d3;
+                        } else {
+                            sum += (double)x[c].x * (double)y.x;
+                            sum += (double)x[c].y * (double)y.y;
+                            sum += (double)x[c].z * (double)y.z;
+                            sum += (double)x[c].w * (double)y.w;
+                        }
                     }
                 }
 #pragma unroll
                 for (int o = CL_GS / 2; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
                 if (sub == 0 && ok) {
-                    const u64 key = make_key((float)sum, id);
+                    const u64 key = make_key(L2 ? (float)(-sum) : (float)sum, id);
                     if (key > my_best[qi]) my_best[qi] = key;
                 }
             }
@@ -222,7 +232,9 @@ __global__ void fill_u64_kernel(u64 *p, u64 v, int64_t n)
 }
 
 // query preparation: queries rounded to the scan dtype, zero padded to [Qpad, dpad]
-template <int DT>
+// L2: the scan scores a row as 2<q, x> - |x|^2, its squared norm being stored behind the row as the
+// sum of two scan-dtype numbers (columns d and d+1): the query is doubled and gets -1 in both.
+template <int DT, bool L2>
 __global__ void query_prep_kernel(const float *__restrict__ q, int64_t Q, int d, uint16_t *__restrict__ out,
                                   int64_t Qpad, int dpad)
 {
@@ -231,7 +243,8 @@ __global__ void query_prep_kernel(const float *__restrict__ q, int64_t Q, int d,
         const int64_t row = i / dpad;
         const int col = (int)(i % dpad);
         uint32_t bits = 0;
-        if (row < Q && col < d) bits = f32_to_scan_bits<DT>(q[row * d + col]);
+        if (row < Q && col < d) bits = f32_to_scan_bits<DT>(L2 ? 2.f * q[row * d + col] : q[row * d + col]);
+        if (L2 && row < Q && (col == d || col == d + 1)) bits = f32_to_scan_bits<DT>(-1.f);
         out[i] = (uint16_t)bits;
     }
 }
@@ -251,6 +264,47 @@ __global__ void convert_rows_kernel(const float *__restrict__ src, int64_t src_l
     }
 }
 
+// Scan copy for the squared-distance metric: one wave per row.  dst row = the d elements rounded
+// to the scan dtype (skipped when dst is src: fp16 keys that are their own scan copy), then the
+// row's squared norm (summed in double from the source) as hi + lo in the scan dtype, then six
+// zeros: 8 extra columns, 16 bytes.
+template <int SRC, int DT>
+__global__ __launch_bounds__(256) void l2_scan_copy_kernel(const void *src, int64_t src_ld,
+                                                            uint16_t *dst, int64_t dst_ld, int64_t N, int d,
+                                                            int in_place)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= N) return;
+    double sum = 0.0;
+    for (int c = lane * 8; c < d; c += 512) {
+        float4 a, b;
+        if constexpr (SRC == DT_F32) {
+            const float *s = static_cast<const float *>(src) + row * src_ld + c;
+            a = *reinterpret_cast<const float4 *>(s);
+            b = *reinterpret_cast<const float4 *>(s + 4);
+        } else {
+            const uint4 h = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(src) + row * src_ld + c);
+            a = make_float4(f16_bits_to_f32(h.x & 0xffffu), f16_bits_to_f32(h.x >> 16),
+                            f16_bits_to_f32(h.y & 0xffffu), f16_bits_to_f32(h.y >> 16));
+            b = make_float4(f16_bits_to_f32(h.z & 0xffffu), f16_bits_to_f32(h.z >> 16),
+                            f16_bits_to_f32(h.w & 0xffffu), f16_bits_to_f32(h.w >> 16));
+        }
+        sum += (double)a.x * (double)a.x + (double)a.y * (double)a.y + (double)a.z * (double)a.z +
+               (double)a.w * (double)a.w + (double)b.x * (double)b.x + (double)b.y * (double)b.y +
+               (double)b.z * (double)b.z + (double)b.w * (double)b.w;
+        if (!in_place) *reinterpret_cast<uint4 *>(dst + row * dst_ld + c) = pack8<DT>(a, b);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    if (lane == 0) {
+        const uint32_t hi = f32_to_scan_bits<DT>((float)sum);
+        const float hi_f = DT == DT_F16 ? f16_bits_to_f32(hi) : __uint_as_float(hi << 16);
+        const uint32_t lo = f32_to_scan_bits<DT>((float)(sum - (double)hi_f));
+        *reinterpret_cast<uint4 *>(dst + row * dst_ld + d) = make_uint4(hi | (lo << 16), 0u, 0u, 0u);
+    }
+}
+
 int grid_for(int64_t n, int block)
 {
     int64_t g = (n + block - 1) / block;
@@ -259,7 +313,7 @@ int grid_for(int64_t n, int block)
     return (int)g;
 }
 
-template <int EX>
+template <int EX, bool L2>
 hipError_t launch_cache_ex(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
                            const float *queries, int64_t Qt, const int64_t *q_offsets, const void *exact,
                            int64_t ld, int64_t N, int32_t d, int32_t *spec_ids, float *spec_scores,
@@ -271,7 +325,7 @@ hipError_t launch_cache_ex(const int32_t *cache_ids, const int32_t *cache_len, i
     const int nch = (d + CL_GS * 4 - 1) / (CL_GS * 4);
     // a lane keeps its NCH chunks in registers, which bounds the waves a block can hold
 #define RALM_CL(NCHV, NWV)                                                                                  \
-    hipLaunchKernelGGL((cache_lookup_kernel<EX, NCHV, NWV>), dim3((unsigned)R), dim3(NWV * 64),             \
+    hipLaunchKernelGGL((cache_lookup_kernel<EX, NCHV, NWV, L2>), dim3((unsigned)R), dim3(NWV * 64),             \
                        (size_t)qgroup * d * 4 + (size_t)NWV * CL_ROWS * qgroup * sizeof(u64), stream,       \
                        cache_ids, cache_len, C, queries, Qt, q_offsets, exact, ld, N, d, qgroup, spec_ids,  \
                        spec_scores)
@@ -290,14 +344,19 @@ hipError_t launch_cache_ex(const int32_t *cache_ids, const int32_t *cache_len, i
 hipError_t launch_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
                                const float *queries, int64_t Qt, const int64_t *q_offsets,
                                const void *exact, int32_t exact_dtype, int64_t ld, int64_t N, int32_t d,
-                               int32_t *spec_ids, float *spec_scores, hipStream_t stream)
+                               int32_t metric, int32_t *spec_ids, float *spec_scores, hipStream_t stream)
 {
     if (R <= 0) return hipSuccess;
-    if (exact_dtype == DT_F16)
-        return launch_cache_ex<DT_F16>(cache_ids, cache_len, C, R, queries, Qt, q_offsets, exact, ld, N, d,
-                                       spec_ids, spec_scores, stream);
-    return launch_cache_ex<DT_F32>(cache_ids, cache_len, C, R, queries, Qt, q_offsets, exact, ld, N, d,
-                                   spec_ids, spec_scores, stream);
+#define RALM_CACHE(EXV, L2V)                                                                             \
+    return launch_cache_ex<EXV, L2V>(cache_ids, cache_len, C, R, queries, Qt, q_offsets, exact, ld, N, d, \
+                                     spec_ids, spec_scores, stream)
+    if (exact_dtype == DT_F16) {
+        if (metric == METRIC_L2) RALM_CACHE(DT_F16, true);
+        RALM_CACHE(DT_F16, false);
+    }
+    if (metric == METRIC_L2) RALM_CACHE(DT_F32, true);
+    RALM_CACHE(DT_F32, false);
+#undef RALM_CACHE
 }
 
 hipError_t launch_verify(const int32_t *spec, const int32_t *truth, int64_t true_stride, int64_t Qt,
@@ -341,17 +400,44 @@ hipError_t launch_fill_u64(u64 *p, u64 v, int64_t n, hipStream_t stream)
     return hipGetLastError();
 }
 
+hipError_t launch_l2_scan_copy(const void *src, int32_t src_dtype, int64_t src_ld, void *dst, int32_t dst_dtype,
+                               int64_t dst_ld, int64_t N, int32_t d, hipStream_t stream)
+{
+    if (N <= 0) return hipSuccess;
+    const int in_place = src == dst ? 1 : 0;
+    const dim3 grid((unsigned)((N + 3) / 4)), block(256);
+    uint16_t *out = static_cast<uint16_t *>(dst);
+    if (src_dtype == DT_F16) {
+        if (dst_dtype == DT_F16)
+            hipLaunchKernelGGL((l2_scan_copy_kernel<DT_F16, DT_F16>), grid, block, 0, stream, src, src_ld, out, dst_ld, N, d, in_place);
+        else
+            hipLaunchKernelGGL((l2_scan_copy_kernel<DT_F16, DT_BF16>), grid, block, 0, stream, src, src_ld, out, dst_ld, N, d, in_place);
+    } else {
+        if (dst_dtype == DT_F16)
+            hipLaunchKernelGGL((l2_scan_copy_kernel<DT_F32, DT_F16>), grid, block, 0, stream, src, src_ld, out, dst_ld, N, d, in_place);
+        else
+            hipLaunchKernelGGL((l2_scan_copy_kernel<DT_F32, DT_BF16>), grid, block, 0, stream, src, src_ld, out, dst_ld, N, d, in_place);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_query_prep(const float *q, int64_t Q, int32_t d, uint16_t *out, int64_t Qpad, int32_t dpad,
-                             int32_t scan_dtype, hipStream_t stream)
+                             int32_t scan_dtype, int32_t metric, hipStream_t stream)
 {
     const int64_t n = Qpad * dpad;
     if (n <= 0) return hipSuccess;
-    if (scan_dtype == DT_F16)
-        hipLaunchKernelGGL(query_prep_kernel<DT_F16>, dim3(grid_for(n, 256)), dim3(256), 0, stream, q, Q, d,
-                           out, Qpad, dpad);
-    else
-        hipLaunchKernelGGL(query_prep_kernel<DT_BF16>, dim3(grid_for(n, 256)), dim3(256), 0, stream, q, Q, d,
-                           out, Qpad, dpad);
+    const dim3 grid(grid_for(n, 256)), block(256);
+    if (scan_dtype == DT_F16) {
+        if (metric == METRIC_L2)
+            hipLaunchKernelGGL((query_prep_kernel<DT_F16, true>), grid, block, 0, stream, q, Q, d, out, Qpad, dpad);
+        else
+            hipLaunchKernelGGL((query_prep_kernel<DT_F16, false>), grid, block, 0, stream, q, Q, d, out, Qpad, dpad);
+    } else {
+        if (metric == METRIC_L2)
+            hipLaunchKernelGGL((query_prep_kernel<DT_BF16, true>), grid, block, 0, stream, q, Q, d, out, Qpad, dpad);
+        else
+            hipLaunchKernelGGL((query_prep_kernel<DT_BF16, false>), grid, block, 0, stream, q, Q, d, out, Qpad, dpad);
+    }
     return hipGetLastError();
 }
 

@@ -60,6 +60,9 @@ struct Plan {
     size_t off_q, off_tau, off_cnt, off_flags, off_cand, off_sel, total;
 };
 
+// columns of a scan-copy row: the squared-distance metric keeps the row's squared norm behind it
+int32_t scan_cols(const ralm_datastore_t *ds) { return ds->d + (ds->metric == RALM_METRIC_L2 ? L2_EXTRA_COLS : 0); }
+
 int32_t default_k_prime(int32_t k)
 {
     if (k <= 32) return 64;
@@ -90,7 +93,7 @@ ralm_status make_plan(int64_t Q, const ralm_datastore_t *ds, int32_t k, int32_t 
     pl.cap = (uint32_t)(safety * k_prime * (g_coarse - 1) + k_prime);
     if (pl.cap < 16384u) pl.cap = 16384u;
     pl.Qpad = (Q + SCAN_QPAD - 1) / SCAN_QPAD * SCAN_QPAD;
-    pl.dpad = (ds->d + SCAN_BK - 1) / SCAN_BK * SCAN_BK;
+    pl.dpad = (scan_cols(ds) + SCAN_BK - 1) / SCAN_BK * SCAN_BK;
 
     const int64_t tiles = (ds->N + SCAN_BM - 1) / SCAN_BM;
     auto fits = [&](int64_t s) { return ((tiles + s - 1) / s) * SCAN_BM <= (int64_t)pl.cap; };
@@ -132,11 +135,18 @@ ralm_status check_datastore(const ralm_datastore_t *ds, bool need_scan)
     if (es < ds->d) return fail(RALM_ERR_SHAPE, "exact_stride < d");
     if (!aligned16(ds->exact) || (es * elem_bytes(ds->exact_dtype)) % 16)
         return fail(RALM_ERR_ALIGN, "exact copy: base and row pitch must be multiples of 16 bytes");
+    if (ds->metric != RALM_METRIC_IP && ds->metric != RALM_METRIC_L2) return fail(RALM_ERR_DTYPE, "metric unknown");
+    if (need_scan && ds->metric == RALM_METRIC_L2) {
+        if (!ds->scan) return fail(RALM_ERR_NULL, "the squared-distance metric needs a scan copy built by ralm_build_scan_copy_l2");
+        if (ds->scan_dtype != RALM_BF16 && ds->scan_dtype != RALM_F16)
+            return fail(RALM_ERR_DTYPE, "the squared-distance metric needs a bf16 or fp16 scan copy");
+    }
     if (need_scan && ds->scan) {
         if (ds->scan_dtype != RALM_BF16 && ds->scan_dtype != RALM_F16 && ds->scan_dtype != RALM_F32)
             return fail(RALM_ERR_DTYPE, "scan_dtype unknown");
-        const int64_t ss = ds->scan_stride ? ds->scan_stride : ds->d;
-        if (ss < ds->d) return fail(RALM_ERR_SHAPE, "scan_stride < d");
+        const int64_t sd = scan_cols(ds);
+        const int64_t ss = ds->scan_stride ? ds->scan_stride : sd;
+        if (ss < sd) return fail(RALM_ERR_SHAPE, "scan_stride < d (+ 8 norm columns for the squared-distance metric)");
         if (!aligned16(ds->scan) || (ss * elem_bytes(ds->scan_dtype)) % 16)
             return fail(RALM_ERR_ALIGN, "scan copy: base and row pitch must be multiples of 16 bytes");
     }
@@ -214,18 +224,18 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
 
     const void *scan = ds->scan ? ds->scan : ds->exact;
     const int scan_dt = ds->scan ? ds->scan_dtype : ds->exact_dtype;
-    const int64_t scan_ld = ds->scan ? (ds->scan_stride ? ds->scan_stride : ds->d)
+    const int64_t scan_ld = ds->scan ? (ds->scan_stride ? ds->scan_stride : scan_cols(ds))
                                      : (ds->exact_stride ? ds->exact_stride : ds->d);
     const int mma_dt = scan_dt == RALM_F16 ? RALM_F16 : RALM_BF16;   // fp32 rows are rounded to bf16
     const int n_cu = device_cus();
 
-    RALM_HIP(launch_query_prep(queries, Q, ds->d, qs, pl.Qpad, pl.dpad, mma_dt, stream));
+    RALM_HIP(launch_query_prep(queries, Q, ds->d, qs, pl.Qpad, pl.dpad, mma_dt, ds->metric, stream));
     RALM_HIP(launch_fill_u64(tau, 0ull, pl.Qpad, stream));
     RALM_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(flags), 0u, 64, stream));
     RALM_HIP(launch_fill_u32(cnt, 0u, pl.Qpad, stream));
 
     ScanParams sp;
-    sp.X = scan; sp.ldx = scan_ld; sp.N = ds->N; sp.d = ds->d; sp.in_dtype = scan_dt;
+    sp.X = scan; sp.ldx = scan_ld; sp.N = ds->N; sp.d = scan_cols(ds); sp.in_dtype = scan_dt;
     sp.Qs = qs; sp.dpad = pl.dpad; sp.Q = (int32_t)Q;
     sp.tau = tau; sp.cand = cand; sp.cnt = cnt; sp.cap = pl.cap;
     // one stage: scan the tiles sp describes, then cut every list down to its k' best
@@ -282,8 +292,8 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
         }
     }
     const int64_t exact_ld = ds->exact_stride ? ds->exact_stride : ds->d;
-    RALM_HIP(launch_rescore(cand, cnt, pl.cap, pl.k_prime, queries, Q, ds->exact, ds->exact_dtype, exact_ld, ds->d, k,
-                            out_ids, out_scores, out_margin, stream));
+    RALM_HIP(launch_rescore(cand, cnt, pl.cap, pl.k_prime, queries, Q, ds->exact, ds->exact_dtype, exact_ld, ds->d,
+                            ds->metric, k, out_ids, out_scores, out_margin, stream));
     return RALM_OK;
 }
 
@@ -365,6 +375,25 @@ ralm_status ralm_build_scan_copy(const float *src, int64_t src_stride, void *dst
     return RALM_OK;
 }
 
+ralm_status ralm_build_scan_copy_l2(const void *src, int32_t src_dtype, int64_t src_stride, void *dst,
+                                    int32_t dst_dtype, int64_t dst_stride, int64_t N, int32_t d, void *stream)
+{
+    if (!src || !dst) return fail(RALM_ERR_NULL, "src/dst is NULL");
+    if (N < 1 || d < 8 || d % 8) return fail(RALM_ERR_SHAPE, "N >= 1 and d a multiple of 8 required");
+    if (src_dtype != RALM_F32 && src_dtype != RALM_F16) return fail(RALM_ERR_DTYPE, "src_dtype must be RALM_F32 or RALM_F16");
+    if (dst_dtype != RALM_BF16 && dst_dtype != RALM_F16) return fail(RALM_ERR_DTYPE, "dst_dtype must be RALM_BF16 or RALM_F16");
+    if (src_stride == 0) src_stride = d;
+    if (dst_stride == 0) dst_stride = d + L2_EXTRA_COLS;
+    if (src_stride < d || dst_stride < d + L2_EXTRA_COLS) return fail(RALM_ERR_SHAPE, "src_stride < d or dst_stride < d + 8");
+    if (src == dst && (src_dtype != dst_dtype || src_stride != dst_stride))
+        return fail(RALM_ERR_SHAPE, "in place (src == dst) needs equal dtypes and strides");
+    if (!aligned16(src) || !aligned16(dst) || (src_stride * elem_bytes(src_dtype)) % 16 || (dst_stride * 2) % 16)
+        return fail(RALM_ERR_ALIGN, "bases and row pitches must be multiples of 16 bytes");
+    RALM_HIP(launch_l2_scan_copy(src, src_dtype, src_stride, dst, dst_dtype, dst_stride, N, d,
+                                 static_cast<hipStream_t>(stream)));
+    return RALM_OK;
+}
+
 ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
                               const float *queries, int64_t Qt, const int64_t *q_offsets,
                               const ralm_datastore_t *ds, int32_t *spec_ids, float *spec_scores, void *stream)
@@ -379,7 +408,7 @@ ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len
     if (!aligned16(queries)) return fail(RALM_ERR_ALIGN, "queries must be 16-byte aligned");
     const int64_t ld = ds->exact_stride ? ds->exact_stride : ds->d;
     RALM_HIP(launch_cache_lookup(cache_ids, cache_len, C, R, queries, Qt, q_offsets, ds->exact, ds->exact_dtype, ld,
-                                 ds->N, ds->d, spec_ids, spec_scores, static_cast<hipStream_t>(stream)));
+                                 ds->N, ds->d, ds->metric, spec_ids, spec_scores, static_cast<hipStream_t>(stream)));
     return RALM_OK;
 }
 

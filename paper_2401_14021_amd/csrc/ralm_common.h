@@ -8,6 +8,8 @@ namespace ralm {
 typedef unsigned long long u64;
 
 enum { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
+enum { METRIC_IP = 0, METRIC_L2 = 1 };   // inner product; minus the squared Euclidean distance
+constexpr int L2_EXTRA_COLS = 8;        // columns behind a scan-copy row that hold its squared norm
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));

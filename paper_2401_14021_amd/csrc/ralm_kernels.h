@@ -41,7 +41,9 @@ hipError_t launch_fill_u64(u64 *p, u64 v, int64_t n, hipStream_t stream);
 
 // fp32 [Q, d] -> scan dtype [Qpad, dpad], zero padded
 hipError_t launch_query_prep(const float *q, int64_t Q, int32_t d, uint16_t *out, int64_t Qpad,
-                             int32_t dpad, int32_t scan_dtype, hipStream_t stream);
+                             int32_t dpad, int32_t scan_dtype, int32_t metric, hipStream_t stream);
+hipError_t launch_l2_scan_copy(const void *src, int32_t src_dtype, int64_t src_ld, void *dst, int32_t dst_dtype,
+                               int64_t dst_ld, int64_t N, int32_t d, hipStream_t stream);
 
 hipError_t launch_convert_rows(const float *src, int64_t src_ld, void *dst, int32_t dst_dtype,
                                int64_t dst_ld, int64_t N, int32_t d, hipStream_t stream);
@@ -55,13 +57,13 @@ hipError_t launch_select(u64 *cand, uint32_t *cnt, uint32_t cap, int32_t k_prime
 // per query: exact scores of the (at most k') rows left in its list, final ranking, top k out
 hipError_t launch_rescore(const u64 *cand, const uint32_t *cnt, uint32_t cap, int32_t k_prime,
                           const float *queries, int64_t Q, const void *exact, int32_t exact_dtype, int64_t ld,
-                          int32_t d, int32_t k, int32_t *out_ids, float *out_scores, float *out_margin,
-                          hipStream_t stream);
+                          int32_t d, int32_t metric, int32_t k, int32_t *out_ids, float *out_scores,
+                          float *out_margin, hipStream_t stream);
 
 hipError_t launch_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
                                const float *queries, int64_t Qt, const int64_t *q_offsets,
                                const void *exact, int32_t exact_dtype, int64_t ld, int64_t N, int32_t d,
-                               int32_t *spec_ids, float *spec_scores, hipStream_t stream);
+                               int32_t metric, int32_t *spec_ids, float *spec_scores, hipStream_t stream);
 
 constexpr int CACHE_INSERT_MAX_C = 16384;   // a request's cache row is held in LDS during an update
 hipError_t launch_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *cache_head, int32_t C, int64_t R,

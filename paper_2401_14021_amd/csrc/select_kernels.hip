@@ -134,7 +134,9 @@ __device__ __forceinline__ double wave_sum(double x)
 
 constexpr int RS_THREADS = 1024, RS_WAVES = RS_THREADS / 64;
 
-template <int EX>   // DT_F32 or DT_F16 exact rows
+// EX: DT_F32 or DT_F16 exact rows.  L2: the score is minus the squared distance; the scan's
+// score of a row is then 2<q, x> - |x|^2, so |q|^2 is subtracted from it for the margin.
+template <int EX, bool L2>
 __global__ __launch_bounds__(RS_THREADS) void rescore_kernel(const u64 *__restrict__ cand,
                                                       const uint32_t *__restrict__ cnt, uint32_t cap,
                                                       int k_prime, int kp2, const float *__restrict__ queries,
@@ -166,10 +168,19 @@ __global__ __launch_bounds__(RS_THREADS) void rescore_kernel(const u64 *__restri
             for (int j = lane * 4; j < d; j += 256) {
                 const float4 x = *reinterpret_cast<const float4 *>(row + j);
                 const float4 y = *reinterpret_cast<const float4 *>(qv + j);
-                sum += (double)x.x * (double)y.x;
-                sum += (double)x.y * (double)y.y;
-                sum += (double)x.z * (double)y.z;
-                sum += (double)x.w * (double)y.w;
+                if constexpr (L2) {
+                    const double d0 = (double)y.x - (double)x.x, d1 = (double)y.y - (double)x.y;
+                    const double d2 = (double)y.z - (double)x.z, d3 = (double)y.w - (double)x.w;
+                    sum += d0 * d0;
+                    sum += d1 * d1;
+                    sum += d2 * d2;
+                    sum += d3 * d3;
+                } else {
+                    sum += (double)x.x * (double)y.x;
+                    sum += (double)x.y * (double)y.y;
+                    sum += (double)x.z * (double)y.z;
+                    sum += (double)x.w * (double)y.w;
+                }
             }
         } else {
             const uint16_t *row = static_cast<const uint16_t *>(exact) + (int64_t)id * ld;
@@ -177,18 +188,25 @@ __global__ __launch_bounds__(RS_THREADS) void rescore_kernel(const u64 *__restri
                 const uint4 x = *reinterpret_cast<const uint4 *>(row + j);
                 const float4 y0 = *reinterpret_cast<const float4 *>(qv + j);
                 const float4 y1 = *reinterpret_cast<const float4 *>(qv + j + 4);
-                sum += (double)f16_bits_to_f32(x.x & 0xffffu) * (double)y0.x;
-                sum += (double)f16_bits_to_f32(x.x >> 16) * (double)y0.y;
-                sum += (double)f16_bits_to_f32(x.y & 0xffffu) * (double)y0.z;
-                sum += (double)f16_bits_to_f32(x.y >> 16) * (double)y0.w;
-                sum += (double)f16_bits_to_f32(x.z & 0xffffu) * (double)y1.x;
-                sum += (double)f16_bits_to_f32(x.z >> 16) * (double)y1.y;
-                sum += (double)f16_bits_to_f32(x.w & 0xffffu) * (double)y1.z;
-                sum += (double)f16_bits_to_f32(x.w >> 16) * (double)y1.w;
+                const double xs[8] = {(double)f16_bits_to_f32(x.x & 0xffffu), (double)f16_bits_to_f32(x.x >> 16),
+                                      (double)f16_bits_to_f32(x.y & 0xffffu), (double)f16_bits_to_f32(x.y >> 16),
+                                      (double)f16_bits_to_f32(x.z & 0xffffu), (double)f16_bits_to_f32(x.z >> 16),
+                                      (double)f16_bits_to_f32(x.w & 0xffffu), (double)f16_bits_to_f32(x.w >> 16)};
+                const double ys[8] = {(double)y0.x, (double)y0.y, (double)y0.z, (double)y0.w,
+                                      (double)y1.x, (double)y1.y, (double)y1.z, (double)y1.w};
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if constexpr (L2) {
+                        const double df = ys[u] - xs[u];
+                        sum += df * df;
+                    } else {
+                        sum += xs[u] * ys[u];
+                    }
+                }
             }
         }
         sum = wave_sum(sum);
-        if (lane == 0) keys[c] = make_key((float)sum, id);
+        if (lane == 0) keys[c] = make_key(L2 ? (float)(-sum) : (float)sum, id);
     }
     for (int c = n + tid; c < kp2; c += RS_THREADS) keys[c] = 0ull;
     if (lane == 0) s_min_scan[wave] = min_scan;
@@ -218,6 +236,12 @@ __global__ __launch_bounds__(RS_THREADS) void rescore_kernel(const u64 *__restri
         out_scores[q * k + r] = have ? key_score(key) : (overflow ? __builtin_nanf("") : -__builtin_inff());
     }
     if (out_margin && tid == 0) {
+        float q_sq = 0.f;
+        if constexpr (L2) {
+            double t = 0.0;
+            for (int j = 0; j < d; ++j) t += (double)qv[j] * (double)qv[j];
+            q_sq = (float)t;
+        }
         u64 ms = s_min_scan[0];
         for (int w = 1; w < RS_WAVES; ++w) ms = s_min_scan[w] < ms ? s_min_scan[w] : ms;
         float margin;
@@ -226,7 +250,7 @@ __global__ __launch_bounds__(RS_THREADS) void rescore_kernel(const u64 *__restri
         else if (n < k_prime)
             margin = __builtin_inff();   // every row of the datastore was re-scored
         else
-            margin = key_score(keys[k - 1]) - key_score(ms);
+            margin = key_score(keys[k - 1]) - (key_score(ms) - q_sq);
         out_margin[q] = margin;
     }
 }
@@ -243,19 +267,24 @@ hipError_t launch_select(u64 *cand, uint32_t *cnt, uint32_t cap, int32_t k_prime
 }
 
 hipError_t launch_rescore(const u64 *cand, const uint32_t *cnt, uint32_t cap, int32_t k_prime, const float *queries,
-                          int64_t Q, const void *exact, int32_t exact_dtype, int64_t ld, int32_t d, int32_t k,
-                          int32_t *out_ids, float *out_scores, float *out_margin, hipStream_t stream)
+                          int64_t Q, const void *exact, int32_t exact_dtype, int64_t ld, int32_t d, int32_t metric,
+                          int32_t k, int32_t *out_ids, float *out_scores, float *out_margin, hipStream_t stream)
 {
     if (Q <= 0) return hipSuccess;
     int kp2 = 2;
     while (kp2 < k_prime) kp2 <<= 1;
     const size_t smem = (size_t)kp2 * sizeof(u64);
-    if (exact_dtype == DT_F16)
-        hipLaunchKernelGGL(rescore_kernel<DT_F16>, dim3((unsigned)Q), dim3(RS_THREADS), smem, stream, cand, cnt, cap,
-                           k_prime, kp2, queries, exact, ld, d, k, out_ids, out_scores, out_margin);
-    else
-        hipLaunchKernelGGL(rescore_kernel<DT_F32>, dim3((unsigned)Q), dim3(RS_THREADS), smem, stream, cand, cnt, cap,
-                           k_prime, kp2, queries, exact, ld, d, k, out_ids, out_scores, out_margin);
+#define RALM_RS(EXV, L2V)                                                                                    \
+    hipLaunchKernelGGL((rescore_kernel<EXV, L2V>), dim3((unsigned)Q), dim3(RS_THREADS), smem, stream, cand, cnt, \
+                       cap, k_prime, kp2, queries, exact, ld, d, k, out_ids, out_scores, out_margin)
+    if (exact_dtype == DT_F16) {
+        if (metric == METRIC_L2) RALM_RS(DT_F16, true);
+        else RALM_RS(DT_F16, false);
+    } else {
+        if (metric == METRIC_L2) RALM_RS(DT_F32, true);
+        else RALM_RS(DT_F32, false);
+    }
+#undef RALM_RS
     return hipGetLastError();
 }
 

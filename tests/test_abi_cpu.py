@@ -59,6 +59,26 @@ def test_argument_errors_return_status_without_a_device(L):
     assert call(P, 8, ref(ds), 5, 0, P, P, None, None, ws, None) == 6            # no workspace
     assert call(P, 8, ref(ds), 5, 0, P, P, None, P + 16, ws, None) == 6          # misaligned workspace
     assert call(P, 8, ref(ds), 5, 0, P, P, None, P, ws - 1, None) == 6           # too small
+    l2 = _ds(b)
+    l2.metric = 1
+    l2.scan_stride = 770
+    assert call(P, 8, ref(l2), 5, 0, P, P, None, P, 1 << 30, None) == 2          # scan pitch below d + 8
+    l2.scan_stride = 776
+    assert L.ralm_workspace_bytes(8, ref(l2), 5, 0) > 0                          # accepted with d + 8 columns
+    l2.scan = None
+    assert call(P, 8, ref(l2), 5, 0, P, P, None, P, 1 << 30, None) == 1          # squared distance needs a scan copy
+    l2 = _ds(b, scan_dtype=0)
+    l2.metric = 1
+    assert call(P, 8, ref(l2), 5, 0, P, P, None, P, 1 << 30, None) == 4          # ... in bf16 or fp16
+    bad = _ds(b)
+    bad.metric = 5
+    assert call(P, 8, ref(bad), 5, 0, P, P, None, P, 1 << 30, None) == 4
+    bl2 = L.ralm_build_scan_copy_l2
+    assert bl2(P, 0, 0, None, 1, 0, 10, 768, None) == 1
+    assert bl2(P, 1, 0, P, 1, 0, 10, 768, None) == 4                             # bf16 is not an exact copy
+    assert bl2(P, 0, 0, P, 0, 0, 10, 768, None) == 4                             # fp32 is not a scan copy
+    assert bl2(P, 0, 0, P, 1, 770, 10, 768, None) == 2                           # dst pitch below d + 8
+    assert bl2(P, 2, 776, P, 1, 776, 10, 768, None) == 2                         # in place needs equal dtypes
     assert L.ralm_workspace_bytes(8, ref(ds), 0, 0) == 0
     assert L.ralm_workspace_bytes(0, ref(ds), 5, 0) == 0
     # workspace grows with Q and with k'

@@ -495,3 +495,107 @@ def test_knnlm_probs_hand_case_and_retrieval_output(B, oracle):
     got = B.ralm_knnlm_probs(ids, sc, vals.cuda(), 1.0)
     want = oracle.knnlm_probs(ids.cpu().numpy(), sc.cpu().numpy(), vals.numpy(), 1.0)
     _check_probs(got, want)
+
+
+# ----------------------------------------------------------------------------------------
+# squared-distance metric
+# ----------------------------------------------------------------------------------------
+def _retrieve_l2(B, oracle, X, Qm, k, k_prime=0, scan_dtype=None, margin=False):
+    ds = B.Datastore.for_l2(X.cuda(), scan_dtype)
+    qd = Qm.cuda()
+    ws = B.alloc_workspace(qd.shape[0], ds, k, k_prime)
+    mg = torch.empty(qd.shape[0], dtype=torch.float32, device="cuda") if margin else None
+    ids, sc = B.ralm_retrieve_topk_ex(qd, ds, k, k_prime, workspace=ws, out_margin=mg)
+    assert B.ralm_workspace_overflows(ws) == 0
+    Xo = X.numpy() if X.dtype == torch.float32 else X.numpy()
+    wi, wsc = oracle.retrieve_topk(Qm.numpy(), Xo, k, metric="l2")
+    return ids.cpu().numpy(), sc.cpu().numpy(), wi, wsc, (mg.cpu().numpy() if margin else None), ds
+
+
+def _l2_score_fn(oracle, Qm, Xnp):
+    def f(i, ids):
+        return oracle.scores(Qm[i], Xnp[np.asarray(ids, dtype=np.int64)], "l2")
+    return f
+
+
+def test_l2_hand_case_and_scan_copy_layout(B, oracle):
+    X = torch.zeros(5, 8)
+    X[:, :2] = torch.tensor([[0., 0.], [3., 4.], [1., 1.], [3., 4.], [-1., 2.]])
+    Qm = torch.zeros(1, 8)
+    Qm[0, :2] = torch.tensor([1., 2.])
+    ids, sc, wi, wsc, _, ds = _retrieve_l2(B, oracle, X, Qm, 5)
+    assert ids.tolist() == [[2, 4, 0, 1, 3]] and sc.tolist() == [[-1, -4, -5, -8, -8]]
+    assert np.array_equal(ids, wi) and np.array_equal(sc, wsc)
+    # layout of the scan copy: rounded row, squared norm as head + remainder, zeros
+    g = torch.Generator().manual_seed(7)
+    X = torch.randn(300, 72, generator=g) * 5
+    for dt in (torch.bfloat16, torch.float16):
+        ds = B.Datastore.for_l2(X.cuda(), dt)
+        scan = ds.scan.cpu()
+        assert torch.equal(scan[:, :72], X.to(dt))
+        n = (X.double() ** 2).sum(dim=1)
+        head = n.float().to(dt)
+        assert torch.equal(scan[:, 72], head)
+        assert torch.equal(scan[:, 73], (n - head.double()).float().to(dt))
+        assert bool((scan[:, 74:] == 0).all())
+        got = scan[:, 72].double() + scan[:, 73].double()
+        assert float(((got - n).abs() / n).max()) < (2.0 ** -15 if dt == torch.bfloat16 else 2.0 ** -21)
+
+
+@pytest.mark.parametrize("N,d,Q,k,dt", [
+    (805, 8, 1, 1, torch.bfloat16), (2101, 768, 33, 20, torch.bfloat16), (5000, 136, 70, 64, torch.float16),
+    (70000, 256, 9, 20, torch.bfloat16), (30000, 1024, 140, 100, torch.float16), (1300, 64, 300, 7, torch.bfloat16),
+])
+def test_l2_retrieval_matches_oracle(B, oracle, N, d, Q, k, dt):
+    """Rows of very different norms (so that the distance ranking is far from the inner-product
+    ranking), queries near rows."""
+    from paper_2401_14021_amd import inputs
+    g = torch.Generator().manual_seed(N + d)
+    X, _ = inputs.clustered_datastore(N, d, 32, seed=N, normalise=False)
+    X = X * (0.5 + 1.5 * torch.rand(N, 1, generator=g))
+    Qm = inputs.queries_near_rows(X, inputs.pick_rows(N, Q, seed=3), seed=4, sigma=0.1)
+    ids, sc, wi, wsc, mg, _ = _retrieve_l2(B, oracle, X, Qm, k, scan_dtype=dt, margin=True)
+    ip_ids, _ = oracle.retrieve_topk(Qm.numpy(), X.numpy(), k, metric="ip")
+    if N > 2000:
+        assert not np.array_equal(ip_ids, wi)                  # the two metrics disagree on this data
+    exact, subs, total = check_topk(ids, sc, wi, wsc, _l2_score_fn(oracle, Qm.numpy(), X.numpy()))
+    assert exact >= 0.98 * total
+    assert not np.isnan(mg).any()
+
+
+def test_l2_on_fp16_keys_that_are_their_own_scan_copy(B, oracle):
+    """KNN-LM shape, small: fp16 keys stored with a pitch of d + 8; the 8 spare columns receive the
+    squared norms in place, so no second copy of the keys exists.  Cache lookup ranks by distance too."""
+    from paper_2401_14021_amd import inputs
+    N, d, Q, k = 40000, 128, 24, 64
+    keys, vals = inputs.knnlm_datastore(N, d, 16, seed=81)
+    store = torch.zeros(N, d + 8, dtype=torch.float16, device="cuda")
+    store[:, :d] = keys.cuda()
+    exact = store[:, :d]                                        # a view: pitch d + 8
+    st = B.lib().ralm_build_scan_copy_l2(store.data_ptr(), B.RALM_F16, d + 8, store.data_ptr(), B.RALM_F16, d + 8,
+                                         N, d, None)
+    assert st == 0
+    torch.cuda.synchronize()
+    assert torch.equal(store[:, :d].cpu(), keys)                # the keys are untouched
+    ds = B.Datastore(exact, store, B.RALM_METRIC_L2)
+    rows = inputs.pick_rows(N, Q, seed=82)
+    Qm = inputs.queries_near_rows(keys, rows, seed=83, sigma=0.5)
+    ids, sc = B.ralm_retrieve_topk_ex(Qm.cuda(), ds, k)
+    wi, wsc = oracle.retrieve_topk(Qm.numpy(), keys.numpy(), k, metric="l2")
+    exact_n, subs, total = check_topk(ids.cpu().numpy(), sc.cpu().numpy(), wi, wsc,
+                                      _l2_score_fn(oracle, Qm.numpy(), keys.numpy()))
+    assert exact_n >= 0.98 * total
+    # cache lookup with the same metric
+    off = inputs.stride_offsets([4] * 6)
+    cids, clen = inputs.speculation_caches(N, 6, 32, off, rows, None, seed=84)
+    spec, ssc = B.ralm_cache_lookup(cids.cuda(), clen.cuda(), Qm.cuda(), off.cuda(), ds)
+    wspec, wssc = oracle.cache_lookup(cids.numpy(), clen.numpy(), Qm.numpy(), off.numpy(), keys.numpy(), metric="l2")
+    assert np.array_equal(spec.cpu().numpy(), wspec)
+    assert np.allclose(ssc.cpu().numpy(), wssc, rtol=1e-6)
+    # rank preservation under this metric as well
+    hit = np.array([wi[q, 0] in cids[q // 4, :clen[q // 4]].numpy() for q in range(Q)])
+    assert np.array_equal(spec.cpu().numpy()[hit], wi[hit, 0]) and hit.any()
+    # and the neighbour distribution from distances
+    got = B.ralm_knnlm_probs(ids, sc, (vals % 50).to(torch.int32).cuda(), 10.0)
+    want = oracle.knnlm_probs(ids.cpu().numpy(), sc.cpu().numpy(), (vals % 50).numpy(), 10.0)
+    _check_probs(got, want)
