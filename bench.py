@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--k", type=int, default=0)
     ap.add_argument("--N", type=int, default=0, help="override datastore rows (for quick runs)")
     ap.add_argument("--sweep", default="", help="comma-separated extra batch sizes ('' = workload default, 'none')")
+    ap.add_argument("--metric", default="ip", choices=["ip", "l2"],
+                    help="ip: inner product (the headline); l2: minus the squared distance (KNN-LM style)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -69,16 +71,28 @@ def main():
 
     # ---- inputs, resident in HBM -------------------------------------------------------------
     t0 = time.time()
+    l2 = args.metric == "l2"
+    values = None
     if w.exact_dtype == "f16":
-        keys = torch.empty(N, w.d, dtype=torch.float16, device=dev)
-        inputs.knnlm_datastore(N, w.d, w.n_clusters, w.seed, device=dev, out=keys)
-        ds = B.Datastore(keys, None)
+        # the fp16 keys are their own scan copy; for the squared-distance metric they are stored
+        # with 8 spare columns per row, which receive the squared norms in place
+        cols = w.d + (64 if l2 else 0)      # 8 are used; 64 keeps the rows on 128-byte lines
+        store = torch.empty(N, cols, dtype=torch.float16, device=dev)
+        keys = store[:, :w.d]
+        _, values = inputs.knnlm_datastore(N, w.d, w.n_clusters, w.seed, device=dev, out=keys)
+        if l2:
+            B._check(B.lib().ralm_build_scan_copy_l2(store.data_ptr(), B.RALM_F16, cols, store.data_ptr(), B.RALM_F16,
+                                                     cols, N, w.d, None))
+            ds = B.Datastore(keys, store[:, :w.d + 8], B.RALM_METRIC_L2)
+        else:
+            ds = B.Datastore(keys, None)
         assign = None
         q_sigma = 0.5
     else:
         X = torch.empty(N, w.d, dtype=torch.float32, device=dev)
         _, assign = inputs.clustered_datastore(N, w.d, w.n_clusters, w.seed, device=dev, out=X)
-        ds = B.Datastore.from_fp32(X, torch.bfloat16 if w.scan_dtype == "bf16" else torch.float16)
+        sdt = torch.bfloat16 if w.scan_dtype == "bf16" else torch.float16
+        ds = B.Datastore.for_l2(X, sdt) if l2 else B.Datastore.from_fp32(X, sdt)
         q_sigma = 0.05
     torch.cuda.synchronize()
     gen_s = time.time() - t0
@@ -113,6 +127,8 @@ def main():
         B.ralm_retrieve_topk_ex(b["Qm"], ds, k, w.k_prime, workspace=b["ws"], out_ids=b["ids"],
                                 out_scores=b["sc"])
         B.ralm_verify(b["spec"], b["ids"], b["off"], true_stride=k, first_mismatch=b["mism"])
+        if values is not None:      # KNN-LM: the retrieved entries' distribution over target tokens
+            B.ralm_knnlm_probs(b["ids"], b["sc"], values, 10.0 if l2 else 1.0)
 
     def run(Q, steps, warmup):
         b = make_batch(Q, seed=w.seed * 7 + Q)
@@ -132,7 +148,7 @@ def main():
         assert B.ralm_workspace_overflows(b["ws"]) == 0, "candidate buffer overflow"
         ms = dt / steps * 1e3
         scan = scan_ms / steps                            # all scan launches of one call: every row read once
-        bytes_scan = N * w.d * 2
+        bytes_scan = N * w.d * 2 + (N * 4 if l2 else 0)        # rows, plus one squared norm per row
         flops = 2.0 * b["Q"] * N * w.d
         hit = float((b["spec"] == b["ids"][:, 0]).float().mean().item())
         gbps, tflops = bytes_scan / scan / 1e6, flops / scan / 1e9
@@ -156,14 +172,14 @@ def main():
                 "unit": "TFLOP/s", "frac": round(head["scan_TFLOPs"] / MFMA_PEAK_TFLOPS, 4), "traffic": None}
     roof["kernel"] = "scan kernel, one pass over the datastore (sum of the call's scan launches)"
     roof["kernel_ms"] = round(head["scan_ms"], 4)
-    roof["algorithmic_bytes"] = N * w.d * 2
+    roof["algorithmic_bytes"] = N * w.d * 2 + (N * 4 if l2 else 0)
     roof["algorithmic_flops"] = 2.0 * head["Q"] * N * w.d
     # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (summaries and the
     # scaling against a copy kernel of known size are under profiles/); null if not measured for
     # this workload and batch size
     try:
         with open(os.path.join(ROOT, "profiles", "scan_hbm_traffic.json")) as fh:
-            t = json.load(fh).get(f"{args.workload}:Q={head['Q']}") if not args.N else None
+            t = json.load(fh).get(f"{args.workload}:Q={head['Q']}") if not args.N and not l2 else None
         if t:
             roof["traffic"] = t["fetch_bytes"] + t["write_bytes"]
     except OSError:
@@ -213,7 +229,7 @@ def main():
         Xs = ds.exact[:n_s].cpu().numpy()
         qs = hb["Qm"][:q_s].cpu().numpy()
         t = time.perf_counter()
-        o_ids, _ = oracle.retrieve_topk(qs, Xs, k)
+        o_ids, _ = oracle.retrieve_topk(qs, Xs, k, metric=args.metric)
         ot = time.perf_counter() - t
         # retrieval over the first n_s rows costs n_s/N of a full query (scores are linear in N)
         cpu = {"value": round(q_s / (ot * N / n_s), 4), "unit": "queries/s", "cores": oracle.threads(),
@@ -230,7 +246,7 @@ def main():
         "dtype": "bf16" if w.scan_dtype == "bf16" else "f16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: N={N} d={w.d} scan={w.scan_dtype} exact={w.exact_dtype} "
                                f"Q={head['Q']} k={k} k_prime={w.k_prime} requests={hb['R']} "
-                               f"cache={C}",
+                               f"cache={C} metric={args.metric}",
                    "gen_seconds": round(gen_s, 1), "spec_hit_rate": round(head["spec_hit_rate"], 3)},
         "roofline": roof,
         "cpu_baseline": cpu,

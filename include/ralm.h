@@ -84,7 +84,9 @@ typedef enum { RALM_METRIC_IP = 0, RALM_METRIC_L2 = 1 } ralm_metric;
  *          copy is mandatory, bf16 or fp16, and its rows have d + 8 columns:
  *          the d rounded elements, then the row's squared norm as the sum of
  *          two scan-dtype numbers, then six zeros (ralm_build_scan_copy_l2
- *          writes this layout; scan_stride 0 = d + 8).  The scan then scores a
+ *          writes this layout; scan_stride 0 = d + 8, but a pitch that is a
+ *          multiple of 64 elements keeps rows on 128-byte lines and scans
+ *          ~20 % faster).  The scan then scores a
  *          row as 2<q, x> - |x|^2 on the matrix cores with no change to its
  *          kernels; final scores are -|q - x|^2 from the exact copy.
  */

@@ -135,7 +135,8 @@ class Datastore:
         if scan_dtype is None:
             scan_dtype = torch.float16 if exact.dtype == torch.float16 else torch.bfloat16
         N, d = exact.shape
-        scan = torch.empty(N, d + 8, dtype=scan_dtype, device=exact.device)
+        pitch = (d + 8 + 63) // 64 * 64          # rows start on 128-byte lines
+        scan = torch.empty(N, pitch, dtype=scan_dtype, device=exact.device)[:, :d + 8]
         _check(lib().ralm_build_scan_copy_l2(exact.data_ptr(), _DT[exact.dtype], exact.stride(0), scan.data_ptr(),
                                              _DT[scan_dtype], scan.stride(0), N, d, _stream()))
         return cls(exact, scan, RALM_METRIC_L2)

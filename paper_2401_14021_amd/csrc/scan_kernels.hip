@@ -457,7 +457,7 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     int is_qt = vb % nqt;
     int is_kt = 0, is_buf = 0;
     // wave-uniform state of the stage being issued
-    const unsigned char *is_abase = nullptr, *is_bbase = nullptr;
+    const unsigned char *is_abase = nullptr, *is_bbase = nullptr, *is_aload = nullptr;
     uint32_t is_rowmax = 0, is_kmax = 0, is_lds = 0;
     auto issue_begin = [&]() __attribute__((always_inline)) {
         if (is_kt == 0) {
@@ -470,15 +470,19 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
             const int64_t left = p.N - 1 - row0;            // rows past N re-read row N-1
             is_rowmax = (uint32_t)(left < BM - 1 ? left : BM - 1);
         }
-        const int kleft = (p.d - 8 - is_kt * BK) * 2;        // chunks past d re-read the last valid one
-        is_kmax = (uint32_t)(kleft < ROWB - 16 ? kleft : ROWB - 16);
+        // chunks past d re-read the row's last valid one (the query side is zero there): inside a
+        // strip by clamping the chunk offset, for a strip that lies past d entirely by stepping
+        // the strip's base back to that chunk
+        const int kleft = (p.d - 8 - is_kt * BK) * 2;
+        is_kmax = (uint32_t)(kleft < 0 ? 0 : (kleft < ROWB - 16 ? kleft : ROWB - 16));
+        is_aload = is_abase + (kleft < 0 ? kleft : 0);
         is_lds = lds0 + is_buf * STAGE + wave * (NA * 1024);
     };
     auto issue_part = [&](int idx) __attribute__((always_inline)) {
         if (idx < NA) {
             const uint32_t r = a_row[idx] < is_rowmax ? a_row[idx] : is_rowmax;
             const uint32_t c = a_chunk[idx] < is_kmax ? a_chunk[idx] : is_kmax;
-            dma_1kb(is_abase, __umul24(r, ldx2) + c, is_lds + idx * 1024);   // r < 2^8, ldx2 < 2^24
+            dma_1kb(is_aload, __umul24(r, ldx2) + c, is_lds + idx * 1024);   // r < 2^8, ldx2 < 2^24
         } else {
             const int j = idx - NA;
             dma_1kb(is_bbase, b_voff[j], lds0 + is_buf * STAGE + A_BYTES + (wave * NB + j) * 1024);

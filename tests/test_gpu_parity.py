@@ -599,3 +599,26 @@ def test_l2_on_fp16_keys_that_are_their_own_scan_copy(B, oracle):
     got = B.ralm_knnlm_probs(ids, sc, (vals % 50).to(torch.int32).cuda(), 10.0)
     want = oracle.knnlm_probs(ids.cpu().numpy(), sc.cpu().numpy(), (vals % 50).numpy(), 10.0)
     _check_probs(got, want)
+
+
+@pytest.mark.parametrize("Q", [5, 70, 140])
+def test_padding_columns_behind_the_rows_are_never_used(B, oracle, Q):
+    """Both copies are stored with a pitch larger than d and NaN in the spare columns; d = 136 is
+    padded by the scan to 192, so a 32-element strip lies entirely past d.  Nothing of the padding
+    may reach a score."""
+    from paper_2401_14021_amd import inputs
+    N, d, pitch, k = 20000, 136, 192, 10
+    X, _ = inputs.clustered_datastore(N, d, 16, seed=91)
+    Qm = inputs.queries_near_rows(X, inputs.pick_rows(N, Q, seed=92), seed=93)
+    exact_store = torch.full((N, pitch), float("nan"), device="cuda")
+    exact_store[:, :d] = X.cuda()
+    scan_store = torch.full((N, pitch), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.ralm_build_scan_copy(exact_store[:, :d], scan_store[:, :d])
+    ds = B.Datastore(exact_store[:, :d], scan_store[:, :d])
+    ws = B.alloc_workspace(Q, ds, k)
+    ids, sc = B.ralm_retrieve_topk_ex(Qm.cuda(), ds, k, workspace=ws)
+    assert B.ralm_workspace_overflows(ws) == 0
+    wi, wsc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), k)
+    exact, subs, total = check_topk(ids.cpu().numpy(), sc.cpu().numpy(), wi, wsc,
+                                    _score_fn(oracle, Qm.numpy(), X.numpy()))
+    assert exact >= 0.98 * total
