@@ -71,6 +71,8 @@ def _load():
         L.ralm_oracle_os3_stride.restype = i32
         L.ralm_oracle_os3_gamma.argtypes = [vp, vp, i32, dbl]
         L.ralm_oracle_os3_gamma.restype = dbl
+        L.ralm_oracle_os3_latency.argtypes = [vp, i32]
+        L.ralm_oracle_os3_latency.restype = dbl
         L.ralm_oracle_knnlm_probs.argtypes = [vp, vp, i64, i32, vp, dbl, vp, vp, vp, vp]
         L.ralm_oracle_knnlm_probs.restype = None
         _lib = L
@@ -250,3 +252,8 @@ def knnlm_probs(ids: np.ndarray, scores: np.ndarray, values: np.ndarray, tempera
     _load().ralm_oracle_knnlm_probs(_ptr(ids), _ptr(scores), Q, k, _ptr(values), float(temperature),
                                     _ptr(tokens), _ptr(weights), _ptr(top_token), _ptr(top_prob))
     return tokens, weights, top_token, top_prob
+
+
+def os3_latency(samples) -> float:
+    a = np.ascontiguousarray(samples, dtype=np.float64)
+    return float(_load().ralm_oracle_os3_latency(_ptr(a), a.shape[0]))

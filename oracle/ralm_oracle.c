@@ -441,3 +441,17 @@ void ralm_oracle_knnlm_probs(const int32_t *ids, const float *scores, int64_t Q,
     }
     free(e);
 }
+
+/*
+ * Latencies a and b for OS^3 (Appendix A.2: "we directly estimate their value
+ * with the profiling results from the most recent steps"; the number of steps
+ * is not stated: the same window as for gamma is used): the arithmetic mean of
+ * the samples, 0 when there is none.
+ */
+double ralm_oracle_os3_latency(const double *samples, int32_t n)
+{
+    if (n <= 0) return 0.0;
+    double sum = 0.0;
+    for (int32_t i = 0; i < n; ++i) sum += samples[i];
+    return sum / (double)n;
+}

@@ -606,3 +606,12 @@ def test_l2_metric_against_float64_and_inner_product_on_unit_rows(oracle):
     assert spec.tolist() == [77]
     sub_ids, sub_sc = oracle.retrieve_topk(X[77:78] + 0.01, X[cache[0]], 1, metric="l2")
     assert cache[0][sub_ids[0, 0]] == spec[0] and sub_sc[0, 0] == ssc[0]
+
+
+def test_os3_latency_estimate_is_the_window_mean(oracle):
+    assert oracle.os3_latency([]) == 0.0
+    assert oracle.os3_latency([2.5]) == 2.5
+    assert oracle.os3_latency([1.0, 2.0, 6.0]) == 3.0
+    rng = np.random.default_rng(2)
+    x = rng.random(5) * 10
+    assert oracle.os3_latency(x) == pytest.approx(float(np.mean(x)), rel=1e-15)
