@@ -318,10 +318,21 @@ ralm_status ralm_knnlm_probs(const int32_t *ids, const float *scores, int64_t Q,
  *   needs no special case.  NaN for s < 1, negative a or b, gamma outside [0, 1].
  * ralm_os3_stride: the s in [1, s_max] with the largest objective; the
  *   smallest such s on ties.
+ * ralm_os3_latency: a (or b) as the mean of the n most recent measurements
+ *   (the paper takes "the profiling results from the most recent steps"
+ *   without saying how many); 0 for n <= 0.
+ * ralm_os3_next_stride: the stride for the next round from a request's history:
+ *   gamma^ from (strides, matched, w), a and b from their samples, then
+ *   ralm_os3_stride.  1 while any of the three histories is empty (the paper
+ *   starts with s = 1).
  */
 double ralm_os3_gamma(const int32_t *strides, const int32_t *matched, int32_t w, double gamma_max);
 double ralm_os3_objective(double gamma, double a, double b, int32_t s, int32_t async);
 int32_t ralm_os3_stride(double gamma, double a, double b, int32_t s_max, int32_t async);
+double ralm_os3_latency(const double *samples, int32_t n);
+int32_t ralm_os3_next_stride(const int32_t *strides, const int32_t *matched, int32_t w,
+                             const double *a_samples, int32_t n_a, const double *b_samples, int32_t n_b,
+                             double gamma_max, int32_t s_max, int32_t async);
 
 /*
  * Timing aid for benchmarks.  While enabled, ralm_retrieve_topk_ex brackets

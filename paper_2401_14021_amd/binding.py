@@ -72,6 +72,10 @@ def lib() -> ctypes.CDLL:
         L.ralm_os3_objective.restype = ctypes.c_double
         L.ralm_os3_stride.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_double, i32, i32]
         L.ralm_os3_stride.restype = i32
+        L.ralm_os3_latency.argtypes = [vp, i32]
+        L.ralm_os3_latency.restype = ctypes.c_double
+        L.ralm_os3_next_stride.argtypes = [vp, vp, i32, vp, i32, vp, i32, ctypes.c_double, i32, i32]
+        L.ralm_os3_next_stride.restype = i32
         L.ralm_profile_enable.argtypes = [i32]
         L.ralm_profile_enable.restype = None
         L.ralm_profile_scan_ms.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
@@ -291,6 +295,19 @@ def ralm_os3_objective(gamma: float, a: float, b: float, s: int, asynchronous: b
 
 def ralm_os3_stride(gamma: float, a: float, b: float, s_max: int, asynchronous: bool = False) -> int:
     return int(lib().ralm_os3_stride(gamma, a, b, s_max, 1 if asynchronous else 0))
+
+
+def ralm_os3_next_stride(strides, matched, a_samples, b_samples, s_max: int, gamma_max: float = 0.6,
+                         asynchronous: bool = False) -> int:
+    """Host-side: stride of the next round from a request's recent history."""
+    w = len(strides)
+    assert len(matched) == w
+    s = (ctypes.c_int32 * max(w, 1))(*[int(v) for v in strides])
+    m = (ctypes.c_int32 * max(w, 1))(*[int(v) for v in matched])
+    a = (ctypes.c_double * max(len(a_samples), 1))(*[float(v) for v in a_samples])
+    b = (ctypes.c_double * max(len(b_samples), 1))(*[float(v) for v in b_samples])
+    return int(lib().ralm_os3_next_stride(s, m, w, a, len(a_samples), b, len(b_samples), gamma_max, s_max,
+                                          1 if asynchronous else 0))
 
 
 def ralm_profile_enable(on: bool) -> None:

@@ -6,6 +6,8 @@
 //   objective        expected number of verified documents per unit time for a stride s,
 //                    with synchronous or asynchronous verification
 //   stride           the s in [1, s_max] that maximises the objective (smallest s on ties)
+//   latency          a and b as the mean of the most recent measurements
+//   next stride      the three combined: what the serving loop calls after each verification
 #include "../../include/ralm.h"
 
 #include <cmath>
@@ -55,6 +57,14 @@ double ralm_os3_objective(double gamma, double a, double b, int32_t s, int32_t a
     return expected / latency;
 }
 
+double ralm_os3_latency(const double *samples, int32_t n)
+{
+    if (!samples || n <= 0) return 0.0;
+    double sum = 0.0;
+    for (int32_t i = 0; i < n; ++i) sum += samples[i];
+    return sum / (double)n;
+}
+
 int32_t ralm_os3_stride(double gamma, double a, double b, int32_t s_max, int32_t async)
 {
     if (s_max < 1) return 1;
@@ -68,6 +78,15 @@ int32_t ralm_os3_stride(double gamma, double a, double b, int32_t s_max, int32_t
         }
     }
     return best;
+}
+
+int32_t ralm_os3_next_stride(const int32_t *strides, const int32_t *matched, int32_t w, const double *a_samples,
+                             int32_t n_a, const double *b_samples, int32_t n_b, double gamma_max, int32_t s_max,
+                             int32_t async)
+{
+    if (w <= 0 || n_a <= 0 || n_b <= 0) return 1;   // no history yet: the paper starts with s = 1
+    const double gamma = ralm_os3_gamma(strides, matched, w, gamma_max);
+    return ralm_os3_stride(gamma, ralm_os3_latency(a_samples, n_a), ralm_os3_latency(b_samples, n_b), s_max, async);
 }
 
 }  // extern "C"

@@ -149,5 +149,19 @@ def test_os3_matches_oracle(L, oracle):
         m = np.minimum(rng.integers(0, 10, size=w), st)
         assert b.ralm_os3_gamma(st, m, 0.6) == oracle.os3_gamma(st, m, 0.6) if w else b.ralm_os3_gamma(st, m) == 0.0
     assert b.ralm_os3_stride(0.5, 1, 4, 16) == 2 and b.ralm_os3_stride(0.0, 1, 4, 16) == 1
+    # the combined call = the oracle's pieces put together; 1 while there is no history
+    assert b.ralm_os3_next_stride([], [], [1.0], [4.0], 16) == 1
+    assert b.ralm_os3_next_stride([3], [3], [], [4.0], 16) == 1
+    for _ in range(200):
+        w = int(rng.integers(1, 6))
+        st = rng.integers(1, 9, size=w)
+        m = np.minimum(rng.integers(0, 10, size=w), st)
+        a_s, b_s = rng.random(int(rng.integers(1, 6))) + 0.05, rng.random(int(rng.integers(1, 6))) * 20
+        asy = bool(rng.integers(0, 2))
+        want = oracle.os3_stride(oracle.os3_gamma(st, m, 0.6), oracle.os3_latency(a_s), oracle.os3_latency(b_s), 16, asy)
+        got = b.ralm_os3_next_stride(st, m, a_s, b_s, 16, 0.6, asy)
+        g, a, bb = oracle.os3_gamma(st, m, 0.6), oracle.os3_latency(a_s), oracle.os3_latency(b_s)
+        assert got == want or oracle.os3_objective(g, a, bb, got, asy) == pytest.approx(
+            oracle.os3_objective(g, a, bb, want, asy), rel=1e-12)
     assert b.ralm_os3_objective(0.5, 1, 4, 0) != b.ralm_os3_objective(0.5, 1, 4, 0)      # NaN for s < 1
     assert b.ralm_os3_objective(1.5, 1, 4, 2) != b.ralm_os3_objective(1.5, 1, 4, 2)      # NaN for gamma > 1
