@@ -622,3 +622,19 @@ def test_padding_columns_behind_the_rows_are_never_used(B, oracle, Q):
     exact, subs, total = check_topk(ids.cpu().numpy(), sc.cpu().numpy(), wi, wsc,
                                     _score_fn(oracle, Qm.numpy(), X.numpy()))
     assert exact >= 0.98 * total
+
+
+@pytest.mark.parametrize("k,k_prime,N", [
+    (1, 1, 700), (2, 2, 700), (63, 64, 63), (63, 64, 64), (64, 64, 64), (64, 64, 65), (65, 128, 129), (65, 65, 3000),
+    (1023, 1024, 1023), (1023, 1024, 1025), (1024, 1024, 1024), (1024, 2048, 2047), (1024, 2048, 2049),
+    (1024, 4096, 4095), (1024, 4096, 4097), (1024, 4096, 30000), (20, 4096, 30000),
+])
+def test_k_and_k_prime_boundaries(B, oracle, k, k_prime, N):
+    """k at 1, 2 and around 64 and 1024 (the largest), k' from k itself to the largest allowed,
+    datastores just below and just above k' rows.  Integer-valued rows: bit-exact incl. ties."""
+    g = torch.Generator().manual_seed(k * 7 + N)
+    d = 32
+    X = torch.randint(-4, 5, (N, d), generator=g).float()
+    Qm = torch.randint(-4, 5, (5, d), generator=g).float()
+    ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, X, Qm, k, k_prime=k_prime)
+    assert np.array_equal(ids, wi) and np.array_equal(sc, wsc)
