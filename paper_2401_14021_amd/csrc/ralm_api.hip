@@ -126,7 +126,8 @@ ralm_status check_datastore(const ralm_datastore_t *ds, bool need_scan)
 {
     if (!ds) return fail(RALM_ERR_NULL, "datastore descriptor is NULL");
     if (!ds->exact) return fail(RALM_ERR_NULL, "datastore.exact is NULL");
-    if (ds->N < 1 || ds->N > 0x7fffffffLL) return fail(RALM_ERR_SHAPE, "N=%lld out of [1, 2^31)", (long long)ds->N);
+    // row numbers of a padded last tile must still fit int32
+    if (ds->N < 1 || ds->N > 0x7fffffffLL - 512) return fail(RALM_ERR_SHAPE, "N=%lld out of [1, 2^31 - 512]", (long long)ds->N);
     if (ds->d < 8 || ds->d % 8 != 0 || ds->d > 16384)
         return fail(RALM_ERR_SHAPE, "d=%d must be a multiple of 8 in [8, 16384]", ds->d);
     if (ds->exact_dtype != RALM_F32 && ds->exact_dtype != RALM_F16)

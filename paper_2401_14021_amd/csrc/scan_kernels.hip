@@ -394,7 +394,9 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     constexpr int NM = TM * TN, NR = TM + TN;
     constexpr int LAG = NM > 2 ? 2 : NM - 1;     // selection runs this many MFMAs behind
     constexpr int RV = NR - 1;                   // k-step 0 slot after which the stage rendezvous sits
-    static_assert((NW == 4 || NW == 8) && BM == SCAN_BM && NA >= 1 && NB >= 1, "tile shape");
+    // a workgroup tile covers the whole 256-row tile of the ladder, or half of it
+    constexpr int PARTS = SCAN_BM / BM;
+    static_assert((NW == 4 || NW == 8) && (BM == SCAN_BM || BM * 2 == SCAN_BM) && NA >= 1 && NB >= 1, "tile shape");
     static_assert(S >= 3 && KS % 2 == 0, "ring depth / k-steps per stage");
     static_assert(LPS * (S - 2) < 64, "vmcnt range");
 
@@ -417,8 +419,13 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     // item indices fit 32 bits: at most 2^23 row tiles times a few query tiles (host checks)
     const int G = (int)gridDim.x;
     const int vb = (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8);
-    const int total = (int)p.n_row_tiles * nqt;
-    const int n_tiles = (int)p.n_row_tiles;
+    const int n_tiles = (int)p.n_row_tiles * PARTS;      // workgroup tiles of this launch
+    const int total = n_tiles * nqt;
+    // first datastore row of the rt-th workgroup tile
+    auto tile_row0 = [&](int rt) __attribute__((always_inline)) -> int64_t {
+        if constexpr (PARTS == 1) return visited_tile(p, rt) * SCAN_BM;
+        else return visited_tile(p, rt / PARTS) * SCAN_BM + (rt % PARTS) * BM;
+    };
     const int KT = p.dpad / BK;
     const int n_mine = vb < total ? (total - vb + G - 1) / G : 0;
     if (n_mine == 0) return;
@@ -464,10 +471,14 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
             // The cursor is never stopped: past this workgroup's last tile it fetches (valid)
             // strips that nobody multiplies, so the steady-state loop has no conditionals.
             const int rt = is_rt < n_tiles ? is_rt : 0;
-            const int64_t row0 = visited_tile(p, rt) * BM;
+            int64_t row0 = tile_row0(rt);
+            int64_t left = p.N - 1 - row0;                  // rows past N re-read row N-1 ...
+            if (left < 0) {                                 // ... also a half tile that starts past it
+                row0 = p.N - 1;
+                left = 0;
+            }
             is_abase = Xb + row0 * p.ldx * 2;
             is_bbase = Qb + (int64_t)is_qt * BN * p.dpad * 2;
-            const int64_t left = p.N - 1 - row0;            // rows past N re-read row N-1
             is_rowmax = (uint32_t)(left < BM - 1 ? left : BM - 1);
         }
         // chunks past d re-read the row's last valid one (the query side is zero there): inside a
@@ -543,7 +554,7 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     int cur_qt = vb % nqt;
     for (int it = 0; it < n_mine; ++it) {
         f32x16 acc[TM][TN];
-        const int32_t row0 = (int32_t)(visited_tile(p, cur_rt) * BM);
+        const int32_t row0 = (int32_t)tile_row0(cur_rt);
         const int q0 = cur_qt * BN;
         // admission keys of this lane's TN queries
         u64 tkey[TN];
@@ -693,7 +704,7 @@ hipError_t launch_dma_variant(const ScanParams &p, int n_cu, hipStream_t stream)
         attr_done = true;
     }
     const int nqt = (int)((p.Q + BN - 1) / BN);
-    const int64_t total = p.n_row_tiles * nqt;
+    const int64_t total = p.n_row_tiles * (SCAN_BM / BM) * nqt;
     if (total <= 0) return hipSuccess;
     if (total > 0x7fffffffLL) return hipErrorInvalidValue;   // the kernel counts items in 32 bits
     const int per_cu = smem * 2 <= 160 * 1024 ? 2 : 1;
@@ -710,7 +721,7 @@ hipError_t launch_dma(const ScanParams &p, int n_cu, hipStream_t stream)
     const int bn = scan_bn_for(p.Q);
     switch (bn) {
         case 32: return launch_dma_variant<F16, 4, 1, 2, 1, 64, 4>(p, n_cu, stream);
-        case 64: return launch_dma_variant<F16, 4, 1, 2, 2, 32, 7>(p, n_cu, stream);
+        case 64: return launch_dma_variant<F16, 4, 1, 1, 2, 64, 6>(p, n_cu, stream);
         case 128: return launch_dma_variant<F16, 2, 2, 4, 2, 32, 6>(p, n_cu, stream);
         default: return launch_dma_variant<F16, 2, 4, 4, 2, 32, 4>(p, n_cu, stream);
     }
