@@ -8,7 +8,7 @@ namespace ralm {
 
 typedef unsigned long long u64;
 
-constexpr int SCAN_BM = 256;       // datastore rows per scan tile (all variants)
+constexpr int SCAN_BM = 256;       // datastore rows per tile of the stage ladder (a workgroup takes one, or half of one)
 constexpr int SCAN_BK = 64;        // reduction elements staged per pipeline step
 constexpr int SCAN_QPAD = 256;     // query matrix is zero-padded to a multiple of this
 
@@ -16,7 +16,7 @@ struct ScanParams {
     const void *X;          // scan copy [N, ldx]
     int64_t ldx;            // elements
     int64_t N;
-    int32_t d;              // true reduction length (multiple of 8)
+    int32_t d;              // reduction length: columns of X that are scored (multiple of 8)
     int32_t in_dtype;       // DT_* of X
     const uint16_t *Qs;     // converted queries [Qpad, dpad], zero padded
     int32_t dpad;           // multiple of SCAN_BK

@@ -7,8 +7,8 @@
 // accumulation) and each one is compared at once with its query's admission key; the few
 // that pass are appended to that query's candidate list.
 //
-// Tiling: a workgroup of 4 waves owns a 256-row x BN-query tile; the reduction dimension is
-// walked in strips of BK elements.  Datastore rows are the A operand of v_mfma_f32_32x32x16,
+// Tiling: a workgroup of 4 or 8 waves owns a 256-row (for one variant: 128-row) x BN-query
+// tile; the reduction dimension is walked in strips of BK elements.  Datastore rows are the A operand of v_mfma_f32_32x32x16,
 // queries the B operand, so every accumulator register of a lane belongs to ONE query
 // (column = lane % 32) and the lane can hold that query's threshold in a register.
 //
@@ -19,8 +19,8 @@
 //                       boundaries; the 16-byte chunks of a row are XOR-swizzled on the way in
 //                       (by choosing which global chunk each lane fetches) so that the MFMA
 //                       operand reads (32 rows, same chunk) are free of bank conflicts.
-//   scan_staged_kernel  fp32 datastore: rows are rounded to bf16 in registers on the way to
-//                       LDS (double buffered).
+//   scan_staged_kernel  global -> registers -> LDS, double buffered: fp32 datastores (rows are
+//                       rounded to bf16 on the way) and the stages that keep every score.
 //
 // Work items (row tile, query tile) are dealt to a persistent grid so that workgroups that
 // run at the same time on one XCD (workgroup b lands on XCD b % 8) hold consecutive items:
