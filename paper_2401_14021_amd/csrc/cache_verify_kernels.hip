@@ -14,6 +14,8 @@
 //                       verification": top-1 or top-k update; Section 5.3: the next n rows
 //                       after a retrieved one), skipping ids already cached, first in first
 //                       out once the cache is full.
+#include <atomic>
+
 #include "ralm_common.h"
 #include "ralm_kernels.h"
 
@@ -375,12 +377,12 @@ hipError_t launch_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *
 {
     if (R <= 0) return hipSuccess;
     const size_t smem = (size_t)((C + 255) & ~255) * sizeof(int32_t);
-    static bool attr_done = false;
-    if (!attr_done) {
+    static std::atomic<bool> attr_done{false};   // per instantiation; setting it twice is harmless
+    if (!attr_done.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(cache_insert_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, CACHE_INSERT_MAX_C * 4);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_done.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(cache_insert_kernel, dim3((unsigned)R), dim3(64), smem, stream, cache_ids, cache_len,
                        cache_head, C, truth, true_stride, Qt, q_offsets, first_mismatch, p, n_next, N);

@@ -28,6 +28,8 @@
 // readers therefore hit that XCD's L2.
 #include <type_traits>
 
+#include <atomic>
+
 #include "ralm_common.h"
 #include "ralm_kernels.h"
 
@@ -696,12 +698,12 @@ hipError_t launch_dma_variant(const ScanParams &p, int n_cu, hipStream_t stream)
     static_assert(smem <= 160 * 1024, "LDS budget");
     auto kern = scan_dma_kernel<F16, WM, WN, TM, TN, BK, S>;
     const int tau_in_lds = p.Q <= tau_lds_q(BN) ? 1 : 0;
-    static bool attr_done = false;
-    if (!attr_done) {
+    static std::atomic<bool> attr_done{false};   // per instantiation; setting it twice is harmless
+    if (!attr_done.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_done.store(true, std::memory_order_release);
     }
     const int nqt = (int)((p.Q + BN - 1) / BN);
     const int64_t total = p.n_row_tiles * (SCAN_BM / BM) * nqt;
@@ -733,12 +735,12 @@ hipError_t launch_variant(const ScanParams &p, int n_cu, hipStream_t stream)
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, LDA = SCAN_BK + 8;
     constexpr size_t smem = (size_t)2 * (BM + BN) * LDA * sizeof(uint16_t);
     auto kern = scan_staged_kernel<IN, WM, WN, TM, TN>;
-    static bool attr_done = false;   // per instantiation
-    if (!attr_done) {
+    static std::atomic<bool> attr_done{false};   // per instantiation; setting it twice is harmless
+    if (!attr_done.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_done.store(true, std::memory_order_release);
     }
     const int nqt = (int)((p.Q + BN - 1) / BN);
     const int64_t total = p.n_row_tiles * nqt;
