@@ -646,7 +646,32 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
             buf = nbuf;
         };
 
-        if (KT == 1) {
+        // A wave whose query columns are all padding (the batch's last query tile is ragged) has
+        // nothing to multiply or select: it only keeps its part of the load ring and the
+        // rendezvous going, and reads the operands of the next tile's first k-step at the end.
+        auto stage_idle = [&]() __attribute__((always_inline)) {
+            const int nbuf = buf + 1 == S ? 0 : buf + 1;
+            RALM_SCHED_FENCE();
+            wait_vmcnt<LPS *(S - 3)>();
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            issue_begin();
+#pragma unroll
+            for (int idx = NA; idx < LPS; ++idx) issue_part(idx);   // query part, as in k-step 0
+#pragma unroll
+            for (int idx = 0; idx < NA; ++idx) issue_part(idx);     // datastore part, as in k-step 1
+            issue_end();
+#pragma unroll
+            for (int idx = 0; idx < NR; ++idx) read_frag(((KS - 1) & 1) ^ 1, smem + nbuf * STAGE, 0, idx);
+            RALM_SCHED_FENCE();
+            buf = nbuf;
+        };
+        const bool wave_idle = q0 + wn * TN * 32 >= p.Q;   // wave-uniform
+
+        if (wave_idle) {
+            for (int kt = 0; kt < KT; ++kt) stage_idle();
+        } else if (KT == 1) {
             stage(std::true_type{}, std::true_type{});
         } else {
             stage(std::true_type{}, std::false_type{});
