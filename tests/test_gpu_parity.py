@@ -638,3 +638,28 @@ def test_k_and_k_prime_boundaries(B, oracle, k, k_prime, N):
     Qm = torch.randint(-4, 5, (5, d), generator=g).float()
     ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, X, Qm, k, k_prime=k_prime)
     assert np.array_equal(ids, wi) and np.array_equal(sc, wsc)
+
+
+@pytest.mark.parametrize("d,Q", [(8, 3), (2048, 5), (2048, 70), (4096, 33), (16384, 2)])
+def test_extreme_row_lengths(B, oracle, d, Q):
+    """The shortest and the longest rows the library accepts (cache lookup: up to d = 2048)."""
+    g = torch.Generator().manual_seed(d + Q)
+    N, k = 3000, 6
+    X = torch.randint(-2, 3, (N, d), generator=g).float()
+    Qm = torch.randint(-2, 3, (Q, d), generator=g).float()
+    ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, X, Qm, k)
+    assert np.array_equal(ids, wi) and np.array_equal(sc, wsc)
+    if d <= 2048:
+        R = Q
+        off = torch.arange(R + 1, dtype=torch.int64)
+        cache = torch.stack([torch.randperm(N, generator=g)[:40] for _ in range(R)]).to(torch.int32)
+        clen = torch.full((R,), 40, dtype=torch.int32)
+        ds = B.Datastore.from_fp32(X.cuda())
+        spec, ssc = B.ralm_cache_lookup(cache.cuda(), clen.cuda(), Qm.cuda(), off.cuda(), ds)
+        wspec, wssc = oracle.cache_lookup(cache.numpy(), clen.numpy(), Qm.numpy(), off.numpy(), X.numpy())
+        assert np.array_equal(spec.cpu().numpy(), wspec) and np.array_equal(ssc.cpu().numpy(), wssc)
+    else:
+        ds = B.Datastore.from_fp32(X.cuda())
+        with pytest.raises(B.RalmError):
+            B.ralm_cache_lookup(torch.zeros(1, 4, dtype=torch.int32).cuda(), torch.zeros(1, dtype=torch.int32).cuda(),
+                                Qm[:1].cuda(), torch.tensor([0, 1]).cuda(), ds)
