@@ -185,6 +185,17 @@ def main():
     except OSError:
         pass
 
+    # fraction of cycles in which the matrix cores were busy, and the shader clock, from rocprofv3
+    # counters of the same command (summary under profiles/); absent if not measured for this case
+    try:
+        with open(os.path.join(ROOT, "profiles", "scan_mfma_busy.json")) as fh:
+            mb = json.load(fh).get(f"{args.workload}:Q={head['Q']}") if not args.N and not l2 else None
+        if mb:
+            roof["mfma_busy_frac"] = mb["mfma_busy_frac"]
+            roof["shader_clock_GHz"] = mb["shader_clock_GHz"]
+    except OSError:
+        pass
+
     # ---- the speculation loop closed by the cache update (stress workload only) ----------------
     closed = None
     if args.workload == "specloop":
