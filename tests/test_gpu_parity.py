@@ -663,3 +663,14 @@ def test_extreme_row_lengths(B, oracle, d, Q):
         with pytest.raises(B.RalmError):
             B.ralm_cache_lookup(torch.zeros(1, 4, dtype=torch.int32).cuda(), torch.zeros(1, dtype=torch.int32).cuda(),
                                 Qm[:1].cuda(), torch.tensor([0, 1]).cuda(), ds)
+
+
+def test_more_queries_than_admission_keys_fit_in_lds(B, oracle):
+    """Beyond 2560 queries the scan reads its admission keys from global memory instead of LDS."""
+    from paper_2401_14021_amd import inputs
+    N, d, Q, k = 40000, 64, 3000, 5
+    X, _ = inputs.clustered_datastore(N, d, 32, seed=95)
+    Qm = inputs.queries_near_rows(X, inputs.pick_rows(N, Q, seed=96), seed=97)
+    ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, X, Qm, k)
+    exact, subs, total = check_topk(ids, sc, wi, wsc, _score_fn(oracle, Qm.numpy(), X.numpy()))
+    assert exact >= 0.99 * total
