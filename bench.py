@@ -47,7 +47,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build is a one-GPU kernel path; run with --gpus 1 "
-              "(row-sharding over several GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+              "(sharding the datastore by rows over several GPUs is a design note only, not built)", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2401_14021_amd import binding as B, inputs
