@@ -19,6 +19,10 @@
  *   - Calls enqueue work on the given HIP stream (a hipStream_t passed as
  *     void*; NULL = the default stream) and return without synchronising,
  *     except where stated.  Work of one call is ordered on that stream.
+ *     Apart from ralm_retrieve_topk and ralm_workspace_overflows, a call only
+ *     launches kernels (no allocation, no memset or copy nodes), so after one
+ *     ordinary call of the same shapes (the first launch of a kernel sets its
+ *     attributes) it may be recorded into a HIP graph and replayed.
  *   - Matrices are row-major.  ids are int32 row numbers of the datastore
  *     (N < 2^31); sizes are int64.
  *   - The ranking is always (score descending, row id ascending): equal scores

@@ -674,3 +674,70 @@ def test_more_queries_than_admission_keys_fit_in_lds(B, oracle):
     ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, X, Qm, k)
     exact, subs, total = check_topk(ids, sc, wi, wsc, _score_fn(oracle, Qm.numpy(), X.numpy()))
     assert exact >= 0.99 * total
+
+
+def test_a_verification_round_replays_from_a_hip_graph(B, oracle):
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no
+    synchronisation, no memset nodes), so a whole round - speculate, verify, compare, update the
+    caches - can be captured once and replayed.  Every replay, with new queries written into the
+    captured input buffer and eager work in between, must equal the eager result."""
+    from paper_2401_14021_amd import inputs
+    N, d, R, C, k = 50000, 128, 16, 32, 5
+    X, _ = inputs.clustered_datastore(N, d, 32, seed=101)
+    ds = B.Datastore.from_fp32(X.cuda())
+    off = inputs.stride_offsets(inputs.uniform_strides(R, 1, 4, seed=102))
+    Q = int(off[-1])
+    offd = off.cuda()
+    rows = inputs.pick_rows(N, Q, seed=103)
+    q_in = inputs.queries_near_rows(X, rows, seed=104).cuda()
+    cids0, clen0 = inputs.speculation_caches(N, R, C, off, rows, None, seed=105)
+    ws = B.alloc_workspace(Q, ds, k)
+
+    def fresh_state():
+        return cids0.cuda().clone(), clen0.cuda().clone(), torch.zeros(R, dtype=torch.int32, device="cuda")
+
+    def one_round(cids, clen, head, out):
+        B.ralm_cache_lookup(cids, clen, q_in, offd, ds, out["spec"], out["ssc"])
+        B.ralm_retrieve_topk_ex(q_in, ds, k, workspace=ws, out_ids=out["ids"], out_scores=out["sc"])
+        B.ralm_verify(out["spec"], out["ids"], offd, true_stride=k, first_mismatch=out["fm"])
+        B.ralm_cache_insert(cids, clen, head, out["ids"], offd, N, p=k, first_mismatch=out["fm"])
+
+    def outputs():
+        return dict(spec=torch.empty(Q, dtype=torch.int32, device="cuda"), ssc=torch.empty(Q, device="cuda"),
+                    ids=torch.empty(Q, k, dtype=torch.int32, device="cuda"), sc=torch.empty(Q, k, device="cuda"),
+                    fm=torch.empty(R, dtype=torch.int32, device="cuda"))
+
+    g_state, g_out = fresh_state(), outputs()
+    one_round(*g_state, g_out)                 # warm-up: first launches set kernel attributes
+    torch.cuda.synchronize()
+    g_state[0].copy_(cids0.cuda()); g_state[1].copy_(clen0.cuda()); g_state[2].zero_()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        one_round(*g_state, g_out)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g_state[0].copy_(cids0.cuda()); g_state[1].copy_(clen0.cuda()); g_state[2].zero_()
+
+    e_state, e_out = fresh_state(), outputs()
+    q_cur = q_in.clone()
+    for rep in range(4):
+        q_in.copy_(q_cur)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = {n: t.clone() for n, t in g_out.items()}
+        got_state = [t.clone() for t in g_state]
+        one_round(*e_state, e_out)             # eager, same inputs, its own state
+        torch.cuda.synchronize()
+        for n in e_out:
+            assert torch.equal(got[n], e_out[n]), (rep, n)
+        for a, b in zip(got_state[1:], e_state[1:]):
+            assert torch.equal(a, b), rep
+        for r in range(R):
+            assert torch.equal(got_state[0][r, :int(got_state[1][r])], e_state[0][r, :int(e_state[1][r])])
+        q_cur = inputs.drift_queries(q_cur, seed=110 + rep)
+    wi, _ = oracle.retrieve_topk(q_in.cpu().numpy(), X.numpy(), k)
+    assert np.array_equal(got["ids"].cpu().numpy(), wi)
