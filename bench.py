@@ -116,6 +116,7 @@ def main():
         cids, clen = inputs.speculation_caches(N, R, C, off, rows, None, seed=seed + 2)
         return dict(Q=Q, R=R, off=off.to(dev), Qm=Qm, cids=cids.to(dev), clen=clen.to(dev),
                     ws=B.alloc_workspace(Q, ds, k, w.k_prime),
+                    cl_ws=torch.empty(Q, dtype=torch.int64, device=dev),
                     ids=torch.empty(Q, k, dtype=torch.int32, device=dev),
                     sc=torch.empty(Q, k, dtype=torch.float32, device=dev),
                     spec=torch.empty(Q, dtype=torch.int32, device=dev),
@@ -123,7 +124,7 @@ def main():
                     mism=torch.empty(R, dtype=torch.int32, device=dev))
 
     def step(b):
-        B.ralm_cache_lookup(b["cids"], b["clen"], b["Qm"], b["off"], ds, b["spec"], b["spec_sc"])
+        B.ralm_cache_lookup(b["cids"], b["clen"], b["Qm"], b["off"], ds, b["spec"], b["spec_sc"], workspace=b["cl_ws"])
         B.ralm_retrieve_topk_ex(b["Qm"], ds, k, w.k_prime, workspace=b["ws"], out_ids=b["ids"],
                                 out_scores=b["sc"])
         B.ralm_verify(b["spec"], b["ids"], b["off"], true_stride=k, first_mismatch=b["mism"])
@@ -214,7 +215,7 @@ def main():
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
         rounds, hit, accepted, ins_ms = 12, [], [], 0.0
         for rnd in range(rounds):
-            B.ralm_cache_lookup(cids, clen, q, b["off"], ds, b["spec"], b["spec_sc"])
+            B.ralm_cache_lookup(cids, clen, q, b["off"], ds, b["spec"], b["spec_sc"], workspace=b["cl_ws"])
             B.ralm_retrieve_topk_ex(q, ds, kc, w.k_prime, workspace=ws_c, out_ids=ids_c, out_scores=sc_c)
             B.ralm_verify(b["spec"], ids_c, b["off"], true_stride=kc, first_mismatch=b["mism"])
             ev[0].record()

@@ -223,11 +223,20 @@ ralm_status ralm_build_scan_copy_l2(const void *src, int32_t src_dtype, int64_t 
  *   spec_ids   device int32 [Qt]: top-1 cached id per query (-1 if the cache
  *              is empty);  spec_scores device fp32 [Qt] (-inf if empty).
  *              Rows of [0, Qt) that no request owns are left untouched.
+ *   workspace  optional device scratch (may be NULL) of at least
+ *              ralm_cache_lookup_workspace_bytes(Qt) = 8 bytes per query,
+ *              8-byte aligned, contents undefined between calls.  Without it
+ *              one workgroup serves a request, which leaves most of the chip
+ *              idle when there are few requests (a single request with 4096
+ *              cached rows then takes ~0.4 ms); with it the caches of fewer
+ *              than 128 requests are each split over several workgroups that
+ *              merge through the workspace (same results).
  */
+size_t ralm_cache_lookup_workspace_bytes(int64_t Qt);
 ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
                               const float *queries, int64_t Qt, const int64_t *q_offsets,
                               const ralm_datastore_t *ds, int32_t *spec_ids, float *spec_scores,
-                              void *stream);
+                              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Verification compare (Alg. 1: m = argmin_i d^_i != d_i).  For request r with

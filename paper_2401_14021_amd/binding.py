@@ -62,7 +62,9 @@ def lib() -> ctypes.CDLL:
         L.ralm_workspace_overflows.argtypes = [vp, vp, ctypes.POINTER(i32)]
         L.ralm_build_scan_copy.argtypes = [vp, i64, vp, i32, i64, i64, i32, vp]
         L.ralm_build_scan_copy_l2.argtypes = [vp, i32, i64, vp, i32, i64, i64, i32, vp]
-        L.ralm_cache_lookup.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, vp, vp, vp]
+        L.ralm_cache_lookup.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ralm_cache_lookup_workspace_bytes.argtypes = [i64]
+        L.ralm_cache_lookup_workspace_bytes.restype = ctypes.c_size_t
         L.ralm_verify.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp]
         L.ralm_cache_insert.argtypes = [vp, vp, vp, i32, i64, vp, i64, i64, vp, vp, i32, i32, i64, vp]
         L.ralm_knnlm_probs.argtypes = [vp, vp, i64, i32, vp, i64, ctypes.c_float, vp, vp, vp, vp, vp]
@@ -217,8 +219,11 @@ def ralm_retrieve_topk(queries: torch.Tensor, datastore: torch.Tensor, k: int
 
 def ralm_cache_lookup(cache_ids: torch.Tensor, cache_len: torch.Tensor, queries: torch.Tensor,
                       q_offsets: torch.Tensor, ds: Datastore,
-                      spec_ids: Optional[torch.Tensor] = None, spec_scores: Optional[torch.Tensor] = None
+                      spec_ids: Optional[torch.Tensor] = None, spec_scores: Optional[torch.Tensor] = None,
+                      workspace: Optional[torch.Tensor] = None, use_workspace: bool = True
                       ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """``workspace``: int64 tensor of at least Qt elements; allocated here when None (pass
+    use_workspace=False to call without one: one workgroup per request)."""
     assert cache_ids.dtype == torch.int32 and cache_len.dtype == torch.int32
     assert q_offsets.dtype == torch.int64 and queries.dtype == torch.float32
     assert cache_ids.is_contiguous() and queries.is_contiguous()
@@ -228,9 +233,12 @@ def ralm_cache_lookup(cache_ids: torch.Tensor, cache_len: torch.Tensor, queries:
         spec_ids = torch.full((Qt,), -1, dtype=torch.int32, device=queries.device)
     if spec_scores is None:
         spec_scores = torch.full((Qt,), float("-inf"), dtype=torch.float32, device=queries.device)
+    if workspace is None and use_workspace:
+        workspace = torch.empty(max(Qt, 1), dtype=torch.int64, device=queries.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().ralm_cache_lookup(cache_ids.data_ptr(), cache_len.data_ptr(), C, R, queries.data_ptr(), Qt,
                                    q_offsets.data_ptr(), ctypes.byref(ds.desc), spec_ids.data_ptr(),
-                                   spec_scores.data_ptr(), _stream()))
+                                   spec_scores.data_ptr(), _ptr(workspace), ws_bytes, _stream()))
     return spec_ids, spec_scores
 
 

@@ -44,13 +44,16 @@ __global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
     const int32_t *__restrict__ cache_ids, const int32_t *__restrict__ cache_len, int C,
     const float *__restrict__ queries, int64_t Qt, const int64_t *__restrict__ q_offsets,
     const void *__restrict__ exact, int64_t ld, int64_t N, int d, int qgroup,
-    int32_t *__restrict__ spec_ids, float *__restrict__ spec_scores)
+    int32_t *__restrict__ spec_ids, float *__restrict__ spec_scores, u64 *__restrict__ partial)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     float *qs = reinterpret_cast<float *>(smem);                   // [qgroup][d]
     u64 *best = reinterpret_cast<u64 *>(qs + (size_t)qgroup * d);   // [NW waves][CL_ROWS][qgroup]
 
+    // gridDim.y workgroups share a request (few requests: spread each over many CUs); they then
+    // merge their best keys with a 64-bit atomic max in `partial`, decoded by a second kernel
     const int64_t r = blockIdx.x;
+    const int part = blockIdx.y, parts = gridDim.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane % CL_GS, slot = lane / CL_GS;
     int64_t q_lo, q_hi;
@@ -68,7 +71,7 @@ __global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
         __syncthreads();
         u64 *my_best = best + (wave * CL_ROWS + slot) * qgroup;
 
-        for (int e0 = wave * CL_ROWS; e0 < len; e0 += NW * CL_ROWS) {
+        for (int e0 = (part * NW + wave) * CL_ROWS; e0 < len; e0 += parts * NW * CL_ROWS) {
             const int e = e0 + slot;
             const int32_t id = e < len ? ids[e] : -1;
             const bool ok = id >= 0 && (int64_t)id < N;
@@ -127,9 +130,31 @@ __global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
                 const u64 v = best[w * qgroup + qi];
                 b = v > b ? v : b;
             }
-            spec_ids[g0 + qi] = b ? key_id(b) : -1;
-            spec_scores[g0 + qi] = b ? key_score(b) : -__builtin_inff();
+            if (partial) {
+                if (b) atomicMax(reinterpret_cast<unsigned long long *>(partial + g0 + qi), b);
+            } else {
+                spec_ids[g0 + qi] = b ? key_id(b) : -1;
+                spec_scores[g0 + qi] = b ? key_score(b) : -__builtin_inff();
+            }
         }
+    }
+}
+
+// decodes the merged keys of the split lookup; one wave per request
+__global__ __launch_bounds__(256) void cache_lookup_finish_kernel(const u64 *__restrict__ partial, int64_t Qt,
+                                                                  const int64_t *__restrict__ q_offsets, int64_t R,
+                                                                  int32_t *__restrict__ spec_ids,
+                                                                  float *__restrict__ spec_scores)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= R) return;
+    int64_t lo, hi;
+    clamp_range(q_offsets, r, Qt, lo, hi);
+    for (int64_t q = lo + lane; q < hi; q += 64) {
+        const u64 b = partial[q];
+        spec_ids[q] = b ? key_id(b) : -1;
+        spec_scores[q] = b ? key_score(b) : -__builtin_inff();
     }
 }
 
@@ -319,7 +344,7 @@ template <int EX, bool L2>
 hipError_t launch_cache_ex(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
                            const float *queries, int64_t Qt, const int64_t *q_offsets, const void *exact,
                            int64_t ld, int64_t N, int32_t d, int32_t *spec_ids, float *spec_scores,
-                           hipStream_t stream)
+                           u64 *partial, int parts, hipStream_t stream)
 {
     int qgroup = CL_LDS_BYTES / (d * 4);
     if (qgroup > 16) qgroup = 16;
@@ -327,10 +352,11 @@ hipError_t launch_cache_ex(const int32_t *cache_ids, const int32_t *cache_len, i
     const int nch = (d + CL_GS * 4 - 1) / (CL_GS * 4);
     // a lane keeps its NCH chunks in registers, which bounds the waves a block can hold
 #define RALM_CL(NCHV, NWV)                                                                                  \
-    hipLaunchKernelGGL((cache_lookup_kernel<EX, NCHV, NWV, L2>), dim3((unsigned)R), dim3(NWV * 64),             \
+    hipLaunchKernelGGL((cache_lookup_kernel<EX, NCHV, NWV, L2>), dim3((unsigned)R, (unsigned)parts),         \
+                       dim3(NWV * 64),                                                                      \
                        (size_t)qgroup * d * 4 + (size_t)NWV * CL_ROWS * qgroup * sizeof(u64), stream,       \
                        cache_ids, cache_len, C, queries, Qt, q_offsets, exact, ld, N, d, qgroup, spec_ids,  \
-                       spec_scores)
+                       spec_scores, partial)
     if (nch <= 4) RALM_CL(4, 16);
     else if (nch <= 8) RALM_CL(8, 16);
     else if (nch <= 12) RALM_CL(12, 16);
@@ -346,19 +372,40 @@ hipError_t launch_cache_ex(const int32_t *cache_ids, const int32_t *cache_len, i
 hipError_t launch_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
                                const float *queries, int64_t Qt, const int64_t *q_offsets,
                                const void *exact, int32_t exact_dtype, int64_t ld, int64_t N, int32_t d,
-                               int32_t metric, int32_t *spec_ids, float *spec_scores, hipStream_t stream)
+                               int32_t metric, int32_t *spec_ids, float *spec_scores, u64 *partial,
+                               hipStream_t stream)
 {
     if (R <= 0) return hipSuccess;
-#define RALM_CACHE(EXV, L2V)                                                                             \
-    return launch_cache_ex<EXV, L2V>(cache_ids, cache_len, C, R, queries, Qt, q_offsets, exact, ld, N, d, \
-                                     spec_ids, spec_scores, stream)
+    // With few requests one workgroup per request leaves most of the chip idle: split every
+    // request's cache over `parts` workgroups (at least 64 cached rows each), if the caller
+    // gave scratch for the merge.
+    int parts = 1;
+    if (partial && R < 128) {
+        const int64_t want = (256 + R - 1) / R, most = (C + 63) / 64;
+        parts = (int)(want < most ? want : most);
+        if (parts < 1) parts = 1;
+    }
+    if (parts == 1) partial = nullptr;
+    hipError_t e = hipSuccess;
+    if (partial) {
+        e = launch_fill_u64(partial, 0ull, Qt, stream);
+        if (e != hipSuccess) return e;
+    }
+#define RALM_CACHE(EXV, L2V)                                                                           \
+    e = launch_cache_ex<EXV, L2V>(cache_ids, cache_len, C, R, queries, Qt, q_offsets, exact, ld, N, d, \
+                                  spec_ids, spec_scores, partial, parts, stream)
     if (exact_dtype == DT_F16) {
         if (metric == METRIC_L2) RALM_CACHE(DT_F16, true);
-        RALM_CACHE(DT_F16, false);
+        else RALM_CACHE(DT_F16, false);
+    } else {
+        if (metric == METRIC_L2) RALM_CACHE(DT_F32, true);
+        else RALM_CACHE(DT_F32, false);
     }
-    if (metric == METRIC_L2) RALM_CACHE(DT_F32, true);
-    RALM_CACHE(DT_F32, false);
 #undef RALM_CACHE
+    if (e != hipSuccess || !partial) return e;
+    hipLaunchKernelGGL(cache_lookup_finish_kernel, dim3((unsigned)((R + 3) / 4)), dim3(256), 0, stream, partial, Qt,
+                       q_offsets, R, spec_ids, spec_scores);
+    return hipGetLastError();
 }
 
 hipError_t launch_verify(const int32_t *spec, const int32_t *truth, int64_t true_stride, int64_t Qt,

@@ -395,9 +395,12 @@ ralm_status ralm_build_scan_copy_l2(const void *src, int32_t src_dtype, int64_t 
     return RALM_OK;
 }
 
+size_t ralm_cache_lookup_workspace_bytes(int64_t Qt) { return Qt < 0 ? 0 : up256((size_t)(Qt > 0 ? Qt : 1) * 8); }
+
 ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
                               const float *queries, int64_t Qt, const int64_t *q_offsets,
-                              const ralm_datastore_t *ds, int32_t *spec_ids, float *spec_scores, void *stream)
+                              const ralm_datastore_t *ds, int32_t *spec_ids, float *spec_scores, void *workspace,
+                              size_t workspace_bytes, void *stream)
 {
     if (!cache_ids || !cache_len || !queries || !q_offsets || !spec_ids || !spec_scores)
         return fail(RALM_ERR_NULL, "a pointer is NULL");
@@ -407,9 +410,12 @@ ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len
     if (st != RALM_OK) return st;
     if (ds->d > 2048) return fail(RALM_ERR_SHAPE, "cache lookup supports d <= 2048");
     if (!aligned16(queries)) return fail(RALM_ERR_ALIGN, "queries must be 16-byte aligned");
+    if (workspace && ((reinterpret_cast<uintptr_t>(workspace) & 7u) || workspace_bytes < (size_t)Qt * 8))
+        return fail(RALM_ERR_WORKSPACE, "workspace must be 8-byte aligned and hold 8 bytes per query");
     const int64_t ld = ds->exact_stride ? ds->exact_stride : ds->d;
     RALM_HIP(launch_cache_lookup(cache_ids, cache_len, C, R, queries, Qt, q_offsets, ds->exact, ds->exact_dtype, ld,
-                                 ds->N, ds->d, ds->metric, spec_ids, spec_scores, static_cast<hipStream_t>(stream)));
+                                 ds->N, ds->d, ds->metric, spec_ids, spec_scores, static_cast<u64 *>(workspace),
+                                 static_cast<hipStream_t>(stream)));
     return RALM_OK;
 }
 

@@ -63,7 +63,8 @@ hipError_t launch_rescore(const u64 *cand, const uint32_t *cnt, uint32_t cap, in
 hipError_t launch_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
                                const float *queries, int64_t Qt, const int64_t *q_offsets,
                                const void *exact, int32_t exact_dtype, int64_t ld, int64_t N, int32_t d,
-                               int32_t metric, int32_t *spec_ids, float *spec_scores, hipStream_t stream);
+                               int32_t metric, int32_t *spec_ids, float *spec_scores, u64 *partial,
+                               hipStream_t stream);
 
 constexpr int CACHE_INSERT_MAX_C = 16384;   // a request's cache row is held in LDS during an update
 hipError_t launch_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *cache_head, int32_t C, int64_t R,

@@ -88,9 +88,12 @@ def test_argument_errors_return_status_without_a_device(L):
     assert L.ralm_retrieve_topk(None, 8, P, 1000, 768, 5, P, P) == 1
     assert L.ralm_retrieve_topk(P, 8, P, 1000, 768, 1001, P, P) == 3
     # cache lookup / verify / scan copy
-    assert L.ralm_cache_lookup(None, P, 4, 2, P, 6, P, ref(ds), P, P, None) == 1
-    assert L.ralm_cache_lookup(P, P, 0, 2, P, 6, P, ref(ds), P, P, None) == 2
-    assert L.ralm_cache_lookup(P, P, 4, 2, P, -1, P, ref(ds), P, P, None) == 7
+    assert L.ralm_cache_lookup(None, P, 4, 2, P, 6, P, ref(ds), P, P, None, 0, None) == 1
+    assert L.ralm_cache_lookup(P, P, 0, 2, P, 6, P, ref(ds), P, P, None, 0, None) == 2
+    assert L.ralm_cache_lookup(P, P, 4, 2, P, -1, P, ref(ds), P, P, None, 0, None) == 7
+    assert L.ralm_cache_lookup(P, P, 4, 2, P, 6, P, ref(ds), P, P, P, 40, None) == 6     # 8 bytes per query needed
+    assert L.ralm_cache_lookup(P, P, 4, 2, P, 6, P, ref(ds), P, P, P + 4, 64, None) == 6 # misaligned scratch
+    assert L.ralm_cache_lookup_workspace_bytes(6) >= 48 and L.ralm_cache_lookup_workspace_bytes(-1) == 0
     ins = L.ralm_cache_insert
     assert ins(P, P, None, 4, 2, P, 5, 6, P, None, 1, 0, 1000, None) == 1         # no head array
     assert ins(P, P, P, 0, 2, P, 5, 6, P, None, 1, 0, 1000, None) == 2            # C < 1

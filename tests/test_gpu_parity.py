@@ -692,12 +692,13 @@ def test_a_verification_round_replays_from_a_hip_graph(B, oracle):
     q_in = inputs.queries_near_rows(X, rows, seed=104).cuda()
     cids0, clen0 = inputs.speculation_caches(N, R, C, off, rows, None, seed=105)
     ws = B.alloc_workspace(Q, ds, k)
+    cl_ws = torch.empty(Q, dtype=torch.int64, device="cuda")
 
     def fresh_state():
         return cids0.cuda().clone(), clen0.cuda().clone(), torch.zeros(R, dtype=torch.int32, device="cuda")
 
     def one_round(cids, clen, head, out):
-        B.ralm_cache_lookup(cids, clen, q_in, offd, ds, out["spec"], out["ssc"])
+        B.ralm_cache_lookup(cids, clen, q_in, offd, ds, out["spec"], out["ssc"], workspace=cl_ws)
         B.ralm_retrieve_topk_ex(q_in, ds, k, workspace=ws, out_ids=out["ids"], out_scores=out["sc"])
         B.ralm_verify(out["spec"], out["ids"], offd, true_stride=k, first_mismatch=out["fm"])
         B.ralm_cache_insert(cids, clen, head, out["ids"], offd, N, p=k, first_mismatch=out["fm"])
@@ -741,3 +742,29 @@ def test_a_verification_round_replays_from_a_hip_graph(B, oracle):
         q_cur = inputs.drift_queries(q_cur, seed=110 + rep)
     wi, _ = oracle.retrieve_topk(q_in.cpu().numpy(), X.numpy(), k)
     assert np.array_equal(got["ids"].cpu().numpy(), wi)
+
+
+@pytest.mark.parametrize("R,C,smax,d", [(1, 4096, 1, 768), (1, 64, 5, 768), (2, 1024, 4, 768), (7, 300, 8, 136),
+                                        (40, 2000, 3, 64), (127, 128, 2, 256), (128, 512, 2, 64)])
+def test_cache_lookup_split_over_workgroups_equals_one_per_request(B, oracle, R, C, smax, d):
+    """With a workspace and fewer than 128 requests each cache is searched by several workgroups;
+    ragged cache lengths, empty caches and requests without queries included."""
+    from paper_2401_14021_amd import inputs
+    N = 30000
+    rng = np.random.default_rng(R * 7 + C)
+    X, _ = inputs.clustered_datastore(N, d, 32, seed=C)
+    strides = rng.integers(0, smax + 1, size=R)
+    strides[0] = max(strides[0], 1)
+    off = inputs.stride_offsets([int(v) for v in strides])
+    Q = int(off[-1])
+    rows = inputs.pick_rows(N, Q, seed=5)
+    Qm = inputs.queries_near_rows(X, rows, seed=6)
+    cids = torch.from_numpy(rng.integers(0, N, size=(R, C)).astype(np.int32))
+    clen = torch.from_numpy(rng.choice([0, 1, C // 3, C], size=R).astype(np.int32))
+    clen[0] = C
+    ds = B.Datastore.from_fp32(X.cuda())
+    a_ids, a_sc = B.ralm_cache_lookup(cids.cuda(), clen.cuda(), Qm.cuda(), off.cuda(), ds, use_workspace=False)
+    b_ids, b_sc = B.ralm_cache_lookup(cids.cuda(), clen.cuda(), Qm.cuda(), off.cuda(), ds)
+    assert torch.equal(a_ids, b_ids) and torch.equal(a_sc, b_sc)
+    w_ids, w_sc = oracle.cache_lookup(cids.numpy(), clen.numpy(), Qm.numpy(), off.numpy(), X.numpy())
+    assert np.array_equal(b_ids.cpu().numpy(), w_ids) and np.array_equal(b_sc.cpu().numpy(), w_sc)
