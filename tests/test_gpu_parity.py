@@ -768,3 +768,29 @@ def test_cache_lookup_split_over_workgroups_equals_one_per_request(B, oracle, R,
     assert torch.equal(a_ids, b_ids) and torch.equal(a_sc, b_sc)
     w_ids, w_sc = oracle.cache_lookup(cids.numpy(), clen.numpy(), Qm.numpy(), off.numpy(), X.numpy())
     assert np.array_equal(b_ids.cpu().numpy(), w_ids) and np.array_equal(b_sc.cpu().numpy(), w_sc)
+
+
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        N = int(rng.integers(1, 60000))
+        d = int(rng.integers(1, 66)) * 8
+        Q = int(rng.choice([1, 2, 7, 31, 32, 33, 63, 64, 65, 100, 127, 128, 129, 200, 255, 256, 257, 300, 520]))
+        k = int(min(N, rng.choice([1, 2, 5, 20, 64, 100])))
+        if N * d * Q <= 1.5e9:
+            out.append((N, d, Q, k))
+    return out
+
+
+@pytest.mark.parametrize("N,d,Q,k", _random_shapes(36, seed=2024))
+def test_random_shapes_bit_exact(B, oracle, N, d, Q, k):
+    """Seeded random shapes around every tile and strip boundary (rows per tile, query tile widths,
+    strip lengths, ladder depths), both scan dtypes; small integers, so everything is bit-exact."""
+    g = torch.Generator().manual_seed(N * 7 + d * 3 + Q)
+    X = torch.randint(-3, 4, (N, d), generator=g).float()
+    Qm = torch.randint(-3, 4, (Q, d), generator=g).float()
+    dt = torch.float16 if (N + Q) % 2 else torch.bfloat16
+    ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, X, Qm, k, scan_dtype=dt)
+    assert np.array_equal(ids, wi)
+    assert np.array_equal(sc, wsc)
