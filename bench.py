@@ -186,6 +186,27 @@ def main():
     except OSError:
         pass
 
+    # ---- is the exact top-k provably inside the scan's top-k'? (untimed extra call) ----------------
+    # margin = exact score at rank k minus scan score of the k'-th kept candidate.  A row outside the
+    # candidates has a scan score <= the latter, and its exact score exceeds its scan score by at
+    # most the scan's rounding error: hard bound (2u + u^2)|q||x| with u = 2^-8 (bf16) or 2^-11
+    # (fp16) for unit-norm rows (u|q||x| when only the query is rounded: fp16 keys); soft estimate
+    # 8 sigma with sigma = 0.4 u |q||x| / sqrt(d) for rounding errors that behave like noise.
+    cert = None
+    if w.exact_dtype == "f32" and not l2:
+        mg = torch.empty(hb["Q"], dtype=torch.float32, device=dev)
+        B.ralm_retrieve_topk_ex(hb["Qm"], ds, k, w.k_prime, workspace=hb["ws"], out_ids=hb["ids"],
+                                out_scores=hb["sc"], out_margin=mg)
+        u = 2.0 ** -8 if w.scan_dtype == "bf16" else 2.0 ** -11
+        qn = hb["Qm"].norm(dim=1)                      # rows are unit vectors
+        hard = (2 * u + u * u) * qn + w.d * 2.0 ** -24 * qn
+        soft = 8 * 0.4 * u * qn / (w.d ** 0.5)
+        cert = {"margin_min": round(float(mg.min().item()), 6), "margin_median": round(float(mg.median().item()), 6),
+                "hard_certified_frac": round(float((mg > hard).float().mean().item()), 4),
+                "soft_certified_frac": round(float((mg > soft).float().mean().item()), 4),
+                "hard_bound_median": round(float(hard.median().item()), 6),
+                "soft_bound_median": round(float(soft.median().item()), 6)}
+
     # fraction of cycles in which the matrix cores were busy, and the shader clock, from rocprofv3
     # counters of the same command (summary under profiles/); absent if not measured for this case
     try:
@@ -266,6 +287,8 @@ def main():
     }
     if closed:
         out["closed_loop"] = closed
+    if cert:
+        out["certificate"] = cert
     print(json.dumps(out))
 
 
