@@ -12,6 +12,10 @@
  *   m = argmin_i d^_i!=d_i first mis-speculated step -> ralm_verify
  *   Q.insert(C.retrieve(..)) cache update after verification -> ralm_cache_insert
  *
+ * and, around that loop: the stride scheduler of Section 4 as host functions
+ * (ralm_os3_*), and for KNN-LM datastores (Section 5.3) ranking by distance
+ * (RALM_METRIC_L2) and the neighbour distribution (ralm_knnlm_probs).
+ *
  * General conventions
  *   - Unless a parameter says "host", every data pointer is a DEVICE pointer
  *     owned by the caller.  The library keeps no reference after the call's
@@ -24,7 +28,7 @@
  *     ordinary call of the same shapes (the first launch of a kernel sets its
  *     attributes) it may be recorded into a HIP graph and replayed.
  *   - Matrices are row-major.  ids are int32 row numbers of the datastore
- *     (N < 2^31); sizes are int64.
+ *     (N <= 2^31 - 512); sizes are int64.
  *   - The ranking is always (score descending, row id ascending): equal scores
  *     go to the lower id.  The paper does not define ties; this is this
  *     library's rule, at every stage.
