@@ -92,8 +92,10 @@ __device__ __forceinline__ f32x16 mfma32(const uint4 &a, const uint4 &b, const f
 __device__ __forceinline__ int64_t visited_tile(const ScanParams &p, int64_t t)
 {
     if (p.tile_skip) {
-        const int64_t g1 = p.tile_skip - 1;
-        t = (t / g1) * p.tile_skip + t % g1 + 1;
+        // tile counts fit 32 bits (N < 2^31 rows): a 32-bit division, not an emulated 64-bit one
+        const uint32_t g1 = (uint32_t)p.tile_skip - 1u, t32 = (uint32_t)t;
+        const uint32_t q = t32 / g1;
+        t = (int64_t)q * p.tile_skip + (t32 - q * g1) + 1;
     }
     return (p.tile_begin + t) * p.tile_stride;
 }
