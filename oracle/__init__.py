@@ -58,6 +58,9 @@ def _load():
         L.ralm_oracle_cache_lookup_metric.argtypes = [vp, vp, i32, i64, vp, vp, vp, ctypes.c_int, i64, i32, i64,
                                                       ctypes.c_int, vp, vp]
         L.ralm_oracle_cache_lookup_metric.restype = ctypes.c_int
+        L.ralm_oracle_cache_lookup_topk.argtypes = [vp, vp, i32, i64, vp, vp, vp, ctypes.c_int, i64, i32, i64,
+                                                    ctypes.c_int, i32, vp, vp]
+        L.ralm_oracle_cache_lookup_topk.restype = ctypes.c_int
         L.ralm_oracle_verify.argtypes = [vp, vp, i64, vp, i64, vp]
         L.ralm_oracle_verify.restype = None
         L.ralm_oracle_cache_insert.argtypes = [vp, vp, vp, i32, i64, vp, i64, vp, vp, i32, i32, i64]
@@ -257,3 +260,24 @@ def knnlm_probs(ids: np.ndarray, scores: np.ndarray, values: np.ndarray, tempera
 def os3_latency(samples) -> float:
     a = np.ascontiguousarray(samples, dtype=np.float64)
     return float(_load().ralm_oracle_os3_latency(_ptr(a), a.shape[0]))
+
+
+def cache_lookup_topk(cache_ids: np.ndarray, cache_len: np.ndarray, queries: np.ndarray, q_offsets: np.ndarray,
+                      X, k: int, metric: str = "ip") -> Tuple[np.ndarray, np.ndarray]:
+    """The k best cached entries of each query's request: (ids [Qt,k], scores [Qt,k]); -1 / -inf padding."""
+    Xa, tag = _store_any(X)
+    cache_ids = np.ascontiguousarray(cache_ids, dtype=np.int32)
+    cache_len = np.ascontiguousarray(cache_len, dtype=np.int32)
+    queries = np.ascontiguousarray(queries, dtype=np.float32)
+    q_offsets = np.ascontiguousarray(q_offsets, dtype=np.int64)
+    R, C = cache_ids.shape
+    N, d = Xa.shape
+    Qt = int(q_offsets[-1]) if R > 0 else 0
+    assert queries.shape == (Qt, d) and q_offsets.shape == (R + 1,)
+    ids = np.empty((Qt, k), dtype=np.int32)
+    sc = np.empty((Qt, k), dtype=np.float32)
+    rc = _load().ralm_oracle_cache_lookup_topk(_ptr(cache_ids), _ptr(cache_len), C, R, _ptr(queries), _ptr(q_offsets),
+                                               _ptr(Xa), tag, N, d, d, METRICS[metric], k, _ptr(ids), _ptr(sc))
+    if rc != 0:
+        raise ValueError("oracle cache_lookup_topk: bad arguments")
+    return ids, sc

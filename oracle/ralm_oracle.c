@@ -455,3 +455,45 @@ double ralm_oracle_os3_latency(const double *samples, int32_t n)
     for (int32_t i = 0; i < n; ++i) sum += samples[i];
     return sum / (double)n;
 }
+
+/*
+ * Speculative retrieval of k entries from the local cache (Section 5.3: for
+ * KNN-LM the distribution over next tokens is formed from the k retrieved
+ * entries, so the speculation step needs the k best CACHED entries, ranked
+ * with the retriever's own metric like every cache retrieval: Section 3,
+ * Fig. 2).  Per query: score every id the request has cached, sort all of them
+ * by (score descending, id ascending), output the first k; ranks beyond the
+ * number of cached ids get id -1 and score -inf.  Cached ids outside [0, N) are
+ * ignored.
+ */
+int ralm_oracle_cache_lookup_topk(const int32_t *cache_ids, const int32_t *cache_len, int32_t C,
+                                  int64_t R, const float *queries, const int64_t *q_offsets,
+                                  const void *X, int dtype, int64_t N, int32_t d, int64_t ld,
+                                  int metric, int32_t k, int32_t *out_ids, float *out_scores)
+{
+    if (R < 0 || C < 0 || d < 1 || ld < d || k < 1) return -1;
+    scored_t *ranked = (scored_t *)malloc((size_t)(C > 0 ? C : 1) * sizeof(scored_t));
+    if (!ranked) return -1;
+    for (int64_t r = 0; r < R; ++r) {
+        int32_t len = cache_len[r];
+        if (len < 0 || len > C) { free(ranked); return -1; }
+        for (int64_t i = q_offsets[r]; i < q_offsets[r + 1]; ++i) {
+            const float *q = queries + i * (int64_t)d;
+            int32_t n = 0;
+            for (int32_t e = 0; e < len; ++e) {
+                int32_t id = cache_ids[r * (int64_t)C + e];
+                if (id < 0 || id >= N) continue;
+                ranked[n].score = score_of(metric, q, X, dtype, id, ld, d);
+                ranked[n].id = id;
+                ++n;
+            }
+            qsort(ranked, (size_t)n, sizeof(scored_t), by_score_then_id);
+            for (int32_t j = 0; j < k; ++j) {
+                out_ids[i * k + j] = j < n ? ranked[j].id : -1;
+                out_scores[i * k + j] = j < n ? ranked[j].score : -INFINITY;
+            }
+        }
+    }
+    free(ranked);
+    return 0;
+}

@@ -615,3 +615,51 @@ def test_os3_latency_estimate_is_the_window_mean(oracle):
     rng = np.random.default_rng(2)
     x = rng.random(5) * 10
     assert oracle.os3_latency(x) == pytest.approx(float(np.mean(x)), rel=1e-15)
+
+
+# ----------------------------------------------------------------------------------------
+# k entries from the cache (KNN-LM speculation, Section 5.3)
+# ----------------------------------------------------------------------------------------
+def test_cache_lookup_topk_is_retrieval_on_the_cached_rows(oracle):
+    rng = np.random.default_rng(61)
+    X = rng.integers(-3, 4, size=(500, 8)).astype(np.float32)        # integer scores: ties occur
+    Qm = rng.integers(-3, 4, size=(7, 8)).astype(np.float32)
+    off = np.array([0, 3, 3, 7], dtype=np.int64)                      # the middle request has no query
+    cache = np.full((3, 40), -1, dtype=np.int32)
+    lens = np.array([40, 5, 12], dtype=np.int32)
+    for r in range(3):
+        cache[r, :lens[r]] = rng.choice(500, size=lens[r], replace=False)
+    cache[2, 3] = 900                                                 # an id outside the datastore is ignored
+    for metric in ("ip", "l2"):
+        for k in (1, 5, 12, 20):
+            ids, sc = oracle.cache_lookup_topk(cache, lens, Qm, off, X, k, metric)
+            for r in range(3):
+                valid = [int(v) for v in cache[r, :lens[r]] if 0 <= v < 500]
+                for qi in range(off[r], off[r + 1]):
+                    kk = min(k, len(valid))
+                    sub_ids, sub_sc = oracle.retrieve_topk(Qm[qi:qi + 1], X[valid], kk, metric)
+                    # the sub-matrix ranks ties by position; map back and re-rank ties by id
+                    want = sorted(((-float(oracle.scores(Qm[qi], X[[v]], metric)[0]), v) for v in valid))[:kk]
+                    assert ids[qi, :kk].tolist() == [v for _, v in want]
+                    assert sc[qi, :kk].tolist() == [-s for s, _ in want]
+                    assert sorted(sub_sc[0].tolist(), reverse=True) == sc[qi, :kk].tolist()
+                    assert np.all(ids[qi, kk:] == -1) and np.all(np.isneginf(sc[qi, kk:]))
+        # k = 1 is the speculative top-1
+        ids1, sc1 = oracle.cache_lookup_topk(cache, lens, Qm, off, X, 1, metric)
+        spec, ssc = oracle.cache_lookup(np.where((cache >= 0) & (cache < 500), cache, cache[:, :1]), lens, Qm, off, X, metric)
+        assert ids1[:, 0].tolist() == spec.tolist() and sc1[:, 0].tolist() == ssc.tolist()
+
+
+def test_cache_lookup_topk_rank_preservation(oracle):
+    """Section 3's property for k entries: if the knowledge base's k best are all cached, the cache
+    returns exactly them, in the same order."""
+    rng = np.random.default_rng(67)
+    X = rng.standard_normal((2000, 16)).astype(np.float32)
+    Qm = rng.standard_normal((4, 16)).astype(np.float32)
+    top, top_sc = oracle.retrieve_topk(Qm, X, 8)
+    off = np.arange(5, dtype=np.int64)
+    cache = np.stack([np.concatenate([top[q][::-1], rng.choice(2000, size=24, replace=False)]) for q in range(4)])
+    cache = np.stack([np.array(list(dict.fromkeys(row.tolist()))[:30] + [0] * 2)[:30] for row in cache]).astype(np.int32)
+    lens = np.full(4, 30, dtype=np.int32)
+    ids, sc = oracle.cache_lookup_topk(cache, lens, Qm, off, X, 8)
+    assert np.array_equal(ids, top) and np.array_equal(sc, top_sc)
