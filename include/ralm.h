@@ -243,6 +243,29 @@ ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Speculative retrieval of k entries from the local caches (Section 5.3: KNN-LM
+ * forms its next-token distribution from k retrieved entries, so its
+ * speculation step needs the k best CACHED entries; ranked with the
+ * retriever's own metric like every cache retrieval, Section 3 / Fig. 2).
+ * Arguments as ralm_cache_lookup, plus
+ *
+ *   k           1 <= k <= min(C, RALM_MAX_K); C <= RALM_MAX_K_PRIME
+ *   out_ids / out_scores  device [Qt, k], best first; ranks beyond the number
+ *               of (valid) cached ids get id -1 / score -inf, as do queries
+ *               that no request owns
+ *   workspace   device scratch, 256-byte aligned, at least
+ *               ralm_cache_lookup_topk_workspace_bytes(Qt, C)
+ *
+ * Cached ids must be distinct within a request (a repeated id is returned
+ * repeatedly).  Feeds ralm_knnlm_probs directly.
+ */
+size_t ralm_cache_lookup_topk_workspace_bytes(int64_t Qt, int32_t C);
+ralm_status ralm_cache_lookup_topk(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
+                                   const float *queries, int64_t Qt, const int64_t *q_offsets,
+                                   const ralm_datastore_t *ds, int32_t k, int32_t *out_ids,
+                                   float *out_scores, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Verification compare (Alg. 1: m = argmin_i d^_i != d_i).  For request r with
  * stride s_r = q_offsets[r+1] - q_offsets[r]:
  *   first_mismatch[r] = min { i in [0, s_r) : spec_ids[q_offsets[r] + i] !=

@@ -65,6 +65,9 @@ def lib() -> ctypes.CDLL:
         L.ralm_cache_lookup.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, vp, vp, vp, ctypes.c_size_t, vp]
         L.ralm_cache_lookup_workspace_bytes.argtypes = [i64]
         L.ralm_cache_lookup_workspace_bytes.restype = ctypes.c_size_t
+        L.ralm_cache_lookup_topk.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, i32, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ralm_cache_lookup_topk_workspace_bytes.argtypes = [i64, i32]
+        L.ralm_cache_lookup_topk_workspace_bytes.restype = ctypes.c_size_t
         L.ralm_verify.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp]
         L.ralm_cache_insert.argtypes = [vp, vp, vp, i32, i64, vp, i64, i64, vp, vp, i32, i32, i64, vp]
         L.ralm_knnlm_probs.argtypes = [vp, vp, i64, i32, vp, i64, ctypes.c_float, vp, vp, vp, vp, vp]
@@ -82,7 +85,7 @@ def lib() -> ctypes.CDLL:
         L.ralm_profile_enable.restype = None
         L.ralm_profile_scan_ms.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         for name in ("ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_retrieve_topk_seq", "ralm_workspace_overflows",
-                     "ralm_build_scan_copy", "ralm_build_scan_copy_l2", "ralm_cache_lookup", "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs",
+                     "ralm_build_scan_copy", "ralm_build_scan_copy_l2", "ralm_cache_lookup", "ralm_cache_lookup_topk", "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs",
                      "ralm_profile_scan_ms"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -240,6 +243,28 @@ def ralm_cache_lookup(cache_ids: torch.Tensor, cache_len: torch.Tensor, queries:
                                    q_offsets.data_ptr(), ctypes.byref(ds.desc), spec_ids.data_ptr(),
                                    spec_scores.data_ptr(), _ptr(workspace), ws_bytes, _stream()))
     return spec_ids, spec_scores
+
+
+def ralm_cache_lookup_topk(cache_ids: torch.Tensor, cache_len: torch.Tensor, queries: torch.Tensor,
+                           q_offsets: torch.Tensor, ds: Datastore, k: int,
+                           workspace: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """The k best cached entries per query: (ids [Qt, k] int32, scores [Qt, k] fp32)."""
+    assert cache_ids.dtype == torch.int32 and cache_len.dtype == torch.int32
+    assert q_offsets.dtype == torch.int64 and queries.dtype == torch.float32
+    assert cache_ids.is_contiguous() and queries.is_contiguous()
+    R, C = cache_ids.shape
+    Qt = queries.shape[0]
+    dev = queries.device
+    need = int(lib().ralm_cache_lookup_topk_workspace_bytes(Qt, C))
+    if workspace is None:
+        workspace = torch.empty(need + 256, dtype=torch.uint8, device=dev)
+    ws_ptr, ws_bytes = _ws_view(workspace)
+    out_ids = torch.empty(Qt, k, dtype=torch.int32, device=dev)
+    out_scores = torch.empty(Qt, k, dtype=torch.float32, device=dev)
+    _check(lib().ralm_cache_lookup_topk(cache_ids.data_ptr(), cache_len.data_ptr(), C, R, queries.data_ptr(), Qt,
+                                        q_offsets.data_ptr(), ctypes.byref(ds.desc), k, out_ids.data_ptr(),
+                                        out_scores.data_ptr(), ws_ptr, ws_bytes, _stream()))
+    return out_ids, out_scores
 
 
 def ralm_verify(spec_ids: torch.Tensor, true_ids: torch.Tensor, q_offsets: torch.Tensor,

@@ -247,6 +247,34 @@ __global__ __launch_bounds__(64) void cache_insert_kernel(
     }
 }
 
+// Candidate lists for the k-entry cache retrieval: every query of a request gets the request's
+// valid cached ids as ranking keys (score part 0), in any order; one workgroup per request.
+__global__ __launch_bounds__(256) void cache_keys_kernel(const int32_t *__restrict__ cache_ids,
+                                                         const int32_t *__restrict__ cache_len, int C, int64_t Qt,
+                                                         const int64_t *__restrict__ q_offsets, int64_t N,
+                                                         u64 *__restrict__ keys, uint32_t *__restrict__ cnt)
+{
+    __shared__ uint32_t s_n;
+    const int64_t r = blockIdx.x;
+    int64_t q_lo, q_hi;
+    clamp_range(q_offsets, r, Qt, q_lo, q_hi);
+    if (q_hi <= q_lo) return;
+    int len = cache_len[r];
+    len = len < 0 ? 0 : (len > C ? C : len);
+    if (threadIdx.x == 0) s_n = 0;
+    __syncthreads();
+    for (int x = threadIdx.x; x < len; x += 256) {
+        const int32_t id = cache_ids[r * (int64_t)C + x];
+        if (id >= 0 && (int64_t)id < N) {
+            const uint32_t at = atomicAdd(&s_n, 1u);
+            const u64 key = make_key(0.f, id);
+            for (int64_t q = q_lo; q < q_hi; ++q) keys[q * C + at] = key;
+        }
+    }
+    __syncthreads();
+    for (int64_t q = q_lo + threadIdx.x; q < q_hi; q += 256) cnt[q] = s_n;
+}
+
 __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
@@ -433,6 +461,16 @@ hipError_t launch_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *
     }
     hipLaunchKernelGGL(cache_insert_kernel, dim3((unsigned)R), dim3(64), smem, stream, cache_ids, cache_len,
                        cache_head, C, truth, true_stride, Qt, q_offsets, first_mismatch, p, n_next, N);
+    return hipGetLastError();
+}
+
+hipError_t launch_cache_keys(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R, int64_t Qt,
+                             const int64_t *q_offsets, int64_t N, u64 *keys, uint32_t *cnt, hipStream_t stream)
+{
+    hipError_t e = launch_fill_u32(cnt, 0u, Qt, stream);
+    if (e != hipSuccess || R <= 0) return e;
+    hipLaunchKernelGGL(cache_keys_kernel, dim3((unsigned)R), dim3(256), 0, stream, cache_ids, cache_len, C, Qt,
+                       q_offsets, N, keys, cnt);
     return hipGetLastError();
 }
 

@@ -451,6 +451,42 @@ ralm_status ralm_knnlm_probs(const int32_t *ids, const float *scores, int64_t Q,
     return RALM_OK;
 }
 
+size_t ralm_cache_lookup_topk_workspace_bytes(int64_t Qt, int32_t C)
+{
+    if (Qt < 0 || C < 1) return 0;
+    const size_t q = (size_t)(Qt > 0 ? Qt : 1);
+    return up256(q * (size_t)C * 8) + up256(q * 4);
+}
+
+ralm_status ralm_cache_lookup_topk(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
+                                   const float *queries, int64_t Qt, const int64_t *q_offsets,
+                                   const ralm_datastore_t *ds, int32_t k, int32_t *out_ids, float *out_scores,
+                                   void *workspace, size_t workspace_bytes, void *stream_)
+{
+    if (!cache_ids || !cache_len || !queries || !q_offsets || !out_ids || !out_scores)
+        return fail(RALM_ERR_NULL, "a pointer is NULL");
+    if (R < 0 || R > 0x7fffffffLL || C < 1 || C > RALM_MAX_K_PRIME)
+        return fail(RALM_ERR_SHAPE, "R=%lld, C=%d out of range (C <= %d)", (long long)R, C, RALM_MAX_K_PRIME);
+    if (Qt < 0 || Qt > (1 << 20)) return fail(RALM_ERR_RANGE, "Qt=%lld out of [0, 2^20]", (long long)Qt);
+    if (k < 1 || k > RALM_MAX_K || k > C) return fail(RALM_ERR_K, "k=%d must be in [1, min(C, %d)]", k, RALM_MAX_K);
+    ralm_status st = check_datastore(ds, false);
+    if (st != RALM_OK) return st;
+    if (!aligned16(queries)) return fail(RALM_ERR_ALIGN, "queries must be 16-byte aligned");
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) ||
+        workspace_bytes < ralm_cache_lookup_topk_workspace_bytes(Qt, C))
+        return fail(RALM_ERR_WORKSPACE, "workspace NULL, not 256-byte aligned or too small");
+    if (Qt == 0) return RALM_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    u64 *keys = static_cast<u64 *>(workspace);
+    uint32_t *cnt = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(workspace) + up256((size_t)Qt * C * 8));
+    RALM_HIP(launch_cache_keys(cache_ids, cache_len, C, R, Qt, q_offsets, ds->N, keys, cnt, stream));
+    // the cached rows are the candidates: exact scores, ranking and the first k, as after a scan
+    const int64_t ld = ds->exact_stride ? ds->exact_stride : ds->d;
+    RALM_HIP(launch_rescore(keys, cnt, (uint32_t)C, C, queries, Qt, ds->exact, ds->exact_dtype, ld, ds->d, ds->metric,
+                            k, out_ids, out_scores, nullptr, stream));
+    return RALM_OK;
+}
+
 ralm_status ralm_verify(const int32_t *spec_ids, const int32_t *true_ids, int64_t true_stride, int64_t Qt,
                         const int64_t *q_offsets, int64_t R, int32_t *first_mismatch, void *stream)
 {

@@ -74,6 +74,9 @@ hipError_t launch_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *
 hipError_t launch_knnlm_probs(const int32_t *ids, const float *scores, int64_t Q, int32_t k, const int32_t *values,
                               int64_t N, double T, int32_t *tokens, float *weights, int32_t *top_token,
                               float *top_prob, hipStream_t stream);
+// keys[q, 0..cnt[q]) = ranking keys (score 0) of the valid ids cached by the request that owns query q
+hipError_t launch_cache_keys(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R, int64_t Qt,
+                             const int64_t *q_offsets, int64_t N, u64 *keys, uint32_t *cnt, hipStream_t stream);
 hipError_t launch_verify(const int32_t *spec, const int32_t *truth, int64_t true_stride, int64_t Qt,
                          const int64_t *q_offsets, int64_t R, int32_t *first_mismatch,
                          hipStream_t stream);

@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported(L):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(ralm_[a-z0-9_]+)\s*\(", text))
     assert {"ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_retrieve_topk_seq", "ralm_cache_lookup",
-            "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs", "ralm_os3_stride",
+            "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs", "ralm_os3_stride", "ralm_cache_lookup_topk",
             "ralm_workspace_bytes", "ralm_build_scan_copy", "ralm_last_error"} <= names
     for n in names:
         assert hasattr(L, n), n
@@ -109,6 +109,14 @@ def test_argument_errors_return_status_without_a_device(L):
     assert kp(P, P, 4, 2000, P, 100, 1.0, P, P, P, P, None) == 3                  # k > max
     assert kp(P, P, 4, 8, P, 100, 0.0, P, P, P, P, None) == 7                     # temperature not positive
     assert kp(P, P, 4, 8, P, 0, 1.0, P, P, P, P, None) == 2                       # N < 1
+    tk = L.ralm_cache_lookup_topk
+    wsk = L.ralm_cache_lookup_topk_workspace_bytes(6, 64)
+    assert wsk >= 6 * 64 * 8 + 6 * 4 and L.ralm_cache_lookup_topk_workspace_bytes(6, 0) == 0
+    assert tk(P, P, 64, 2, P, 6, P, ref(ds), 8, None, P, P, wsk, None) == 1        # no output
+    assert tk(P, P, 5000, 2, P, 6, P, ref(ds), 8, P, P, P, 1 << 30, None) == 2     # C above the limit
+    assert tk(P, P, 64, 2, P, 6, P, ref(ds), 65, P, P, P, wsk, None) == 3          # k > C
+    assert tk(P, P, 64, 2, P, 6, P, ref(ds), 8, P, P, None, wsk, None) == 6        # no workspace
+    assert tk(P, P, 64, 2, P, 6, P, ref(ds), 8, P, P, P, wsk - 1, None) == 6       # too small
     assert L.ralm_verify(P, None, 1, 6, P, 2, P, None) == 1
     assert L.ralm_verify(P, P, 0, 6, P, 2, P, None) == 7
     assert L.ralm_verify(P, P, 1, 6, P, -1, P, None) == 2
