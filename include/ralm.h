@@ -119,13 +119,21 @@ typedef struct {
  *   out_ids    device int32 [Q, k]; out_scores device fp32 [Q, k]; each row
  *              ranked best first.
  *
- * Runs on the default stream, allocates and frees its own workspace, and
- * synchronises before returning.  If a candidate list overflows (see
+ * Runs on the default stream and synchronises before returning.  It uses
+ * buffers of its own: the workspace and, if the device has room, a bf16 copy of
+ * the datastore for the scan (N*d*2 bytes, rebuilt on every call).  They are
+ * kept between calls and grown on demand (allocating tens of gigabytes per
+ * call is slow); ralm_release_buffers() frees them.  Calls are serialised.
+ * Meant for convenience; a caller that retrieves repeatedly keeps a scan copy
+ * and uses the full form.  If a candidate list overflows (see
  * ralm_retrieve_topk_ex) the call is redone by ralm_retrieve_topk_seq, so the
  * result is exact for rows in any order.
  */
 ralm_status ralm_retrieve_topk(const float *queries, int64_t Q, const float *datastore, int64_t N,
                                int32_t d, int32_t k, int32_t *out_ids, float *out_scores);
+
+/* Frees the device buffers that ralm_retrieve_topk keeps between calls (synchronises). */
+void ralm_release_buffers(void);
 
 /* Bytes of workspace ralm_retrieve_topk_ex needs for (Q, ds, k, k_prime); 0 on bad arguments. */
 size_t ralm_workspace_bytes(int64_t Q, const ralm_datastore_t *ds, int32_t k, int32_t k_prime);

@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.ralm_os3_latency.restype = ctypes.c_double
         L.ralm_os3_next_stride.argtypes = [vp, vp, i32, vp, i32, vp, i32, ctypes.c_double, i32, i32]
         L.ralm_os3_next_stride.restype = i32
+        L.ralm_release_buffers.argtypes = []
+        L.ralm_release_buffers.restype = None
         L.ralm_profile_enable.argtypes = [i32]
         L.ralm_profile_enable.restype = None
         L.ralm_profile_scan_ms.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
@@ -218,6 +220,10 @@ def ralm_retrieve_topk(queries: torch.Tensor, datastore: torch.Tensor, k: int
     _check(lib().ralm_retrieve_topk(queries.data_ptr(), Q, datastore.data_ptr(), N, d, k,
                                     out_ids.data_ptr(), out_scores.data_ptr()))
     return out_ids, out_scores
+
+
+def ralm_release_buffers() -> None:
+    lib().ralm_release_buffers()
 
 
 def ralm_cache_lookup(cache_ids: torch.Tensor, cache_len: torch.Tensor, queries: torch.Tensor,

@@ -14,6 +14,7 @@
 //      a representative sample, so a stage admits only about k'*(g-1) scores per query.
 //   3. the k' keys left in each list are re-scored from the exact copy and ranked.
 #include <hip/hip_runtime.h>
+#include <mutex>
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -327,6 +328,45 @@ ralm_status ralm_workspace_overflows(const void *workspace, void *stream_, int32
     return RALM_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+// Buffers of the simple entry point, kept between calls and grown on demand: allocating and
+// freeing tens of gigabytes on every call is slow (and gets slower with repetition).
+std::mutex g_simple_mutex;
+void *g_simple_ws = nullptr, *g_simple_scan = nullptr;
+size_t g_simple_ws_bytes = 0, g_simple_scan_bytes = 0;
+
+// true if *buf holds at least `bytes` afterwards; on failure *buf is NULL
+bool simple_reserve(void **buf, size_t *have, size_t bytes)
+{
+    if (*buf && *have >= bytes) return true;
+    if (*buf) (void)hipFree(*buf);
+    *buf = nullptr;
+    *have = 0;
+    if (hipMalloc(buf, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        *buf = nullptr;
+        return false;
+    }
+    *have = bytes;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+void ralm_release_buffers(void)
+{
+    std::lock_guard<std::mutex> lock(g_simple_mutex);
+    if (g_simple_ws) (void)hipFree(g_simple_ws);
+    if (g_simple_scan) (void)hipFree(g_simple_scan);
+    g_simple_ws = g_simple_scan = nullptr;
+    g_simple_ws_bytes = g_simple_scan_bytes = 0;
+}
+
 ralm_status ralm_retrieve_topk(const float *queries, int64_t Q, const float *datastore, int64_t N, int32_t d,
                                int32_t k, int32_t *out_ids, float *out_scores)
 {
@@ -344,8 +384,19 @@ ralm_status ralm_retrieve_topk(const float *queries, int64_t Q, const float *dat
     Plan pl;
     st = make_plan(Q, &ds, k, 0, pl);
     if (st != RALM_OK) return st;
-    void *ws = nullptr;
-    RALM_HIP(hipMalloc(&ws, pl.total));
+    std::lock_guard<std::mutex> lock(g_simple_mutex);
+    if (!simple_reserve(&g_simple_ws, &g_simple_ws_bytes, pl.total))
+        return fail(RALM_ERR_DEVICE, "no device memory for %zu bytes of workspace", pl.total);
+    // Scanning fp32 rows directly reads twice the bytes through the slower staged kernel; a
+    // bf16 copy (one read, one write, redone on every call: the rows may have changed) pays for
+    // itself within the same call.  If the device has no room for it the rows are scanned as
+    // they are: same result either way, the staged kernel rounds to bf16 on the fly.
+    if (simple_reserve(&g_simple_scan, &g_simple_scan_bytes, (size_t)N * d * 2) &&
+        launch_convert_rows(datastore, d, g_simple_scan, RALM_BF16, d, N, d, nullptr) == hipSuccess) {
+        ds.scan = g_simple_scan;
+        ds.scan_dtype = RALM_BF16;
+    }
+    void *ws = g_simple_ws;
     st = ralm_retrieve_topk_ex(queries, Q, &ds, k, 0, out_ids, out_scores, nullptr, ws, pl.total, nullptr);
     int32_t overflows = 0;
     if (st == RALM_OK) st = ralm_workspace_overflows(ws, nullptr, &overflows);
@@ -354,8 +405,6 @@ ralm_status ralm_retrieve_topk(const float *queries, int64_t Q, const float *dat
         st = ralm_retrieve_topk_seq(queries, Q, &ds, k, 0, out_ids, out_scores, nullptr, ws, pl.total, nullptr);
         if (st == RALM_OK) st = ralm_workspace_overflows(ws, nullptr, &overflows);
     }
-    hipError_t e = hipFree(ws);
-    if (st == RALM_OK && e != hipSuccess) return fail(RALM_ERR_DEVICE, "hipFree failed: %s", hipGetErrorString(e));
     if (st == RALM_OK && overflows > 0)
         return fail(RALM_ERR_OVERFLOW, "%d queries overflowed their candidate buffers", overflows);
     return st;

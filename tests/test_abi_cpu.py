@@ -24,6 +24,7 @@ def test_every_declared_symbol_is_exported(L):
     names = set(re.findall(r"\b(ralm_[a-z0-9_]+)\s*\(", text))
     assert {"ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_retrieve_topk_seq", "ralm_cache_lookup",
             "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs", "ralm_os3_stride", "ralm_cache_lookup_topk",
+            "ralm_release_buffers",
             "ralm_workspace_bytes", "ralm_build_scan_copy", "ralm_last_error"} <= names
     for n in names:
         assert hasattr(L, n), n

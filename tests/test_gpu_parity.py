@@ -93,6 +93,15 @@ def test_simple_form_fp32_datastore(B, oracle):
     ids, sc = B.ralm_retrieve_topk(Qm.cuda(), X.cuda(), 5)
     wi, wsc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), 5)
     check_topk(ids.cpu().numpy(), sc.cpu().numpy(), wi, wsc, _score_fn(oracle, Qm.numpy(), X.numpy()))
+    # the buffers it keeps between calls can be handed back; the next call simply allocates again,
+    # also for a datastore of another size
+    B.ralm_release_buffers()
+    ids2, sc2 = B.ralm_retrieve_topk(Qm.cuda(), X.cuda(), 5)
+    assert torch.equal(ids, ids2) and torch.equal(sc, sc2)
+    ids3, _ = B.ralm_retrieve_topk(Qm.cuda(), X[:20000].contiguous().cuda(), 5)
+    wi3, _ = oracle.retrieve_topk(Qm.numpy(), X[:20000].numpy(), 5)
+    assert np.array_equal(ids3.cpu().numpy(), wi3)
+    B.ralm_release_buffers()
 
 
 def test_fp16_keys_are_the_truth_large_k(B, oracle):
