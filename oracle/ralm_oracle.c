@@ -386,9 +386,9 @@ double ralm_oracle_os3_gamma(const int32_t *strides, const int32_t *matched, int
 }
 
 /*
- * KNN-LM neighbour distribution (Section 5.3: "a distribution over these k
- * target tokens is computed based on their distance with respect to the current
- * context embedding").  Entry i of a query has retrieval score s_i (larger =
+ * KNN-LM neighbour distribution (Section 5.3: the k retrieved entries define a
+ * distribution over their target tokens through their distances to the context
+ * embedding).  Entry i of a query has retrieval score s_i (larger =
  * closer: the inner product, or minus the squared distance) and target token
  * values[ids_i].  Its weight is exp(s_i / T) / sum_j exp(s_j / T); the
  * probability of a token is the sum of the weights of the entries that carry
@@ -443,10 +443,10 @@ void ralm_oracle_knnlm_probs(const int32_t *ids, const float *scores, int64_t Q,
 }
 
 /*
- * Latencies a and b for OS^3 (Appendix A.2: "we directly estimate their value
- * with the profiling results from the most recent steps"; the number of steps
- * is not stated: the same window as for gamma is used): the arithmetic mean of
- * the samples, 0 when there is none.
+ * Latencies a and b for OS^3 (Appendix A.2 estimates them from the profiled
+ * latencies of recent steps; the number of steps is not stated: the same
+ * window as for gamma is used): the arithmetic mean of the samples, 0 when
+ * there is none.
  */
 double ralm_oracle_os3_latency(const double *samples, int32_t n)
 {

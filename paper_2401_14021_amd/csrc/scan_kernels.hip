@@ -149,16 +149,6 @@ __device__ __forceinline__ void select_epilogue_direct(const ScanParams &p, f32x
     }
 }
 
-#ifdef RALM_SCAN_TIMING
-// debug builds only: per-wave cycle totals {whole kernel, load waits, barriers, tile ends, stages}
-__device__ unsigned long long g_scan_timing[8];
-#define RALM_T0(var) const unsigned long long var = __builtin_amdgcn_s_memtime()
-#define RALM_TADD(acc, var) acc += __builtin_amdgcn_s_memtime() - var
-#else
-#define RALM_T0(var)
-#define RALM_TADD(acc, var)
-#endif
-
 // Parked epilogue (pipelined kernel).  Admitted scores are first parked in a small LDS list
 // (an LDS atomic is ~20x quicker than a global atomic round trip, which a lone wave per SIMD
 // cannot hide) and moved to the global lists in batches by flush_parked().  An entry that
@@ -441,10 +431,6 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     if (tid == 0) *pl.count = 0;
     if (tau_in_lds)
         for (int q = tid; q < p.Q; q += NT) tau_lds[q] = p.tau[q];
-#ifdef RALM_SCAN_TIMING
-    unsigned long long t_wait = 0, t_bar = 0, t_epi = 0;
-    RALM_T0(t_begin);
-#endif
 
     // ---- issue cursor: runs S-1 stages ahead of the multiply, also across tile boundaries ----
     // per-lane constants of the loads: tile row and swizzled chunk offset of each wave load
@@ -624,14 +610,10 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
                         // written by ds instructions that another wave reads without a later
                         // full barrier, so no LDS fence is needed; the asm statements keep the
                         // compiler from moving memory operations across the barrier.
-                        RALM_T0(tw);
                         wait_vmcnt<LPS *(S - 3)>();
-                        RALM_TADD(t_wait, tw);
-                        RALM_T0(tb);
                         asm volatile("" ::: "memory");
                         __builtin_amdgcn_s_barrier();
                         asm volatile("" ::: "memory");
-                        RALM_TADD(t_bar, tb);
                         issue_begin();
                     }
                     if (LAST && last_kk && m >= LAG && m - LAG < NM) {
@@ -682,7 +664,6 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
         }
 
         // tile end: every few tiles the parked entries move to the global lists
-        RALM_T0(te);
         const bool last_tile = it + 1 == n_mine;
         if ((it & 3) == 3 || last_tile) {
             __syncthreads();
@@ -695,7 +676,6 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
                 parked = held;
             }
         }
-        RALM_TADD(t_epi, te);
         cur_rt += step_rt;
         cur_qt += step_qt;
         if (cur_qt >= nqt) {
@@ -705,15 +685,6 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     }
     (void)parked;
     wait_vmcnt<0>();   // the run-ahead loads must land before this workgroup's LDS is released
-#ifdef RALM_SCAN_TIMING
-    if (lane == 0) {
-        atomicAdd(&g_scan_timing[0], __builtin_amdgcn_s_memtime() - t_begin);
-        atomicAdd(&g_scan_timing[1], t_wait);
-        atomicAdd(&g_scan_timing[2], t_bar);
-        atomicAdd(&g_scan_timing[3], t_epi);
-        atomicAdd(&g_scan_timing[4], (unsigned long long)(n_mine * KT));
-    }
-#endif
 }
 
 template <bool F16, int WM, int WN, int TM, int TN, int BK, int S>
@@ -801,19 +772,6 @@ int scan_bn_for(int64_t Q)
     if (Q <= 128) return 128;
     return 256;
 }
-
-#ifdef RALM_SCAN_TIMING
-extern "C" int ralm_debug_scan_timing(unsigned long long *out8, int reset)
-{
-    hipDeviceSynchronize();
-    if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_scan_timing), 64) != hipSuccess) return 1;
-    if (reset) {
-        unsigned long long z[8] = {0};
-        if (hipMemcpyToSymbol(HIP_SYMBOL(g_scan_timing), z, 64) != hipSuccess) return 1;
-    }
-    return 0;
-}
-#endif
 
 hipError_t launch_scan(const ScanParams &p, int n_cu, hipStream_t stream)
 {
