@@ -151,6 +151,9 @@ ralm_status check_datastore(const ralm_datastore_t *ds, bool need_scan)
         if (ss < sd) return fail(RALM_ERR_SHAPE, "scan_stride < d (+ 8 norm columns for the squared-distance metric)");
         if (!aligned16(ds->scan) || (ss * elem_bytes(ds->scan_dtype)) % 16)
             return fail(RALM_ERR_ALIGN, "scan copy: base and row pitch must be multiples of 16 bytes");
+        // the pipelined scan forms per-lane byte offsets (row in tile) * pitch with a 24-bit multiply
+        if (ss * elem_bytes(ds->scan_dtype) >= (1 << 24))
+            return fail(RALM_ERR_SHAPE, "scan_stride: row pitch of the scan copy must be below 16 MiB");
     }
     return RALM_OK;
 }
@@ -210,6 +213,10 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
     Plan pl;
     st = make_plan(Q, ds, k, k_prime, pl);
     if (st != RALM_OK) return st;
+    // the scan kernels count (row tile, query tile) work items in 32 bits
+    if (((ds->N + SCAN_BM - 1) / SCAN_BM) * 2 * ((Q + 31) / 32) > 0x7fffffffLL)
+        return fail(RALM_ERR_SHAPE, "Q=%lld x N=%lld: more than 2^31 tile pairs in one call; split the batch",
+                    (long long)Q, (long long)ds->N);
     if (!workspace) return fail(RALM_ERR_WORKSPACE, "workspace is NULL");
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(RALM_ERR_WORKSPACE, "workspace must be 256-byte aligned");
     if (workspace_bytes < pl.total)

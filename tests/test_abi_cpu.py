@@ -60,6 +60,13 @@ def test_argument_errors_return_status_without_a_device(L):
     assert call(P, 8, ref(ds), 5, 0, P, P, None, None, ws, None) == 6            # no workspace
     assert call(P, 8, ref(ds), 5, 0, P, P, None, P + 16, ws, None) == 6          # misaligned workspace
     assert call(P, 8, ref(ds), 5, 0, P, P, None, P, ws - 1, None) == 6           # too small
+    wide = _ds(b)
+    wide.scan_stride = 1 << 23                                                   # 16 MiB row pitch
+    assert call(P, 8, ref(wide), 5, 0, P, P, None, P, 1 << 30, None) == 2
+    assert b"pitch" in L.ralm_last_error()
+    huge = _ds(b, N=2_000_000_000)
+    assert call(P, 1 << 20, ref(huge), 5, 0, P, P, None, P, 1 << 62, None) == 2  # too many tile pairs
+    assert b"split the batch" in L.ralm_last_error()
     l2 = _ds(b)
     l2.metric = 1
     l2.scan_stride = 770
