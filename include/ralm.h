@@ -251,6 +251,24 @@ ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * ralm_cache_lookup for callers that can neither allocate device memory nor
+ * pass a workspace: code recorded under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  Same arguments and same results as
+ * ralm_cache_lookup called with a workspace; the merge slots (8 bytes per
+ * query) live in an array inside the library instead, 512 KiB per GPU, held
+ * until the process ends.  Limit: Qt <= 65536 (RALM_ERR_RANGE beyond it).  The
+ * call allocates nothing and only launches kernels (the slots are cleared by a
+ * kernel).  All calls on one GPU share that array: two calls that overlap in
+ * time on the same GPU (different streams or threads) race; calls ordered on
+ * one stream are fine.
+ */
+#define RALM_STATIC_LOOKUP_MAX_QT 65536
+ralm_status ralm_cache_lookup_static(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
+                                     const float *queries, int64_t Qt, const int64_t *q_offsets,
+                                     const ralm_datastore_t *ds, int32_t *spec_ids, float *spec_scores,
+                                     void *stream);
+
+/*
  * Speculative retrieval of k entries from the local caches (Section 5.3: KNN-LM
  * forms its next-token distribution from k retrieved entries, so its
  * speculation step needs the k best CACHED entries; ranked with the
@@ -367,8 +385,8 @@ ralm_status ralm_knnlm_probs(const int32_t *ids, const float *scores, int64_t Q,
  * ralm_os3_stride: the s in [1, s_max] with the largest objective; the
  *   smallest such s on ties.
  * ralm_os3_latency: a (or b) as the mean of the n most recent measurements
- *   (the paper takes "the profiling results from the most recent steps"
- *   without saying how many); 0 for n <= 0.
+ *   (Appendix A.2 estimates both from recent profiling and fixes no window
+ *   length); 0 for n <= 0.
  * ralm_os3_next_stride: the stride for the next round from a request's history:
  *   gamma^ from (strides, matched, w), a and b from their samples, then
  *   ralm_os3_stride.  1 while any of the three histories is empty (the paper

@@ -63,6 +63,7 @@ def lib() -> ctypes.CDLL:
         L.ralm_build_scan_copy.argtypes = [vp, i64, vp, i32, i64, i64, i32, vp]
         L.ralm_build_scan_copy_l2.argtypes = [vp, i32, i64, vp, i32, i64, i64, i32, vp]
         L.ralm_cache_lookup.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ralm_cache_lookup_static.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, vp, vp, vp]
         L.ralm_cache_lookup_workspace_bytes.argtypes = [i64]
         L.ralm_cache_lookup_workspace_bytes.restype = ctypes.c_size_t
         L.ralm_cache_lookup_topk.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, i32, vp, vp, vp, ctypes.c_size_t, vp]
@@ -87,7 +88,8 @@ def lib() -> ctypes.CDLL:
         L.ralm_profile_enable.restype = None
         L.ralm_profile_scan_ms.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         for name in ("ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_retrieve_topk_seq", "ralm_workspace_overflows",
-                     "ralm_build_scan_copy", "ralm_build_scan_copy_l2", "ralm_cache_lookup", "ralm_cache_lookup_topk", "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs",
+                     "ralm_build_scan_copy", "ralm_build_scan_copy_l2", "ralm_cache_lookup", "ralm_cache_lookup_static",
+                     "ralm_cache_lookup_topk", "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs",
                      "ralm_profile_scan_ms"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -248,6 +250,22 @@ def ralm_cache_lookup(cache_ids: torch.Tensor, cache_len: torch.Tensor, queries:
     _check(lib().ralm_cache_lookup(cache_ids.data_ptr(), cache_len.data_ptr(), C, R, queries.data_ptr(), Qt,
                                    q_offsets.data_ptr(), ctypes.byref(ds.desc), spec_ids.data_ptr(),
                                    spec_scores.data_ptr(), _ptr(workspace), ws_bytes, _stream()))
+    return spec_ids, spec_scores
+
+
+def ralm_cache_lookup_static(cache_ids: torch.Tensor, cache_len: torch.Tensor, queries: torch.Tensor,
+                             q_offsets: torch.Tensor, ds: Datastore, spec_ids: torch.Tensor,
+                             spec_scores: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
+    """ralm_cache_lookup with the library's built-in scratch: the caller passes inputs and outputs only."""
+    assert cache_ids.dtype == torch.int32 and cache_len.dtype == torch.int32
+    assert q_offsets.dtype == torch.int64 and queries.dtype == torch.float32
+    assert cache_ids.is_contiguous() and queries.is_contiguous()
+    assert spec_ids.dtype == torch.int32 and spec_scores.dtype == torch.float32
+    R, C = cache_ids.shape
+    Qt = queries.shape[0]
+    _check(lib().ralm_cache_lookup_static(cache_ids.data_ptr(), cache_len.data_ptr(), C, R, queries.data_ptr(), Qt,
+                                          q_offsets.data_ptr(), ctypes.byref(ds.desc), spec_ids.data_ptr(),
+                                          spec_scores.data_ptr(), _stream()))
     return spec_ids, spec_scores
 
 

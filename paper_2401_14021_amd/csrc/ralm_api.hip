@@ -451,12 +451,14 @@ ralm_status ralm_build_scan_copy_l2(const void *src, int32_t src_dtype, int64_t 
     return RALM_OK;
 }
 
-size_t ralm_cache_lookup_workspace_bytes(int64_t Qt) { return Qt < 0 ? 0 : up256((size_t)(Qt > 0 ? Qt : 1) * 8); }
+}  // extern "C"
 
-ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
-                              const float *queries, int64_t Qt, const int64_t *q_offsets,
-                              const ralm_datastore_t *ds, int32_t *spec_ids, float *spec_scores, void *workspace,
-                              size_t workspace_bytes, void *stream)
+namespace {
+
+// argument checks shared by the two forms of the cache lookup (host only)
+ralm_status check_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
+                               const float *queries, int64_t Qt, const int64_t *q_offsets,
+                               const ralm_datastore_t *ds, const int32_t *spec_ids, const float *spec_scores)
 {
     if (!cache_ids || !cache_len || !queries || !q_offsets || !spec_ids || !spec_scores)
         return fail(RALM_ERR_NULL, "a pointer is NULL");
@@ -466,6 +468,22 @@ ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len
     if (st != RALM_OK) return st;
     if (ds->d > 2048) return fail(RALM_ERR_SHAPE, "cache lookup supports d <= 2048");
     if (!aligned16(queries)) return fail(RALM_ERR_ALIGN, "queries must be 16-byte aligned");
+    return RALM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ralm_cache_lookup_workspace_bytes(int64_t Qt) { return Qt < 0 ? 0 : up256((size_t)(Qt > 0 ? Qt : 1) * 8); }
+
+ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
+                              const float *queries, int64_t Qt, const int64_t *q_offsets,
+                              const ralm_datastore_t *ds, int32_t *spec_ids, float *spec_scores, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    ralm_status st = check_cache_lookup(cache_ids, cache_len, C, R, queries, Qt, q_offsets, ds, spec_ids, spec_scores);
+    if (st != RALM_OK) return st;
     if (workspace && ((reinterpret_cast<uintptr_t>(workspace) & 7u) || workspace_bytes < (size_t)Qt * 8))
         return fail(RALM_ERR_WORKSPACE, "workspace must be 8-byte aligned and hold 8 bytes per query");
     const int64_t ld = ds->exact_stride ? ds->exact_stride : ds->d;
@@ -473,6 +491,59 @@ ralm_status ralm_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len
                                  ds->N, ds->d, ds->metric, spec_ids, spec_scores, static_cast<u64 *>(workspace),
                                  static_cast<hipStream_t>(stream)));
     return RALM_OK;
+}
+
+}  // extern "C"
+
+// Scratch of ralm_cache_lookup_static: one merge slot (8 bytes) per query, held by every GPU the
+// library runs on until the process ends.  In host code the array's name is only a stand-in for
+// the symbol; the device address is looked up once per device and used from then on.
+constexpr int64_t STATIC_LOOKUP_MAX_QT = 65536;
+static __device__ __align__(256) unsigned long long scratch[STATIC_LOOKUP_MAX_QT];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+
+// device address of `scratch` on the current device (looked up on the first call per device)
+ralm_status static_scratch(void **out)
+{
+    int dev = -1;
+    RALM_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(RALM_ERR_DEVICE, "device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        RALM_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(RALM_ERR_DEVICE, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return RALM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ralm_status ralm_cache_lookup_static(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
+                                     const float *queries, int64_t Qt, const int64_t *q_offsets,
+                                     const ralm_datastore_t *ds, int32_t *spec_ids, float *spec_scores,
+                                     void *stream)
+{
+    // every argument error is reported before the device is touched
+    ralm_status st = check_cache_lookup(cache_ids, cache_len, C, R, queries, Qt, q_offsets, ds, spec_ids, spec_scores);
+    if (st != RALM_OK) return st;
+    if (Qt > STATIC_LOOKUP_MAX_QT)
+        return fail(RALM_ERR_RANGE, "Qt=%lld exceeds the %lld queries the built-in scratch holds; use "
+                    "ralm_cache_lookup with a workspace", (long long)Qt, (long long)STATIC_LOOKUP_MAX_QT);
+    void *ptr = nullptr;
+    st = static_scratch(&ptr);
+    if (st != RALM_OK) return st;
+    return ralm_cache_lookup(cache_ids, cache_len, C, R, queries, Qt, q_offsets, ds, spec_ids, spec_scores, ptr,
+                             (size_t)STATIC_LOOKUP_MAX_QT * 8, stream);
 }
 
 ralm_status ralm_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *cache_head, int32_t C, int64_t R,

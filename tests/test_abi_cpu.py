@@ -24,6 +24,7 @@ def test_every_declared_symbol_is_exported(L):
     names = set(re.findall(r"\b(ralm_[a-z0-9_]+)\s*\(", text))
     assert {"ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_retrieve_topk_seq", "ralm_cache_lookup",
             "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs", "ralm_os3_stride", "ralm_cache_lookup_topk",
+            "ralm_cache_lookup_static",
             "ralm_release_buffers",
             "ralm_workspace_bytes", "ralm_build_scan_copy", "ralm_last_error"} <= names
     for n in names:
@@ -101,6 +102,10 @@ def test_argument_errors_return_status_without_a_device(L):
     assert L.ralm_cache_lookup(P, P, 4, 2, P, -1, P, ref(ds), P, P, None, 0, None) == 7
     assert L.ralm_cache_lookup(P, P, 4, 2, P, 6, P, ref(ds), P, P, P, 40, None) == 6     # 8 bytes per query needed
     assert L.ralm_cache_lookup(P, P, 4, 2, P, 6, P, ref(ds), P, P, P + 4, 64, None) == 6 # misaligned scratch
+    st = L.ralm_cache_lookup_static
+    assert st(P, None, 4, 2, P, 6, P, ref(ds), P, P, None) == 1                   # argument errors come first,
+    assert st(P, P, 0, 2, P, 6, P, ref(ds), P, P, None) == 2                      # before any device call
+    assert st(P, P, 4, 2, P, 65537, P, ref(ds), P, P, None) == 7                  # beyond the built-in scratch
     assert L.ralm_cache_lookup_workspace_bytes(6) >= 48 and L.ralm_cache_lookup_workspace_bytes(-1) == 0
     ins = L.ralm_cache_insert
     assert ins(P, P, None, 4, 2, P, 5, 6, P, None, 1, 0, 1000, None) == 1         # no head array
