@@ -23,7 +23,8 @@
  *   - Calls enqueue work on the given HIP stream (a hipStream_t passed as
  *     void*; NULL = the default stream) and return without synchronising,
  *     except where stated.  Work of one call is ordered on that stream.
- *     Apart from ralm_retrieve_topk and ralm_workspace_overflows, a call only
+ *     Apart from ralm_retrieve_topk, ralm_workspace_overflows and
+ *     ralm_workspace_counters, a call only
  *     launches kernels (no allocation, no memset or copy nodes), so after one
  *     ordinary call of the same shapes (the first launch of a kernel sets its
  *     attributes) it may be recorded into a HIP graph and replayed.
@@ -146,14 +147,31 @@ size_t ralm_workspace_bytes(int64_t Q, const ralm_datastore_t *ds, int32_t k, in
  * are returned.  k_prime = 0 picks a default (64 for k <= 32, else the power
  * of two >= 2k).
  *
+ * That answer is the exact one unless the scan's rounding pushed a true top-k
+ * row out of the k' kept ones.  The library checks this per query, on the
+ * device: the margin (see out_margin) must exceed 8x the root mean square of
+ * the differences between scan score and exact score seen on the query's own k'
+ * candidates (when all of those differences are zero, a margin of zero is
+ * enough).  A query that fails the check, or whose candidate list lost entries
+ * (below), is answered again in the same call by an exact pass: every row of
+ * the exact copy is scored exactly (the arithmetic of the final scores) and the
+ * best k of the rows that reach the exact rank-k score found so far are
+ * returned, which is the exact top k by construction.  The pass is skipped
+ * when no query needs it; it reads the exact copy once per 8 such queries
+ * (about 10 ms per 8 queries for 21M x 768 fp32).  With k_prime = k there is
+ * no margin to speak of and nearly every query takes that pass.
+ * ralm_workspace_counters reports how many did.
+ *
  *   queries     device fp32 [Q, d] (host code never reads it)
  *   ds          HOST struct of device pointers
  *   out_ids / out_scores  device [Q, k] as above
  *   out_margin  optional device fp32 [Q] (may be NULL): exact score of the
- *               returned rank-k row minus the scan score of the k'-th kept
- *               candidate (brought to the same scale under RALM_METRIC_L2).  A positive margin larger than the scan's rounding
- *               error proves that no row outside the candidates can belong in
- *               the top k.
+ *               rank-k row among the candidates minus the scan score of the
+ *               k'-th kept candidate (brought to the same scale under
+ *               RALM_METRIC_L2).  A row outside the candidates can belong in
+ *               the top k only if the scan mis-scored it by at least this
+ *               much.  Diagnostic: the library acts on it by itself (above).
+ *               +inf when every row was a candidate (N < k').
  *   workspace   device scratch, 256-byte aligned, >= ralm_workspace_bytes();
  *               contents are undefined between calls; two calls that overlap
  *               in time must not share it.
@@ -164,9 +182,12 @@ size_t ralm_workspace_bytes(int64_t Q, const ralm_datastore_t *ds, int32_t k, in
  * scores that beat the k'-th best of the rows visited before.  Does not
  * synchronise.  If the list of some query overflows (only when the order of
  * the rows is correlated with that stride pattern, e.g. every other 256-row
- * tile holding the best matches), that query's outputs are set to id -1 /
- * score NaN and the overflow is counted; read it with
- * ralm_workspace_overflows() and redo the call with ralm_retrieve_topk_seq.
+ * tile holding the best matches), the list keeps what it has, the scan goes
+ * on, and the query is answered by the exact pass, whose list holds only rows
+ * that reach the exact rank-k score of the candidates that survived.  Only if
+ * that list overflows too (more than 16384 rows tie with or beat that score)
+ * are the query's outputs set to id -1 / score NaN; ralm_workspace_overflows()
+ * counts those, and ralm_retrieve_topk_seq answers them.
  */
 ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_datastore_t *ds,
                                   int32_t k, int32_t k_prime, int32_t *out_ids, float *out_scores,
@@ -187,10 +208,32 @@ ralm_status ralm_retrieve_topk_seq(const float *queries, int64_t Q, const ralm_d
 
 /*
  * Number of queries of the LAST ralm_retrieve_topk_ex / _seq call on this workspace
- * whose candidate buffer overflowed.  Synchronises `stream` and copies one
- * int to the host (*count is a host pointer).
+ * that were left unanswered (id -1 / score NaN).  Synchronises `stream` and
+ * copies one int to the host (*count is a host pointer).
  */
 ralm_status ralm_workspace_overflows(const void *workspace, void *stream, int32_t *count);
+
+/*
+ * Counters of the LAST ralm_retrieve_topk_ex / _seq call on this workspace, all
+ * numbers of queries (host struct; synchronises `stream`):
+ *   unanswered        id -1 / score NaN (what ralm_workspace_overflows returns)
+ *   ladder_overflows  candidate list lost entries during the scan; answered by
+ *                     the exact pass
+ *   hard_certified    margin above the deterministic bound of the scan's
+ *                     rounding, (u_q + u_x + u_q u_x) |q| |x| + d 2^-24 |q| |x|
+ *                     with unit roundoffs u = 2^-8 (bf16) or 2^-11 (fp16) of the
+ *                     query and of the rows (0 for rows scanned as they are) and
+ *                     |x| the longest of the query's candidates: a proof when
+ *                     no row is longer than that, e.g. for unit-norm rows
+ *   soft_certified    passed the check described at ralm_retrieve_topk_ex
+ *                     (includes hard_certified)
+ *   exact_pass        answered by the exact pass
+ * soft_certified + exact_pass = Q.
+ */
+typedef struct {
+    int32_t unanswered, ladder_overflows, hard_certified, soft_certified, exact_pass;
+} ralm_counters_t;
+ralm_status ralm_workspace_counters(const void *workspace, void *stream, ralm_counters_t *out);
 
 /*
  * Build the low-precision scan copy of a datastore: dst[j, c] = round-to-

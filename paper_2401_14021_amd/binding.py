@@ -33,6 +33,12 @@ class ralm_datastore_t(ctypes.Structure):
                 ("metric", ctypes.c_int32)]
 
 
+class ralm_counters_t(ctypes.Structure):
+    _fields_ = [("unanswered", ctypes.c_int32), ("ladder_overflows", ctypes.c_int32),
+                ("hard_certified", ctypes.c_int32), ("soft_certified", ctypes.c_int32),
+                ("exact_pass", ctypes.c_int32)]
+
+
 class RalmError(RuntimeError):
     def __init__(self, status: int, text: str):
         super().__init__(f"{STATUS.get(status, status)}: {text}")
@@ -60,6 +66,7 @@ def lib() -> ctypes.CDLL:
         L.ralm_retrieve_topk_ex.argtypes = [vp, i64, dsp, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.ralm_retrieve_topk_seq.argtypes = L.ralm_retrieve_topk_ex.argtypes
         L.ralm_workspace_overflows.argtypes = [vp, vp, ctypes.POINTER(i32)]
+        L.ralm_workspace_counters.argtypes = [vp, vp, ctypes.POINTER(ralm_counters_t)]
         L.ralm_build_scan_copy.argtypes = [vp, i64, vp, i32, i64, i64, i32, vp]
         L.ralm_build_scan_copy_l2.argtypes = [vp, i32, i64, vp, i32, i64, i64, i32, vp]
         L.ralm_cache_lookup.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -88,6 +95,7 @@ def lib() -> ctypes.CDLL:
         L.ralm_profile_enable.restype = None
         L.ralm_profile_scan_ms.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         for name in ("ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_retrieve_topk_seq", "ralm_workspace_overflows",
+                     "ralm_workspace_counters",
                      "ralm_build_scan_copy", "ralm_build_scan_copy_l2", "ralm_cache_lookup", "ralm_cache_lookup_static",
                      "ralm_cache_lookup_topk", "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs",
                      "ralm_profile_scan_ms"):
@@ -207,6 +215,14 @@ def ralm_workspace_overflows(workspace: torch.Tensor) -> int:
     c = ctypes.c_int32(0)
     _check(lib().ralm_workspace_overflows(ws_ptr, _stream(), ctypes.byref(c)))
     return int(c.value)
+
+
+def ralm_workspace_counters(workspace: torch.Tensor) -> dict:
+    """Counters of the last retrieval call on this workspace (numbers of queries)."""
+    ws_ptr, _ = _ws_view(workspace)
+    c = ralm_counters_t()
+    _check(lib().ralm_workspace_counters(ws_ptr, _stream(), ctypes.byref(c)))
+    return {name: int(getattr(c, name)) for name, _ in ralm_counters_t._fields_}
 
 
 def ralm_retrieve_topk(queries: torch.Tensor, datastore: torch.Tensor, k: int

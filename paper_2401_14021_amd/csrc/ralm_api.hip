@@ -58,7 +58,7 @@ struct Plan {
     int n_stages;
     int64_t stride[40];   // tile stride of each stage, first = coarsest, last = 1
     // workspace offsets
-    size_t off_q, off_tau, off_cnt, off_flags, off_cand, off_sel, total;
+    size_t off_q, off_tau, off_cnt, off_lost, off_fb, off_flags, off_cand, off_sel, total;
 };
 
 // columns of a scan-copy row: the squared-distance metric keeps the row's squared norm behind it
@@ -113,10 +113,12 @@ ralm_status make_plan(int64_t Q, const ralm_datastore_t *ds, int32_t k, int32_t 
     for (int i = 0; i < n; ++i) pl.stride[i] = rev[n - 1 - i];
 
     size_t off = 0;
-    pl.off_flags = off;  off += 256;   // always first: word 0 = overflowed queries of the last call
+    pl.off_flags = off;  off += 256;   // always first: the counters of the last call (FLAG_*)
     pl.off_q = off;      off += up256((size_t)pl.Qpad * pl.dpad * 2);
     pl.off_tau = off;    off += up256((size_t)pl.Qpad * 8);
     pl.off_cnt = off;    off += up256((size_t)pl.Qpad * 4);
+    pl.off_lost = off;   off += up256((size_t)pl.Qpad * 4);   // directly behind cnt: cleared together
+    pl.off_fb = off;     off += up256((size_t)pl.Qpad * 4);
     pl.off_cand = off;   off += up256((size_t)Q * pl.cap * 8);
     pl.off_sel = off;    off += up256((size_t)Q * k_prime * 8);   // scratch of the select kernel
     pl.total = off;
@@ -227,6 +229,8 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
     uint16_t *qs = reinterpret_cast<uint16_t *>(ws + pl.off_q);
     u64 *tau = reinterpret_cast<u64 *>(ws + pl.off_tau);
     uint32_t *cnt = reinterpret_cast<uint32_t *>(ws + pl.off_cnt);
+    uint32_t *lost = reinterpret_cast<uint32_t *>(ws + pl.off_lost);
+    int32_t *fb_list = reinterpret_cast<int32_t *>(ws + pl.off_fb);
     int32_t *flags = reinterpret_cast<int32_t *>(ws + pl.off_flags);
     u64 *cand = reinterpret_cast<u64 *>(ws + pl.off_cand);
     u64 *sel = reinterpret_cast<u64 *>(ws + pl.off_sel);
@@ -241,7 +245,7 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
     RALM_HIP(launch_query_prep(queries, Q, ds->d, qs, pl.Qpad, pl.dpad, mma_dt, ds->metric, stream));
     RALM_HIP(launch_fill_u64(tau, 0ull, pl.Qpad, stream));
     RALM_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(flags), 0u, 64, stream));
-    RALM_HIP(launch_fill_u32(cnt, 0u, pl.Qpad, stream));
+    RALM_HIP(launch_fill_u32(cnt, 0u, (int64_t)(pl.off_fb - pl.off_cnt) / 4, stream));   // cnt and lost
 
     ScanParams sp;
     sp.X = scan; sp.ldx = scan_ld; sp.N = ds->N; sp.d = scan_cols(ds); sp.in_dtype = scan_dt;
@@ -264,7 +268,7 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
             RALM_HIP(hipEventRecord(g_prof_ev[g_prof_n][1], stream));
             ++g_prof_n;
         }
-        RALM_HIP(launch_select(cand, cnt, pl.cap, pl.k_prime, Q, tau, sel, flags, stream));
+        RALM_HIP(launch_select(cand, cnt, pl.cap, pl.k_prime, Q, tau, sel, lost, flags, stream));
         return RALM_OK;
     };
 
@@ -301,8 +305,22 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
         }
     }
     const int64_t exact_ld = ds->exact_stride ? ds->exact_stride : ds->d;
+    // The re-score checks each query's result against the scan's rounding; the queries that fail
+    // (and those whose list lost entries) are answered again by an exact pass over the exact copy.
+    // tau is free by now and takes the exact rank-k keys.
+    CertifyParams cert;
+    cert.flags = flags;
+    cert.lost = lost;
+    cert.cnt_rw = cnt;
+    cert.tau_exact = tau;
+    cert.fb_list = fb_list;
+    const float u = mma_dt == RALM_F16 ? 1.f / 2048.f : 1.f / 256.f;   // 11 / 8 significant bits
+    cert.u_query = u;
+    cert.u_rows = (scan == ds->exact && scan_dt == ds->exact_dtype && scan_dt != RALM_F32) ? 0.f : u;
     RALM_HIP(launch_rescore(cand, cnt, pl.cap, pl.k_prime, queries, Q, ds->exact, ds->exact_dtype, exact_ld, ds->d,
-                            ds->metric, k, out_ids, out_scores, out_margin, stream));
+                            ds->metric, k, out_ids, out_scores, out_margin, cert, stream));
+    RALM_HIP(launch_exact_pass(queries, Q, ds->exact, ds->exact_dtype, exact_ld, ds->N, ds->d, ds->metric, k, fb_list,
+                               flags, tau, cand, cnt, pl.cap, out_ids, out_scores, n_cu, stream));
     return RALM_OK;
 }
 
@@ -331,7 +349,23 @@ ralm_status ralm_workspace_overflows(const void *workspace, void *stream_, int32
     if (!workspace || !count) return fail(RALM_ERR_NULL, "workspace/count is NULL");
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     RALM_HIP(hipStreamSynchronize(stream));
-    RALM_HIP(hipMemcpy(count, workspace, sizeof(int32_t), hipMemcpyDeviceToHost));
+    RALM_HIP(hipMemcpy(count, static_cast<const int32_t *>(workspace) + FLAG_UNANSWERED, sizeof(int32_t),
+                       hipMemcpyDeviceToHost));
+    return RALM_OK;
+}
+
+ralm_status ralm_workspace_counters(const void *workspace, void *stream_, ralm_counters_t *out)
+{
+    if (!workspace || !out) return fail(RALM_ERR_NULL, "workspace/out is NULL");
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    int32_t words[8];
+    RALM_HIP(hipStreamSynchronize(stream));
+    RALM_HIP(hipMemcpy(words, workspace, sizeof(words), hipMemcpyDeviceToHost));
+    out->unanswered = words[FLAG_UNANSWERED];
+    out->ladder_overflows = words[FLAG_LADDER_OVERFLOWS];
+    out->hard_certified = words[FLAG_HARD_CERTIFIED];
+    out->soft_certified = words[FLAG_SOFT_CERTIFIED];
+    out->exact_pass = words[FLAG_FALLBACKS];
     return RALM_OK;
 }
 
@@ -609,8 +643,10 @@ ralm_status ralm_cache_lookup_topk(const int32_t *cache_ids, const int32_t *cach
     RALM_HIP(launch_cache_keys(cache_ids, cache_len, C, R, Qt, q_offsets, ds->N, keys, cnt, stream));
     // the cached rows are the candidates: exact scores, ranking and the first k, as after a scan
     const int64_t ld = ds->exact_stride ? ds->exact_stride : ds->d;
+    CertifyParams no_check;
+    memset(&no_check, 0, sizeof(no_check));
     RALM_HIP(launch_rescore(keys, cnt, (uint32_t)C, C, queries, Qt, ds->exact, ds->exact_dtype, ld, ds->d, ds->metric,
-                            k, out_ids, out_scores, nullptr, stream));
+                            k, out_ids, out_scores, nullptr, no_check, stream));
     return RALM_OK;
 }
 

@@ -48,17 +48,46 @@ hipError_t launch_l2_scan_copy(const void *src, int32_t src_dtype, int64_t src_l
 hipError_t launch_convert_rows(const float *src, int64_t src_ld, void *dst, int32_t dst_dtype,
                                int64_t dst_ld, int64_t N, int32_t d, hipStream_t stream);
 
+// Words of a retrieval call's flag block (first 256 bytes of its workspace), all counts of queries.
+enum {
+    FLAG_UNANSWERED = 0,        // answered with id -1 / score NaN
+    FLAG_LADDER_OVERFLOWS = 1,  // candidate list lost entries during the scan (answered by the exact pass)
+    FLAG_HARD_CERTIFIED = 2,    // margin above the deterministic rounding bound
+    FLAG_SOFT_CERTIFIED = 3,    // margin above 8x the rounding spread seen on the candidates (includes the above)
+    FLAG_FALLBACKS = 4          // answered by the exact pass
+};
+
+// What the re-score needs to check its own result and to queue a query for the exact pass; all
+// pointers NULL: no check (flags == NULL decides).
+struct CertifyParams {
+    int32_t *flags;        // flag block
+    const uint32_t *lost;  // [Q] != 0: the query's list lost entries during the scan
+    uint32_t *cnt_rw;      // [Q] list lengths, reset for queued queries
+    u64 *tau_exact;        // [Q] out: exact rank-k key of the queued query
+    int32_t *fb_list;      // [Q] out: queued queries
+    float u_query, u_rows; // unit roundoff applied by the scan to the query / to the rows (0: not rounded)
+};
+
 // per query: k'-th best key of cand[q, 0..cnt[q]) -> tau[q]; the list is then cut down, in place,
 // to its k' best keys (cnt[q] <- min(cnt[q], k')).  tmp is scratch of [Q, k'] keys.  A list
-// that overflowed its cap slots gets cnt[q] = 0xffffffff, tau[q] = ~0 and is counted once.
+// that was sent more than cap keys holds the first cap of them: lost[q] is set and the query
+// counted once in flags[FLAG_LADDER_OVERFLOWS].
 hipError_t launch_select(u64 *cand, uint32_t *cnt, uint32_t cap, int32_t k_prime, int64_t Q, u64 *tau,
-                         u64 *tmp, int32_t *overflow_count, hipStream_t stream);
+                         u64 *tmp, uint32_t *lost, int32_t *flags, hipStream_t stream);
 
-// per query: exact scores of the (at most k') rows left in its list, final ranking, top k out
+// per query: exact scores of the (at most k') rows left in its list, final ranking, top k out;
+// with cert.flags: the result is checked and queries that fail are queued for launch_exact_pass
 hipError_t launch_rescore(const u64 *cand, const uint32_t *cnt, uint32_t cap, int32_t k_prime,
                           const float *queries, int64_t Q, const void *exact, int32_t exact_dtype, int64_t ld,
                           int32_t d, int32_t metric, int32_t k, int32_t *out_ids, float *out_scores,
-                          float *out_margin, hipStream_t stream);
+                          float *out_margin, const CertifyParams &cert, hipStream_t stream);
+
+// exact scan + final ranking for the queries queued by the re-score (two launches that return at
+// once when none is queued)
+hipError_t launch_exact_pass(const float *queries, int64_t Q, const void *exact, int32_t exact_dtype, int64_t ld,
+                             int64_t N, int32_t d, int32_t metric, int32_t k, const int32_t *fb_list, int32_t *flags,
+                             const u64 *tau_exact, u64 *cand, uint32_t *cnt, uint32_t cap, int32_t *out_ids,
+                             float *out_scores, int n_cu, hipStream_t stream);
 
 hipError_t launch_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
                                const float *queries, int64_t Qt, const int64_t *q_offsets,

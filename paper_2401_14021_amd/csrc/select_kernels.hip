@@ -7,7 +7,17 @@
 //                  the EXACT datastore copy, products and sum in double, one rounding to
 //                  fp32; final ranking (score descending, id ascending); first k written.
 //                  This is what makes the result that of the paper's exact dense retriever
-//                  (Section 5.1) although the scan ran in bf16/fp16.
+//                  (Section 5.1) although the scan ran in bf16/fp16.  It also checks that
+//                  result: the gap between the exact rank-k score and the scan's score of the
+//                  worst kept candidate must exceed what the scan's rounding can do to a
+//                  score (judged from the rounding errors seen on the candidates themselves);
+//                  a query that fails the check, or whose list lost entries, is queued for
+//  exact_scan_kernel / exact_finish_kernel: every row of the exact copy is scored exactly
+//                  against the queued queries, the rows that reach the query's exact rank-k
+//                  key are collected, and the best k of them are the answer.  Both kernels
+//                  are always launched and return at once when nothing is queued.
+#include <atomic>
+
 #include "ralm_common.h"
 #include "ralm_kernels.h"
 
@@ -17,48 +27,31 @@ namespace {
 
 constexpr int SEL_THREADS = 1024;
 
-// Exact k'-th best key of a list by a radix descent, 8 bits of the key per pass, from the top.
-// A pass histograms the digit of the keys that match the prefix found so far; wave 0 walks the
-// 256 bins from the best digit down to the one that holds the k'-th key.  As soon as that bin
-// holds a single key the descent stops and one more pass over the list fetches that key
-// (scores are mostly distinct, so this usually happens before the id bits are reached).
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(u64 *__restrict__ cand, uint32_t *__restrict__ cnt,
-                                                             uint32_t cap, int k_prime, u64 *__restrict__ tau,
-                                                             u64 *__restrict__ tmp,
-                                                             int32_t *__restrict__ overflow_count)
+// Exact rank-th best (1-based) key of c[0, n), n >= rank >= 1, by a radix descent over the 64-bit
+// ranking key, 8 bits per pass from the top.  A pass histograms the digit of the keys that match
+// the prefix found so far; wave 0 walks the 256 bins from the best digit down to the one that
+// holds the wanted key.  As soon as that bin holds a single key the descent stops and one more
+// pass over the list fetches that key (scores are mostly distinct, so this usually happens
+// before the id bits are reached).  Called by all SEL_THREADS threads of a workgroup; keys must
+// be distinct.
+struct RadixShared {
+    uint32_t hist[256];
+    uint32_t digit, remaining, bin;
+    u64 kth;
+};
+
+__device__ u64 radix_kth(const u64 *__restrict__ c, uint32_t n, uint32_t rank, RadixShared &sh)
 {
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t s_digit, s_remaining, s_bin, s_out;
-    __shared__ u64 s_kth;
-
-    const int64_t q = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
-    const uint32_t n = cnt[q];
-    u64 *c = cand + q * (int64_t)cap;
-
-    if (n == 0xffffffffu) return;   // flagged by an earlier stage
-    if (n > cap) {                  // list overflowed: this query cannot be answered from it
-        if (tid == 0) {
-            tau[q] = ~0ull;         // admits nothing from now on
-            cnt[q] = 0xffffffffu;
-            atomicAdd(overflow_count, 1);
-        }
-        return;
-    }
-    if (n < (uint32_t)k_prime) {    // fewer than k' candidates exist so far: keep admitting everything
-        if (tid == 0) tau[q] = 0ull;
-        return;
-    }
-
     u64 prefix = 0, mask = 0;
-    uint32_t remaining = (uint32_t)k_prime;
+    uint32_t remaining = rank;
     bool single = false;
     for (int shift = 56; shift >= 0; shift -= 8) {
-        if (tid < 256) hist[tid] = 0;
+        if (tid < 256) sh.hist[tid] = 0;
         __syncthreads();
         for (uint32_t i = tid; i < n; i += SEL_THREADS) {
             const u64 key = c[i];
-            if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
+            if ((key & mask) == prefix) atomicAdd(&sh.hist[(uint32_t)(key >> shift) & 255u], 1u);
         }
         __syncthreads();
         if (tid < 64) {
@@ -66,7 +59,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(u64 *__restrict__ c
             uint32_t h[4], tot = 0;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                h[j] = hist[255 - 4 * lane - j];
+                h[j] = sh.hist[255 - 4 * lane - j];
                 tot += h[j];
             }
             uint32_t incl = tot;
@@ -79,31 +72,69 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(u64 *__restrict__ c
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if (run < remaining && run + h[j] >= remaining) {
-                    s_digit = 255 - 4 * lane - j;
-                    s_remaining = remaining - run;
-                    s_bin = h[j];
+                    sh.digit = 255 - 4 * lane - j;
+                    sh.remaining = remaining - run;
+                    sh.bin = h[j];
                 }
                 run += h[j];
             }
         }
         __syncthreads();
-        prefix |= (u64)s_digit << shift;
+        prefix |= (u64)sh.digit << shift;
         mask |= 0xffull << shift;
-        remaining = s_remaining;
-        if (s_bin == 1) {
+        remaining = sh.remaining;
+        if (sh.bin == 1) {
             single = shift > 0;
             break;
         }
     }
     u64 kth = prefix;
-    if (single) {   // the only key under the prefix is the k'-th
+    if (single) {   // the only key under the prefix is the wanted one
         for (uint32_t i = tid; i < n; i += SEL_THREADS) {
             const u64 key = c[i];
-            if ((key & mask) == prefix) s_kth = key;
+            if ((key & mask) == prefix) sh.kth = key;
         }
         __syncthreads();
-        kth = s_kth;
+        kth = sh.kth;
     }
+    __syncthreads();   // sh may be reused by the caller's next call
+    return kth;
+}
+
+// Per query: the k'-th best key of its list becomes the admission key of the next scan stage
+// and the list is cut down to its k' best keys in place.  A list that was sent more keys than
+// it has slots kept only the first `cap` of them: it is processed as it is (its k'-th best key
+// is still a valid lower bound, the rows behind those keys were all scanned) and the query is
+// marked in `lost`, so that it is answered by the exact pass at the end of the call.
+__global__ __launch_bounds__(SEL_THREADS) void select_kernel(u64 *__restrict__ cand, uint32_t *__restrict__ cnt,
+                                                             uint32_t cap, int k_prime, u64 *__restrict__ tau,
+                                                             u64 *__restrict__ tmp, uint32_t *__restrict__ lost,
+                                                             int32_t *__restrict__ flags)
+{
+    __shared__ RadixShared sh;
+    __shared__ uint32_t s_out;
+
+    const int64_t q = blockIdx.x;
+    const int tid = threadIdx.x;
+    uint32_t n = cnt[q];
+    u64 *c = cand + q * (int64_t)cap;
+
+    if (n > cap) {
+        n = cap;
+        if (tid == 0) {
+            if (lost[q] == 0) atomicAdd(flags + FLAG_LADDER_OVERFLOWS, 1);
+            lost[q] = 1;
+        }
+    }
+    if (n < (uint32_t)k_prime) {    // fewer than k' candidates exist so far: keep admitting everything
+        if (tid == 0) {
+            tau[q] = 0ull;
+            cnt[q] = n;
+        }
+        return;
+    }
+
+    const u64 kth = radix_kth(c, n, (uint32_t)k_prime, sh);
     // keys are distinct: exactly k' of them are >= kth
 
     // cut the list down to those k' keys, in place (via tmp)
@@ -132,10 +163,47 @@ __device__ __forceinline__ double wave_sum(double x)
     return x;
 }
 
+// The exact score, as every kernel of the library forms it: lane l of a wave takes the
+// elements 4l .. 4l+3, 256+4l .., adds their products (squared differences) to its sum in that
+// order, and the 64 lane sums are added by a butterfly (wave_sum).  Products and sums in double;
+// the caller rounds the total once to fp32.
+template <bool L2>
+__device__ __forceinline__ void exact_accum4(double &sum, const float4 &x, const float4 &y)
+{
+    if constexpr (L2) {
+        const double d0 = (double)y.x - (double)x.x, d1 = (double)y.y - (double)x.y;
+        const double d2 = (double)y.z - (double)x.z, d3 = (double)y.w - (double)x.w;
+        sum += d0 * d0;
+        sum += d1 * d1;
+        sum += d2 * d2;
+        sum += d3 * d3;
+    } else {
+        sum += (double)x.x * (double)y.x;
+        sum += (double)x.y * (double)y.y;
+        sum += (double)x.z * (double)y.z;
+        sum += (double)x.w * (double)y.w;
+    }
+}
+
+// elements j .. j+3 of a row of the exact copy, widened exactly to fp32
+template <int EX>
+__device__ __forceinline__ float4 exact_load4(const void *__restrict__ exact, int64_t row_off, int j)
+{
+    if constexpr (EX == DT_F32) {
+        return *reinterpret_cast<const float4 *>(static_cast<const float *>(exact) + row_off + j);
+    } else {
+        const uint2 h = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(exact) + row_off + j);
+        return make_float4(f16_bits_to_f32(h.x & 0xffffu), f16_bits_to_f32(h.x >> 16), f16_bits_to_f32(h.y & 0xffffu),
+                           f16_bits_to_f32(h.y >> 16));
+    }
+}
+
 constexpr int RS_THREADS = 1024, RS_WAVES = RS_THREADS / 64;
 
+// Re-score of the candidates, final ranking, and the check of the result (see CertifyParams).
 // EX: DT_F32 or DT_F16 exact rows.  L2: the score is minus the squared distance; the scan's
-// score of a row is then 2<q, x> - |x|^2, so |q|^2 is subtracted from it for the margin.
+// score of a row is then 2<q, x> - |x|^2, so |q|^2 is subtracted from it wherever the two are
+// compared.
 template <int EX, bool L2>
 __global__ __launch_bounds__(RS_THREADS) void rescore_kernel(const u64 *__restrict__ cand,
                                                       const uint32_t *__restrict__ cnt, uint32_t cap,
@@ -143,73 +211,67 @@ __global__ __launch_bounds__(RS_THREADS) void rescore_kernel(const u64 *__restri
                                                       const void *__restrict__ exact, int64_t ld, int d,
                                                       int k, int32_t *__restrict__ out_ids,
                                                       float *__restrict__ out_scores,
-                                                      float *__restrict__ out_margin)
+                                                      float *__restrict__ out_margin, const CertifyParams cert)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     u64 *keys = reinterpret_cast<u64 *>(smem);   // [kp2]
     __shared__ u64 s_min_scan[RS_WAVES];
+    __shared__ double s_e2[RS_WAVES], s_x2[RS_WAVES], s_q2[RS_WAVES];
 
     const int64_t q = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t n_raw = cnt[q];
-    const bool overflow = n_raw == 0xffffffffu;
-    const int n = overflow ? 0 : (int)(n_raw < (uint32_t)k_prime ? n_raw : (uint32_t)k_prime);
+    const int n = (int)(n_raw < (uint32_t)k_prime ? n_raw : (uint32_t)k_prime);
     const u64 *mine = cand + q * (int64_t)cap;
     const float *qv = queries + q * (int64_t)d;
+    const bool stats = out_margin || cert.flags;   // wave-uniform
+
+    // |q|^2: part of the scan's score under L2, and of the rounding bound
+    double q2 = 0.0;
+    if (stats) {
+        for (int j = tid; j < d; j += RS_THREADS) q2 += (double)qv[j] * (double)qv[j];
+        q2 = wave_sum(q2);
+        if (lane == 0) s_q2[wave] = q2;
+    }
+    __syncthreads();
+    if (stats) {
+        q2 = 0.0;
+        for (int w = 0; w < RS_WAVES; ++w) q2 += s_q2[w];
+    }
+    const float q_sq = L2 ? (float)q2 : 0.f;
 
     u64 min_scan = ~0ull;
+    double e2 = 0.0, x2max = 0.0;   // sum of squared scan errors, largest squared row norm (lane 0)
     for (int c = wave; c < n; c += RS_WAVES) {
         const u64 skey = mine[c];
         min_scan = skey < min_scan ? skey : min_scan;
         const int32_t id = key_id(skey);
-        double sum = 0.0;
-        if constexpr (EX == DT_F32) {
-            const float *row = static_cast<const float *>(exact) + (int64_t)id * ld;
-            for (int j = lane * 4; j < d; j += 256) {
-                const float4 x = *reinterpret_cast<const float4 *>(row + j);
-                const float4 y = *reinterpret_cast<const float4 *>(qv + j);
-                if constexpr (L2) {
-                    const double d0 = (double)y.x - (double)x.x, d1 = (double)y.y - (double)x.y;
-                    const double d2 = (double)y.z - (double)x.z, d3 = (double)y.w - (double)x.w;
-                    sum += d0 * d0;
-                    sum += d1 * d1;
-                    sum += d2 * d2;
-                    sum += d3 * d3;
-                } else {
-                    sum += (double)x.x * (double)y.x;
-                    sum += (double)x.y * (double)y.y;
-                    sum += (double)x.z * (double)y.z;
-                    sum += (double)x.w * (double)y.w;
-                }
-            }
-        } else {
-            const uint16_t *row = static_cast<const uint16_t *>(exact) + (int64_t)id * ld;
-            for (int j = lane * 8; j < d; j += 512) {
-                const uint4 x = *reinterpret_cast<const uint4 *>(row + j);
-                const float4 y0 = *reinterpret_cast<const float4 *>(qv + j);
-                const float4 y1 = *reinterpret_cast<const float4 *>(qv + j + 4);
-                const double xs[8] = {(double)f16_bits_to_f32(x.x & 0xffffu), (double)f16_bits_to_f32(x.x >> 16),
-                                      (double)f16_bits_to_f32(x.y & 0xffffu), (double)f16_bits_to_f32(x.y >> 16),
-                                      (double)f16_bits_to_f32(x.z & 0xffffu), (double)f16_bits_to_f32(x.z >> 16),
-                                      (double)f16_bits_to_f32(x.w & 0xffffu), (double)f16_bits_to_f32(x.w >> 16)};
-                const double ys[8] = {(double)y0.x, (double)y0.y, (double)y0.z, (double)y0.w,
-                                      (double)y1.x, (double)y1.y, (double)y1.z, (double)y1.w};
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    if constexpr (L2) {
-                        const double df = ys[u] - xs[u];
-                        sum += df * df;
-                    } else {
-                        sum += xs[u] * ys[u];
-                    }
-                }
-            }
+        const int64_t row_off = (int64_t)id * ld;
+        double sum = 0.0, x2 = 0.0;
+        for (int j = lane * 4; j < d; j += 256) {
+            const float4 x = exact_load4<EX>(exact, row_off, j);
+            const float4 y = *reinterpret_cast<const float4 *>(qv + j);
+            exact_accum4<L2>(sum, x, y);
+            if (stats)
+                x2 += (double)x.x * (double)x.x + (double)x.y * (double)x.y + (double)x.z * (double)x.z +
+                      (double)x.w * (double)x.w;
         }
         sum = wave_sum(sum);
-        if (lane == 0) keys[c] = make_key(L2 ? (float)(-sum) : (float)sum, id);
+        const float score = L2 ? (float)(-sum) : (float)sum;
+        if (stats) {
+            x2 = wave_sum(x2);
+            const double e = (double)(key_score(skey) - q_sq) - (double)score;
+            e2 += e * e;
+            x2max = x2 > x2max ? x2 : x2max;
+        }
+        if (lane == 0) keys[c] = make_key(score, id);
     }
     for (int c = n + tid; c < kp2; c += RS_THREADS) keys[c] = 0ull;
-    if (lane == 0) s_min_scan[wave] = min_scan;
+    if (lane == 0) {
+        s_min_scan[wave] = min_scan;
+        s_e2[wave] = e2;
+        s_x2[wave] = x2max;
+    }
     __syncthreads();
 
     // bitonic sort, descending by key
@@ -233,42 +295,209 @@ __global__ __launch_bounds__(RS_THREADS) void rescore_kernel(const u64 *__restri
         const u64 key = keys[r];
         const bool have = r < n;
         out_ids[q * k + r] = have ? key_id(key) : -1;
-        out_scores[q * k + r] = have ? key_score(key) : (overflow ? __builtin_nanf("") : -__builtin_inff());
+        out_scores[q * k + r] = have ? key_score(key) : -__builtin_inff();
     }
-    if (out_margin && tid == 0) {
-        float q_sq = 0.f;
-        if constexpr (L2) {
-            double t = 0.0;
-            for (int j = 0; j < d; ++j) t += (double)qv[j] * (double)qv[j];
-            q_sq = (float)t;
-        }
+    if (stats && tid == 0) {
         u64 ms = s_min_scan[0];
-        for (int w = 1; w < RS_WAVES; ++w) ms = s_min_scan[w] < ms ? s_min_scan[w] : ms;
+        double se2 = s_e2[0], x2m = s_x2[0];
+        for (int w = 1; w < RS_WAVES; ++w) {
+            ms = s_min_scan[w] < ms ? s_min_scan[w] : ms;
+            se2 += s_e2[w];
+            x2m = s_x2[w] > x2m ? s_x2[w] : x2m;
+        }
+        // margin: exact score at rank k minus the scan's score of the worst kept candidate.  A row
+        // that was not kept has a scan score at most the latter, so it can belong in the top k only
+        // if the scan mis-scored it by at least the margin.
         float margin;
-        if (overflow || n < k)
+        if (n < k)
             margin = __builtin_nanf("");
         else if (n < k_prime)
             margin = __builtin_inff();   // every row of the datastore was re-scored
         else
             margin = key_score(keys[k - 1]) - (key_score(ms) - q_sq);
-        out_margin[q] = margin;
+        if (out_margin) out_margin[q] = margin;
+        if (cert.flags) {
+            // what the scan's rounding can do to a score: the deterministic bound (every rounding
+            // error aligned; rows outside the candidates are taken to be no longer than the longest
+            // candidate), and the spread actually seen on this query's candidates
+            const double qn = sqrt(q2), xn = sqrt(x2m);
+            const double uq = cert.u_query, ux = cert.u_rows;
+            double hard = (uq + ux + uq * ux) * qn * xn + (double)d * 5.9604644775390625e-08 * qn * xn;
+            if (L2) hard = 2.0 * hard + (ux * ux + (double)d * 5.9604644775390625e-08) * x2m;
+            const double soft = n > 0 ? 8.0 * sqrt(se2 / (double)n) : 0.0;
+            const bool truncated = cert.lost && cert.lost[q] != 0;
+            const bool all_rows = n < k_prime && !truncated;
+            const double m = (double)margin;
+            const bool soft_ok = all_rows || (!truncated && n >= k && (m > soft || (soft == 0.0 && m >= 0.0)));
+            if (soft_ok) {
+                atomicAdd(cert.flags + FLAG_SOFT_CERTIFIED, 1);
+                if (all_rows || m > hard) atomicAdd(cert.flags + FLAG_HARD_CERTIFIED, 1);
+            } else if (n >= k) {
+                // answered again by the exact pass: every row whose exact key reaches the exact
+                // rank-k key found here (a lower bound of the true one) is collected in the list
+                const int at = atomicAdd(cert.flags + FLAG_FALLBACKS, 1);
+                cert.fb_list[at] = (int32_t)q;
+                cert.tau_exact[q] = keys[k - 1];
+                cert.cnt_rw[q] = 0u;
+            }
+        }
+    }
+}
+
+// ---- exact pass for the queries whose scan result could not be trusted -------------------------
+// All rows of the exact copy are scored exactly against up to QG of those queries at a time and
+// every row whose exact key reaches the query's bound is appended to the query's list.  The
+// arithmetic is that of the re-score (same order of the sums), so a row gets the same number.
+constexpr int XS_THREADS = 256, XS_WAVES = XS_THREADS / 64, XS_QG = 8;
+
+template <int EX, bool L2>
+__global__ __launch_bounds__(XS_THREADS) void exact_scan_kernel(const float *__restrict__ queries,
+                                                                const void *__restrict__ exact, int64_t ld,
+                                                                int64_t N, int d, int qgroup,
+                                                                const int32_t *__restrict__ fb_list,
+                                                                const int32_t *__restrict__ flags,
+                                                                const u64 *__restrict__ tau_exact,
+                                                                u64 *__restrict__ cand, uint32_t *__restrict__ cnt,
+                                                                uint32_t cap)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *qs = reinterpret_cast<float *>(smem);   // [qgroup][d]
+    __shared__ u64 s_tau[XS_QG];
+    __shared__ int32_t s_q[XS_QG];
+
+    const int F = flags[FLAG_FALLBACKS];
+    if (F <= 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t wave0 = (int64_t)blockIdx.x * XS_WAVES + wave, n_waves = (int64_t)gridDim.x * XS_WAVES;
+
+    for (int g0 = 0; g0 < F; g0 += qgroup) {
+        const int nq = F - g0 < qgroup ? F - g0 : qgroup;
+        __syncthreads();
+        if (tid < nq) {
+            const int32_t q = fb_list[g0 + tid];
+            s_q[tid] = q;
+            s_tau[tid] = tau_exact[q];
+        }
+        __syncthreads();
+        for (int qi = 0; qi < nq; ++qi) {
+            const float *src = queries + (int64_t)s_q[qi] * d;
+            for (int j = tid * 4; j < d; j += XS_THREADS * 4)
+                *reinterpret_cast<float4 *>(qs + (size_t)qi * d + j) = *reinterpret_cast<const float4 *>(src + j);
+        }
+        __syncthreads();
+
+        for (int64_t row = wave0; row < N; row += n_waves) {
+            const int64_t row_off = row * ld;
+            double sum[XS_QG];
+#pragma unroll
+            for (int qi = 0; qi < XS_QG; ++qi) sum[qi] = 0.0;
+            for (int j = lane * 4; j < d; j += 256) {
+                const float4 x = exact_load4<EX>(exact, row_off, j);
+#pragma unroll
+                for (int qi = 0; qi < XS_QG; ++qi) {
+                    if (qi < nq) {   // wave-uniform
+                        const float4 y = *reinterpret_cast<const float4 *>(qs + (size_t)qi * d + j);
+                        exact_accum4<L2>(sum[qi], x, y);
+                    }
+                }
+            }
+#pragma unroll
+            for (int qi = 0; qi < XS_QG; ++qi) {
+                if (qi < nq) {
+                    const double t = wave_sum(sum[qi]);
+                    if (lane == 0) {
+                        const u64 key = make_key(L2 ? (float)(-t) : (float)t, (int32_t)row);
+                        if (key >= s_tau[qi]) {
+                            const int32_t q = s_q[qi];
+                            const uint32_t at = atomicAdd(cnt + q, 1u);
+                            if (at < cap) cand[(int64_t)q * cap + at] = key;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Final ranking of an exact-pass query: the k best keys of its list, sorted, written out.
+__global__ __launch_bounds__(SEL_THREADS) void exact_finish_kernel(const u64 *__restrict__ cand,
+                                                                   const uint32_t *__restrict__ cnt, uint32_t cap,
+                                                                   int k, int kp2, const int32_t *__restrict__ fb_list,
+                                                                   int32_t *__restrict__ flags,
+                                                                   int32_t *__restrict__ out_ids,
+                                                                   float *__restrict__ out_scores)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    u64 *keys = reinterpret_cast<u64 *>(smem);   // [kp2]
+    __shared__ RadixShared sh;
+    __shared__ uint32_t s_out;
+
+    const int F = flags[FLAG_FALLBACKS];
+    const int tid = threadIdx.x;
+    for (int i = blockIdx.x; i < F; i += gridDim.x) {
+        const int64_t q = fb_list[i];
+        const uint32_t n = cnt[q];
+        const u64 *c = cand + q * (int64_t)cap;
+        __syncthreads();
+        if (n > cap || n < (uint32_t)k) {
+            // more rows reach the bound than a list holds (n < k cannot happen: the k rows that
+            // defined the bound reach it): this query stays unanswered and is counted
+            for (int r = tid; r < k; r += SEL_THREADS) {
+                out_ids[q * k + r] = -1;
+                out_scores[q * k + r] = __builtin_nanf("");
+            }
+            if (tid == 0) atomicAdd(flags + FLAG_UNANSWERED, 1);
+            continue;
+        }
+        const u64 kth = radix_kth(c, n, (uint32_t)k, sh);
+        if (tid == 0) s_out = 0;
+        for (int r = tid; r < kp2; r += SEL_THREADS) keys[r] = 0ull;
+        __syncthreads();
+        for (uint32_t e = tid; e < n; e += SEL_THREADS) {
+            const u64 key = c[e];
+            if (key >= kth) {
+                const uint32_t at = atomicAdd(&s_out, 1u);
+                if (at < (uint32_t)kp2) keys[at] = key;
+            }
+        }
+        __syncthreads();
+        for (int size = 2; size <= kp2; size <<= 1) {
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                for (int t = tid; t < kp2 / 2; t += SEL_THREADS) {
+                    const int lo = 2 * t - (t & (stride - 1));
+                    const int hi = lo + stride;
+                    const bool desc = (lo & size) == 0;
+                    const u64 a = keys[lo], b = keys[hi];
+                    if ((a < b) == desc) {
+                        keys[lo] = b;
+                        keys[hi] = a;
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        for (int r = tid; r < k; r += SEL_THREADS) {
+            out_ids[q * k + r] = key_id(keys[r]);
+            out_scores[q * k + r] = key_score(keys[r]);
+        }
     }
 }
 
 }  // namespace
 
 hipError_t launch_select(u64 *cand, uint32_t *cnt, uint32_t cap, int32_t k_prime, int64_t Q, u64 *tau, u64 *tmp,
-                         int32_t *overflow_count, hipStream_t stream)
+                         uint32_t *lost, int32_t *flags, hipStream_t stream)
 {
     if (Q <= 0) return hipSuccess;
     hipLaunchKernelGGL(select_kernel, dim3((unsigned)Q), dim3(SEL_THREADS), 0, stream, cand, cnt, cap, k_prime, tau, tmp,
-                       overflow_count);
+                       lost, flags);
     return hipGetLastError();
 }
 
 hipError_t launch_rescore(const u64 *cand, const uint32_t *cnt, uint32_t cap, int32_t k_prime, const float *queries,
                           int64_t Q, const void *exact, int32_t exact_dtype, int64_t ld, int32_t d, int32_t metric,
-                          int32_t k, int32_t *out_ids, float *out_scores, float *out_margin, hipStream_t stream)
+                          int32_t k, int32_t *out_ids, float *out_scores, float *out_margin,
+                          const CertifyParams &cert, hipStream_t stream)
 {
     if (Q <= 0) return hipSuccess;
     int kp2 = 2;
@@ -276,7 +505,7 @@ hipError_t launch_rescore(const u64 *cand, const uint32_t *cnt, uint32_t cap, in
     const size_t smem = (size_t)kp2 * sizeof(u64);
 #define RALM_RS(EXV, L2V)                                                                                    \
     hipLaunchKernelGGL((rescore_kernel<EXV, L2V>), dim3((unsigned)Q), dim3(RS_THREADS), smem, stream, cand, cnt, \
-                       cap, k_prime, kp2, queries, exact, ld, d, k, out_ids, out_scores, out_margin)
+                       cap, k_prime, kp2, queries, exact, ld, d, k, out_ids, out_scores, out_margin, cert)
     if (exact_dtype == DT_F16) {
         if (metric == METRIC_L2) RALM_RS(DT_F16, true);
         else RALM_RS(DT_F16, false);
@@ -285,6 +514,52 @@ hipError_t launch_rescore(const u64 *cand, const uint32_t *cnt, uint32_t cap, in
         else RALM_RS(DT_F32, false);
     }
 #undef RALM_RS
+    return hipGetLastError();
+}
+
+hipError_t launch_exact_pass(const float *queries, int64_t Q, const void *exact, int32_t exact_dtype, int64_t ld,
+                             int64_t N, int32_t d, int32_t metric, int32_t k, const int32_t *fb_list, int32_t *flags,
+                             const u64 *tau_exact, u64 *cand, uint32_t *cnt, uint32_t cap, int32_t *out_ids,
+                             float *out_scores, int n_cu, hipStream_t stream)
+{
+    if (Q <= 0) return hipSuccess;
+    // as many of the queries at a time as fit 64 KB of LDS in fp32, at most XS_QG
+    int qgroup = (64 * 1024) / (d * 4);
+    if (qgroup > XS_QG) qgroup = XS_QG;
+    if (qgroup < 1) return hipErrorInvalidValue;   // d <= 16384 is checked by the caller
+    const size_t smem = (size_t)qgroup * d * 4;
+    // both kernels return at once when no query needs them; their grids do not depend on that count,
+    // which only the device knows
+    int64_t rows_per_pass = (int64_t)n_cu * 4 * XS_WAVES;
+    int64_t grid = N < rows_per_pass ? (N + XS_WAVES - 1) / XS_WAVES : (int64_t)n_cu * 4;
+#define RALM_XS(EXV, L2V)                                                                                       \
+    do {                                                                                                        \
+        auto kern = exact_scan_kernel<EXV, L2V>;                                                                \
+        static std::atomic<bool> attr_done{false};                                                              \
+        if (!attr_done.load(std::memory_order_acquire)) {                                                       \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                            \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);          \
+            if (e != hipSuccess) return e;                                                                      \
+            attr_done.store(true, std::memory_order_release);                                                   \
+        }                                                                                                       \
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(XS_THREADS), smem, stream, queries, exact, ld, N, d, \
+                           qgroup, fb_list, flags, tau_exact, cand, cnt, cap);                                  \
+    } while (0)
+    if (exact_dtype == DT_F16) {
+        if (metric == METRIC_L2) RALM_XS(DT_F16, true);
+        else RALM_XS(DT_F16, false);
+    } else {
+        if (metric == METRIC_L2) RALM_XS(DT_F32, true);
+        else RALM_XS(DT_F32, false);
+    }
+#undef RALM_XS
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    int kp2 = 2;
+    while (kp2 < k) kp2 <<= 1;
+    const int64_t fgrid = Q < 256 ? Q : 256;
+    hipLaunchKernelGGL(exact_finish_kernel, dim3((unsigned)fgrid), dim3(SEL_THREADS), (size_t)kp2 * sizeof(u64), stream,
+                       cand, cnt, cap, k, kp2, fb_list, flags, out_ids, out_scores);
     return hipGetLastError();
 }
 

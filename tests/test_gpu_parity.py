@@ -26,7 +26,11 @@ def _score_fn(oracle, Qm, Xnp):
     return f
 
 
+LAST_COUNTERS = {}
+
+
 def _retrieve_both(B, oracle, X, Qm, k, k_prime=0, scan_dtype=torch.bfloat16, margin=False):
+    """GPU result and oracle result; the call's counters are left in LAST_COUNTERS."""
     dev = "cuda"
     Xd = X.to(dev)
     ds = B.Datastore.from_fp32(Xd, scan_dtype) if X.dtype == torch.float32 else B.Datastore(Xd, None)
@@ -35,6 +39,9 @@ def _retrieve_both(B, oracle, X, Qm, k, k_prime=0, scan_dtype=torch.bfloat16, ma
     mg = torch.empty(qd.shape[0], dtype=torch.float32, device=dev) if margin else None
     ids, sc = B.ralm_retrieve_topk_ex(qd, ds, k, k_prime, workspace=ws, out_margin=mg)
     assert B.ralm_workspace_overflows(ws) == 0
+    LAST_COUNTERS.clear()
+    LAST_COUNTERS.update(B.ralm_workspace_counters(ws))
+    assert LAST_COUNTERS["soft_certified"] + LAST_COUNTERS["exact_pass"] == qd.shape[0]
     want_ids, want_sc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), k)
     return ids.cpu().numpy(), sc.cpu().numpy(), want_ids, want_sc, (mg.cpu().numpy() if margin else None)
 
@@ -71,6 +78,8 @@ def test_integer_valued_data_bit_exact(B, oracle, N, d, Q, k):
     ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, X, Qm, k)
     assert np.array_equal(ids, wi)
     assert np.array_equal(sc, wsc)
+    # the scan itself got it right: nothing here may lean on the exact pass
+    assert LAST_COUNTERS["exact_pass"] == 0 and LAST_COUNTERS["ladder_overflows"] == 0
 
 
 @pytest.mark.parametrize("scan_dtype", [torch.bfloat16, torch.float16])
@@ -84,6 +93,7 @@ def test_clustered_real_valued(B, oracle, scan_dtype, N, d, Q, k):
     exact, subs, total = check_topk(ids, sc, wi, wsc, _score_fn(oracle, Qm.numpy(), X.numpy()))
     assert exact >= 0.99 * total
     assert np.all(np.isfinite(mg))
+    assert LAST_COUNTERS["exact_pass"] == 0        # k' = 64 leaves a margin far above the scan's rounding
 
 
 def test_simple_form_fp32_datastore(B, oracle):
@@ -145,7 +155,7 @@ def test_edge_cases(B, oracle):
 def test_tile_admitting_more_than_the_parking_list(B, oracle, Q):
     """A run of identical rows that is every query's best match makes single tiles admit thousands
     of scores in a thresholded stage: more than the workgroup's on-chip list holds, so the tile is
-    redone in direct mode.  Results must still be exact, ties by lowest id."""
+    sent to the global lists directly.  Results must still be exact, ties by lowest id."""
     g = torch.Generator().manual_seed(11)
     N, d = 40000, 64
     X = torch.randint(-2, 3, (N, d), generator=g).float()
@@ -156,6 +166,7 @@ def test_tile_admitting_more_than_the_parking_list(B, oracle, Q):
     ids, sc, wi, wsc, _ = _retrieve_both(B, oracle, X, Qm, 20)
     assert np.array_equal(ids, wi) and np.array_equal(sc, wsc)
     assert ids[1].tolist() == list(range(20000, 20020))
+    assert LAST_COUNTERS["exact_pass"] == 0 and LAST_COUNTERS["ladder_overflows"] == 0
 
 
 def _rows_against_the_strides(N=200000, d=32):
@@ -179,20 +190,24 @@ def _rows_against_the_strides(N=200000, d=32):
     return X, Qm
 
 
-def test_list_overflow_is_flagged_and_the_sequential_ladder_is_exact(B, oracle):
+def test_list_overflow_is_recovered_by_the_exact_pass_and_the_sequential_ladder_has_none(B, oracle):
     X, Qm = _rows_against_the_strides()
     k = 20
     ds = B.Datastore.from_fp32(X.cuda())
     qd = Qm.cuda()
     ws = B.alloc_workspace(3, ds, k)
-    ids, sc = B.ralm_retrieve_topk_ex(qd, ds, k, workspace=ws)
-    assert B.ralm_workspace_overflows(ws) == 3
-    assert bool((ids == -1).all()) and bool(torch.isnan(sc).all())
     wi, wsc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), k)
-    ids, sc = B.ralm_retrieve_topk_ex(qd, ds, k, workspace=ws, sequential=True)
+    # the strided ladder loses list entries for all three queries; the exact pass of the same call
+    # answers them, with no host round trip in between
+    ids, sc = B.ralm_retrieve_topk_ex(qd, ds, k, workspace=ws)
+    c = B.ralm_workspace_counters(ws)
+    assert c["ladder_overflows"] == 3 and c["exact_pass"] == 3 and c["unanswered"] == 0, c
     assert B.ralm_workspace_overflows(ws) == 0
     assert np.array_equal(ids.cpu().numpy(), wi) and np.array_equal(sc.cpu().numpy(), wsc)
-    # the simple form retries by itself
+    ids, sc = B.ralm_retrieve_topk_ex(qd, ds, k, workspace=ws, sequential=True)
+    c = B.ralm_workspace_counters(ws)
+    assert c["ladder_overflows"] == 0 and c["exact_pass"] == 0 and c["unanswered"] == 0, c
+    assert np.array_equal(ids.cpu().numpy(), wi) and np.array_equal(sc.cpu().numpy(), wsc)
     ids, sc = B.ralm_retrieve_topk(qd, X.cuda(), k)
     assert np.array_equal(ids.cpu().numpy(), wi) and np.array_equal(sc.cpu().numpy(), wsc)
 
