@@ -145,8 +145,12 @@ def retrieve_topk_stream(queries: np.ndarray, chunks: Iterable[Tuple[int, object
     """Same result as ``retrieve_topk`` for a datastore delivered as (base_row, rows) chunks.
 
     Per query a carry list of the best k (score, id) pairs so far is kept; for
-    each chunk all of its scores are computed, carry + chunk is fully sorted by
-    (score descending, id ascending) and cut to k.
+    each chunk all of its scores are computed, carry + chunk is sorted by
+    (score descending, id ascending) and cut to k.  Once the carry holds k
+    pairs, a row of the chunk whose score is below the carry's k-th score
+    cannot be among the first k of that sort (k pairs rank before it), so such
+    rows are left out of the sort; rows that tie with the k-th score stay in,
+    the id decides.  Chunks may come in any order.
     """
     queries = np.ascontiguousarray(queries, dtype=np.float32)
     Q = queries.shape[0]
@@ -156,8 +160,13 @@ def retrieve_topk_stream(queries: np.ndarray, chunks: Iterable[Tuple[int, object
         n = (rows.bits if isinstance(rows, bf16_store) else rows).shape[0]
         ids_here = np.arange(base, base + n, dtype=np.int64)
         for i in range(Q):
-            s = np.concatenate([carry_s[i], scores(queries[i], rows, metric)])
-            j = np.concatenate([carry_i[i], ids_here])
+            here_s = scores(queries[i], rows, metric)
+            here_i = ids_here
+            if carry_s[i].shape[0] == k:
+                may_enter = here_s >= carry_s[i][k - 1]
+                here_s, here_i = here_s[may_enter], here_i[may_enter]
+            s = np.concatenate([carry_s[i], here_s])
+            j = np.concatenate([carry_i[i], here_i])
             order = np.lexsort((j, -s.astype(np.float64)))[:k]
             carry_s[i], carry_i[i] = s[order], j[order]
     ids = np.stack([c.astype(np.int32) for c in carry_i])

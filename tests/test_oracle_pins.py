@@ -156,6 +156,30 @@ def test_structural_invariants(oracle):
     assert np.array_equal(ids_s, ids10) and np.array_equal(sc_s, sc10)
 
 
+def test_chunk_streamed_retrieval_with_ties_across_chunks_in_any_order(oracle):
+    """The streamed form drops a chunk's rows that score below the k-th best so far before it
+    sorts; rows that TIE with that score must survive (a lower id in a later-delivered chunk wins).
+    Integer-valued data with few distinct scores, chunks delivered in shuffled order, every
+    split size: equal to the whole-datastore sort, and to a ranking done with Python integers."""
+    rng = np.random.default_rng(11)
+    N, d, k = 3000, 4, 25
+    X = rng.integers(-2, 3, size=(N, d)).astype(np.float32)
+    Qm = rng.integers(-2, 3, size=(4, d)).astype(np.float32)
+    Qm[3] = 0                                               # all scores tie: the answer is ids 0..k-1
+    want_ids, want_sc = oracle.retrieve_topk(Qm, X, k)
+    assert want_ids[3].tolist() == list(range(k))
+    xi, qi = X.astype(int).tolist(), Qm.astype(int).tolist()
+    for i in range(4):
+        ranked = sorted(range(N), key=lambda j: (-sum(a * b for a, b in zip(qi[i], xi[j])), j))[:k]
+        assert ranked == want_ids[i].tolist()
+    for n_parts in (1, 2, 7, 64):
+        parts = np.array_split(np.arange(N), n_parts)
+        for order in (list(range(n_parts)), list(range(n_parts))[::-1], rng.permutation(n_parts).tolist()):
+            chunks = [(int(parts[c][0]), X[parts[c]]) for c in order]
+            ids_s, sc_s = oracle.retrieve_topk_stream(Qm, chunks, k)
+            assert np.array_equal(ids_s, want_ids) and np.array_equal(sc_s, want_sc), (n_parts, order)
+
+
 def test_transposed_or_misindexed_operands_would_fail(oracle):
     """A asymmetric case with d != N, distinct per-component weights and a non-square query
     block: any swap of (row, component) indexing or a dropped last component changes the answer."""
