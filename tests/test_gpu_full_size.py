@@ -20,23 +20,6 @@ def B():
     return binding
 
 
-def _stream_chunks(exact):
-    N = exact.shape[0]
-    for r0 in range(0, N, CHUNK):
-        yield r0, exact[r0:min(N, r0 + CHUNK)].cpu().numpy()
-
-
-def _oracle_sampled(oracle, exact, queries_np, k):
-    return oracle.retrieve_topk_stream(queries_np, _stream_chunks(exact), k)
-
-
-def _score_of_rows(oracle, exact, queries_np):
-    def f(i, ids):
-        rows = exact[torch.as_tensor(np.asarray(ids, dtype=np.int64), device=exact.device)].cpu().numpy()
-        return oracle.scores(queries_np[i], rows)
-    return f
-
-
 def test_medium_batched_verification_every_query(B, oracle):
     """1M x 768, 16 requests x stride {1,2,4,8}, k = 5, 1024-entry caches: every query checked."""
     from paper_2401_14021_amd import inputs
@@ -72,53 +55,104 @@ def test_medium_batched_verification_every_query(B, oracle):
 
 @pytest.fixture(scope="module")
 def dense21m(B):
+    """21M x 768: the fp32 rows on the device (with their bf16 scan copy) and the very same bytes
+    on the host for the oracle, copied back once."""
     from paper_2401_14021_amd import inputs
     w = inputs.WORKLOADS["dense21m"]
     X = torch.empty(w.N, w.d, dtype=torch.float32, device="cuda")
     _, assign = inputs.clustered_datastore(w.N, w.d, w.n_clusters, w.seed, device="cuda", out=X)
     ds = B.Datastore.from_fp32(X)
     torch.cuda.synchronize()
-    yield w, X, assign, ds
-    del ds, X
+    print("dense21m: generated; copying the rows to the host ...", flush=True)
+    Xh = np.empty((w.N, w.d), dtype=np.float32)
+    for r0 in range(0, w.N, CHUNK):
+        r1 = min(w.N, r0 + CHUNK)
+        Xh[r0:r1] = X[r0:r1].cpu().numpy()
+    yield w, X, assign, ds, Xh
+    del ds, X, Xh
     torch.cuda.empty_cache()
 
 
+def _host_chunks(Xh):
+    for r0 in range(0, Xh.shape[0], CHUNK):
+        yield r0, Xh[r0:r0 + CHUNK]
+
+
+def _check_sample(oracle, Xh, qnp, k, got_ids, got_sc, want):
+    """got_*: GPU results of the sampled queries; want: (ids, scores) of the oracle for k_max >= k."""
+    wi, wsc = want[0][:, :k], want[1][:, :k]
+    return check_topk(got_ids, got_sc, wi, wsc,
+                      lambda i, g: oracle.scores(qnp[i], Xh[np.asarray(g, dtype=np.int64)]))
+
+
 def test_dense21m_sampled_queries(B, oracle, dense21m):
-    """21M x 768 bf16 scan + fp32 re-score, Q in {1, 8, 64, 256, 1024}, k in {1, 20}: the oracle
-    ranks all 21M rows for a seeded sample of queries; every batch size must agree with it."""
+    """21M x 768 bf16 scan + fp32 re-score, Q in {1, 8, 64, 256, 1024}, k in {1, 20}.  The oracle
+    ranks all 21M rows for 128 seeded queries: positions of the 1024-batch spread over its four
+    256-query tiles and all wave columns (64 of them in the first 256).  The first 64 of them ARE
+    the batches of 1, 8 and 64 (every query checked); the batches of 256 and 1024 are prefixes of
+    the 1024 queries (64 and 128 of their queries checked).  Whatever the batch, a query's result must
+    be the oracle's; margins must clear the scan's rounding by a wide factor at these sizes."""
     from paper_2401_14021_amd import inputs
-    w, X, assign, ds = dense21m
+    w, X, assign, ds, Xh = dense21m
     Qmax = 1024
     rows = inputs.pick_rows(w.N, Qmax, seed=w.seed + 1)
     Qm = inputs.queries_near_rows(X, rows.cuda(), seed=w.seed + 2)
-    sample = [0, 5, 63, 700]
+    g = torch.Generator().manual_seed(w.seed + 3)
+    first = torch.randperm(256, generator=g)[:64]
+    rest = 256 + torch.randperm(768, generator=g)[:64]
+    # the first 64 sampled positions (32 + 32) make up the small batches
+    sample = torch.cat([first[:32], rest[:32], first[32:], rest[32:]]).tolist()
+    for t in range(4):                                # every 256-query tile is sampled
+        assert sum(1 for i in sample if i // 256 == t) >= 10
+    assert len({(i % 256) // 64 for i in sample}) == 4 and len(set(sample)) == 128
     qs = Qm[sample].cpu().numpy()
-    wi, wsc = _oracle_sampled(oracle, X, qs, 20)
-    score_of = _score_of_rows(oracle, X, qs)
-    # the source row (or a better one) must be found: a sanity check on the oracle's streaming
-    assert all(wsc[j, 0] >= 0.5 for j in range(len(sample)))
+    print("dense21m: oracle ranks 21M rows for 128 queries ...", flush=True)
+    want = oracle.retrieve_topk_stream(qs, _host_chunks(Xh), 20)
+    print("dense21m: oracle done", flush=True)
+    assert (want[1][:, 0] >= 0.5).all()               # the source row (or a better one) is found
+    total_subs = 0
     for Q in (1, 8, 64, 256, 1024):
         for k in (1, 20):
+            if Q <= 64:
+                batch, here = Qm[sample[:Q]].contiguous(), list(range(Q))
+                pos = list(range(Q))
+            else:
+                batch = Qm[:Q].contiguous()
+                here = [j for j, i in enumerate(sample) if i < Q]
+                pos = [sample[j] for j in here]
             ws = B.alloc_workspace(Q, ds, k, w.k_prime)
-            ids, sc = B.ralm_retrieve_topk_ex(Qm[:Q].contiguous(), ds, k, w.k_prime, workspace=ws)
-            assert B.ralm_workspace_overflows(ws) == 0
-            here = [j for j, i in enumerate(sample) if i < Q]
-            gi = ids.cpu().numpy()[[sample[j] for j in here]]
-            gs = sc.cpu().numpy()[[sample[j] for j in here]]
-            exact, subs, total = check_topk(gi, gs, wi[here][:, :k], wsc[here][:, :k],
-                                            lambda i, g: score_of(here[i], g))
-            assert subs <= 1
-            # properties that hold for every query at any size
+            mg = torch.empty(Q, device="cuda")
+            ids, sc = B.ralm_retrieve_topk_ex(batch, ds, k, w.k_prime, workspace=ws, out_margin=mg)
+            c = B.ralm_workspace_counters(ws)
+            assert c["unanswered"] == 0 and c["ladder_overflows"] == 0 and c["exact_pass"] == 0, (Q, k, c)
+            assert c["soft_certified"] == Q
+            exact, subs, total = _check_sample(oracle, Xh, qs[here], k, ids.cpu().numpy()[pos], sc.cpu().numpy()[pos],
+                                               (want[0][here], want[1][here]))
+            total_subs += subs
+            assert len(here) >= min(Q, 64)
+            # every query, at any size: ids in range, distinct, scores ordered, margin clear of the
+            # rounding of a bf16 scan of unit vectors (8 sigma of a noise model: 0.4 u |q||x| / sqrt(d)
+            # per score)
             assert int(ids.min()) >= 0 and int(ids.max()) < w.N
-            assert bool((sc[:, :-1] >= sc[:, 1:]).all()) if k > 1 else True
+            if k > 1:
+                assert bool((sc[:, :-1] >= sc[:, 1:]).all())
+                srt = torch.sort(ids.long(), dim=1).values
+                assert bool((srt[:, 1:] != srt[:, :-1]).all())
+            noise_bound = 8 * 0.4 * 2.0 ** -8 * batch.norm(dim=1) / w.d ** 0.5
+            assert bool((mg > noise_bound).all()), float((mg - noise_bound).min())
+    assert total_subs <= 2          # near-tie substitutions over all checked (query, batch, k) cases
 
 
-def test_specloop_steps_full_size(B, oracle, dense21m):
-    """Speculation loop stress shape: 512 requests with their own 4096-entry caches, strides
-    uniform in 1..8 (about 2300 queries), per step a cache top-1 lookup, one batched exact top-1
-    retrieval and the first-mismatch compare; queries drift between steps."""
+def test_specloop_closed_loop_100_steps_full_size(B, oracle, dense21m):
+    """Speculation loop stress shape, closed: 512 requests with their own 4096-entry caches that
+    start EMPTY, strides uniform in 1..8 (about 2300 queries); per step a cache top-1 lookup, one
+    batched exact top-1 retrieval, the first-mismatch compare and the top-1 cache update with the
+    verified steps; queries drift between steps; 100 steps.  Integer stages (compare, update) are
+    checked against the oracle on everything at every step; the retrieval on 16 seeded queries and
+    the cache lookup on 3 seeded requests at steps 0, 1, 10, 50 and 99; rank preservation
+    (Section 3) on every query at every step."""
     from paper_2401_14021_amd import inputs
-    w, X, assign, ds = dense21m
+    w, X, assign, ds, Xh = dense21m
     c = inputs.WORKLOADS["specloop"]
     R = 512
     strides = inputs.uniform_strides(R, 1, 8, seed=c.seed)
@@ -126,40 +160,60 @@ def test_specloop_steps_full_size(B, oracle, dense21m):
     Q = int(off[-1])
     rows = inputs.pick_rows(c.N, Q, seed=c.seed + 1)
     Qm = X[rows.cuda()].contiguous()
-    cids, clen = inputs.speculation_caches(c.N, R, c.cache_C, off, rows, None, seed=c.seed + 2)
-    cids_d, clen_d, off_d = cids.cuda(), clen.cuda(), off.cuda()
+    off_d, off_h = off.cuda(), off.numpy()
+    cids = torch.full((R, c.cache_C), -1, dtype=torch.int32, device="cuda")
+    clen = torch.zeros(R, dtype=torch.int32, device="cuda")
+    chead = torch.zeros(R, dtype=torch.int32, device="cuda")
+    o_ids, o_len, o_head = cids.cpu().numpy(), clen.cpu().numpy(), chead.cpu().numpy()
     ws = B.alloc_workspace(Q, ds, 1, c.k_prime)
-    sample_q = [0, 1000, Q - 1]
-    sample_r = [0, 17, 511]
-    for step in range(3):
+    cl_ws = torch.empty(Q, dtype=torch.int64, device="cuda")
+    g = torch.Generator().manual_seed(c.seed + 7)
+    req_of = torch.repeat_interleave(torch.arange(R, device="cuda"), torch.tensor(strides, device="cuda"))
+    hit_rates = []
+    for step in range(100):
         Qm = inputs.drift_queries(Qm, seed=c.seed + 100 + step)
-        spec, spec_sc = B.ralm_cache_lookup(cids_d, clen_d, Qm, off_d, ds)
+        spec, spec_sc = B.ralm_cache_lookup(cids, clen, Qm, off_d, ds, workspace=cl_ws)
         ids, sc = B.ralm_retrieve_topk_ex(Qm, ds, 1, c.k_prime, workspace=ws)
         m = B.ralm_verify(spec, ids, off_d, true_stride=1)
-        assert B.ralm_workspace_overflows(ws) == 0
-        # integer stage: exact on everything
-        want_m = oracle.verify(spec.cpu().numpy(), ids.cpu().numpy().reshape(-1), off.numpy(), 1)
-        assert np.array_equal(m.cpu().numpy(), want_m)
-        # cache lookup: sampled requests, all of their queries, oracle over the gathered cached rows
-        qnp = Qm.cpu().numpy()
-        for r in sample_r:
-            n = int(clen[r])
-            ids_r = cids[r, :n].numpy()
-            uniq, inv = np.unique(ids_r, return_inverse=True)
-            sub = X[torch.from_numpy(uniq).cuda().long()].cpu().numpy()
-            lo, hi = int(off[r]), int(off[r + 1])
-            ci, csc = oracle.cache_lookup(inv.astype(np.int32)[None, :], np.array([n], dtype=np.int32),
-                                          qnp[lo:hi], np.array([0, hi - lo], dtype=np.int64), sub)
-            assert np.array_equal(uniq[ci], spec.cpu().numpy()[lo:hi])
-            assert np.array_equal(csc, spec_sc.cpu().numpy()[lo:hi])
-        if step == 0:
-            wi, wsc = _oracle_sampled(oracle, X, qnp[sample_q], 1)
-            score_of = _score_of_rows(oracle, X, qnp[sample_q])
-            check_topk(ids.cpu().numpy()[sample_q], sc.cpu().numpy()[sample_q], wi, wsc, score_of)
-        # rank preservation on every query (Section 3): a cached true top-1 is the cache's top-1
+        spec_h, ids_h, m_h = spec.cpu().numpy(), ids.cpu().numpy(), m.cpu().numpy()
+        cnt = B.ralm_workspace_counters(ws)
+        assert cnt["unanswered"] == 0 and cnt["exact_pass"] == 0 and cnt["ladder_overflows"] == 0, (step, cnt)
+        # rank preservation on every query: a cached true top-1 is the cache's top-1, same score
         t = ids[:, 0]
         same = spec == t
-        req_of = torch.repeat_interleave(torch.arange(R, device="cuda"), torch.tensor(strides, device="cuda"))
-        cached = (cids_d[req_of] == t[:, None]).any(dim=1)
-        assert bool((same | ~cached).all())
-        assert bool((spec_sc[same] == sc[same, 0]).all())
+        cached = (cids[req_of] == t[:, None]).any(dim=1)
+        assert bool((same | ~cached).all()), step
+        assert bool((spec_sc[same] == sc[same, 0]).all()), step
+        hit_rates.append(float(same.float().mean()))
+        # integer stages against the oracle, everything
+        assert np.array_equal(m_h, oracle.verify(spec_h, ids_h.reshape(-1), off_h, 1)), step
+        if step in (0, 1, 10, 50, 99):
+            print(f"specloop: step {step}, hit rate {hit_rates[-1]:.2f}, oracle on 16 queries ...", flush=True)
+            qnp = Qm.cpu().numpy()
+            sample_q = torch.randperm(Q, generator=g)[:16].tolist()
+            want = oracle.retrieve_topk_stream(qnp[sample_q], _host_chunks(Xh), 1)
+            _check_sample(oracle, Xh, qnp[sample_q], 1, ids_h[sample_q], sc.cpu().numpy()[sample_q], want)
+            # cache lookup of sampled requests (the state before this step's update = the oracle's)
+            for r in torch.randperm(R, generator=g)[:3].tolist():
+                n = int(o_len[r])
+                lo, hi = int(off_h[r]), int(off_h[r + 1])
+                if n == 0:
+                    assert (spec_h[lo:hi] == -1).all()
+                    continue
+                ids_r = o_ids[r, :n]
+                uniq, inv = np.unique(ids_r, return_inverse=True)
+                ci, csc = oracle.cache_lookup(inv.astype(np.int32)[None, :], np.array([n], dtype=np.int32),
+                                              qnp[lo:hi], np.array([0, hi - lo], dtype=np.int64), Xh[uniq])
+                assert np.array_equal(uniq[ci], spec_h[lo:hi]), (step, r)
+                assert np.array_equal(csc, spec_sc.cpu().numpy()[lo:hi]), (step, r)
+        B.ralm_cache_insert(cids, clen, chead, ids, off_d, c.N, p=1, first_mismatch=m)
+        o_ids, o_len, o_head = oracle.cache_insert(o_ids, o_len, o_head, ids_h, off_h, N=c.N, p=1, first_mismatch=m_h)
+        assert np.array_equal(clen.cpu().numpy(), o_len) and np.array_equal(chead.cpu().numpy(), o_head), step
+        if step % 10 == 9 or step < 2:
+            got = cids.cpu().numpy()
+            for r in range(R):
+                assert np.array_equal(got[r, :o_len[r]], o_ids[r, :o_len[r]]), (step, r)
+    # the loop is closed: caches that start empty hit nothing at first; while a query is still near
+    # its source row its top-1 repeats from step to step and the cache answers most steps
+    print("hit rate per step:", [round(h, 2) for h in hit_rates[:12]], "...", round(hit_rates[-1], 2))
+    assert hit_rates[0] == 0.0 and max(hit_rates) > 0.5, hit_rates[:12]

@@ -33,8 +33,12 @@ def _advance(q, doc_row, r, t):
     return v / v.norm()
 
 
+@pytest.mark.parametrize("baseline", ["oracle", "library"])
 @pytest.mark.parametrize("asynchronous", [False, True])
-def test_speculative_loop_preserves_the_document_sequence(B, asynchronous):
+def test_speculative_loop_preserves_the_document_sequence(B, oracle, asynchronous, baseline):
+    """baseline = "oracle": the reference document sequence comes from the CPU oracle's retrieval
+    at every step (parity evidence); "library": from the library's own retrieval at every step
+    (the paper's output-preservation claim on the library alone)."""
     from paper_2401_14021_amd import inputs
     N, d, R, T, C, k, s_max = 20000, 64, 6, 20, 64, 5, 6
     X, _ = inputs.clustered_datastore(N, d, 24, seed=131)
@@ -46,8 +50,13 @@ def test_speculative_loop_preserves_the_document_sequence(B, asynchronous):
     # ---- retrieval at every step ------------------------------------------------------------
     base_docs = np.zeros((R, T), dtype=np.int64)
     q = q0.clone()
+    Xnp = X.numpy()
     for t in range(T):
-        ids, _ = B.ralm_retrieve_topk_ex(q.contiguous(), ds, 1)
+        if baseline == "oracle":
+            oi, _ = oracle.retrieve_topk(q.cpu().numpy(), Xnp, 1)
+            ids = torch.from_numpy(oi).cuda()
+        else:
+            ids, _ = B.ralm_retrieve_topk_ex(q.contiguous(), ds, 1)
         base_docs[:, t] = ids[:, 0].cpu().numpy()
         q = torch.stack([_advance(q[r], Xd[ids[r, 0].long()], r, t) for r in range(R)])
 
