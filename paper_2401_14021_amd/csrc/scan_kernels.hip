@@ -349,10 +349,20 @@ __device__ __forceinline__ int swz(int r)
 // 64 lanes x 16 bytes, from  base + per-lane byte offset,  to 1 KB of LDS starting at lds_base
 // (base and lds_base are wave-uniform).  Written as inline asm so that the compiler does not
 // track it: completion is awaited by hand with s_waitcnt vmcnt(n) (loads complete in order).
+//
+// NT: the load is marked non-temporal.  Datastore rows that no other workgroup will read (the
+// batch fits one query tile) are streamed that way: they do not displace the query tile in L2,
+// and a pure read stream reaches a higher HBM rate with it.  Rows that several query tiles share
+// through L2, and the queries themselves, are loaded with the default policy.
+template <bool NT>
 __device__ __forceinline__ void dma_1kb(const unsigned char *base, uint32_t voff, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(base)
-                 : "memory");
+    if constexpr (NT)
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_base), "v"(voff), "s"(base)
+                     : "memory");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(base)
+                     : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
@@ -373,7 +383,16 @@ constexpr int PARK_CAP = 672;         // parked admitted scores per workgroup (1
 // stages ahead.  sched_barrier keeps the compiler from regrouping them.  In a tile's last
 // k-step the MFMA results are written to VGPRs and each block's selection test runs two MFMAs
 // behind its last multiply, so the selection costs no separate pass over the accumulators.
-template <bool F16, int WM, int WN, int TM, int TN, int BK, int S>
+//
+// The ring has S slots and the issue cursor runs D stages ahead of the multiply.  D = S - 1 (the
+// loads issued during stage t refill the slot of stage t - 1) or D = S (they refill the slot of
+// stage t itself, once every wave has read the operands of the stage's last k-step out of it: a
+// ring of two 64-element strips then does the work of four 32-element strips, with half the
+// rendezvous per multiply and whole 128-byte lines per request).  The rendezvous of a stage
+// sits in k-step RK, behind that k-step's operand reads; the query part of the new strip is
+// requested after it in the same k-step, the datastore part in the next k-step.  RK = KS - 2 is
+// the k-step whose reads are the stage's last, which D = S needs.
+template <bool F16, int WM, int WN, int TM, int TN, int BK, int S, bool NTA, int D = S - 1, int RK = 0>
 __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams p, const int nqt, const int tau_in_lds)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
@@ -387,12 +406,13 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     constexpr int KS = BK / 16;
     constexpr int NM = TM * TN, NR = TM + TN;
     constexpr int LAG = NM > 2 ? 2 : NM - 1;     // selection runs this many MFMAs behind
-    constexpr int RV = NR - 1;                   // k-step 0 slot after which the stage rendezvous sits
+    constexpr int RV = NR - 1;                   // slot of k-step RK after which the stage rendezvous sits
     // a workgroup tile covers the whole 256-row tile of the ladder, or half of it
     constexpr int PARTS = SCAN_BM / BM;
     static_assert((NW == 4 || NW == 8) && (BM == SCAN_BM || BM * 2 == SCAN_BM) && NA >= 1 && NB >= 1, "tile shape");
-    static_assert(S >= 3 && KS % 2 == 0, "ring depth / k-steps per stage");
-    static_assert(LPS * (S - 2) < 64, "vmcnt range");
+    static_assert(S >= 2 && (D == S - 1 || D == S) && D >= 2 && KS % 2 == 0, "ring depth / k-steps per stage");
+    static_assert(RK >= 0 && RK + 1 < KS && (D < S || RK == KS - 2), "rendezvous position");
+    static_assert(LPS * (D - 1) < 64, "vmcnt range");
 
     extern __shared__ __align__(16) unsigned char smem[];
     const uint32_t lds0 = (uint32_t)(size_t)(RALM_LDS unsigned char *)smem;
@@ -433,14 +453,15 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
         for (int q = tid; q < p.Q; q += NT) tau_lds[q] = p.tau[q];
 
     // ---- issue cursor: runs S-1 stages ahead of the multiply, also across tile boundaries ----
-    // per-lane constants of the loads: tile row and swizzled chunk offset of each wave load
-    uint32_t a_row[NA], a_chunk[NA], b_voff[NB];
+    // per-lane constants of the loads: byte offset (tile row, swizzled chunk) of each wave load
+    // inside a strip that lies fully inside the datastore; strips at its edges are clamped instead
+    uint32_t a_voff[NA], b_voff[NB];
+    auto a_tile_row = [&](int j) __attribute__((always_inline)) { return (uint32_t)((wave * NA + j) * RPI + l_r); };
+    auto a_tile_chunk = [&](int j) __attribute__((always_inline)) {
+        return (uint32_t)((l_c ^ swz<BK>((int)a_tile_row(j) & 15)) << 4);
+    };
 #pragma unroll
-    for (int j = 0; j < NA; ++j) {
-        const int row = (wave * NA + j) * RPI + l_r;
-        a_row[j] = row;
-        a_chunk[j] = (uint32_t)((l_c ^ swz<BK>(row & 15)) << 4);
-    }
+    for (int j = 0; j < NA; ++j) a_voff[j] = __umul24(a_tile_row(j), ldx2) + a_tile_chunk(j);   // row < 2^8, ldx2 < 2^24
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
         const int row = (wave * NB + j) * RPI + l_r;
@@ -456,6 +477,7 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     // wave-uniform state of the stage being issued
     const unsigned char *is_abase = nullptr, *is_bbase = nullptr, *is_aload = nullptr;
     uint32_t is_rowmax = 0, is_kmax = 0, is_lds = 0;
+    bool is_inside = false;   // the strip needs no clamping
     auto issue_begin = [&]() __attribute__((always_inline)) {
         if (is_kt == 0) {
             // The cursor is never stopped: past this workgroup's last tile it fetches (valid)
@@ -477,16 +499,22 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
         const int kleft = (p.d - 8 - is_kt * BK) * 2;
         is_kmax = (uint32_t)(kleft < 0 ? 0 : (kleft < ROWB - 16 ? kleft : ROWB - 16));
         is_aload = is_abase + (kleft < 0 ? kleft : 0);
+        is_inside = is_rowmax == (uint32_t)(BM - 1) && kleft >= ROWB - 16;
         is_lds = lds0 + is_buf * STAGE + wave * (NA * 1024);
     };
     auto issue_part = [&](int idx) __attribute__((always_inline)) {
         if (idx < NA) {
-            const uint32_t r = a_row[idx] < is_rowmax ? a_row[idx] : is_rowmax;
-            const uint32_t c = a_chunk[idx] < is_kmax ? a_chunk[idx] : is_kmax;
-            dma_1kb(is_aload, __umul24(r, ldx2) + c, is_lds + idx * 1024);   // r < 2^8, ldx2 < 2^24
+            uint32_t voff = a_voff[idx];
+            if (!is_inside) {   // wave-uniform, rare: the datastore's last rows or last columns
+                const uint32_t row = a_tile_row(idx), chunk = a_tile_chunk(idx);
+                const uint32_t r = row < is_rowmax ? row : is_rowmax;
+                const uint32_t c = chunk < is_kmax ? chunk : is_kmax;
+                voff = __umul24(r, ldx2) + c;
+            }
+            dma_1kb<NTA>(is_aload, voff, is_lds + idx * 1024);
         } else {
             const int j = idx - NA;
-            dma_1kb(is_bbase, b_voff[j], lds0 + is_buf * STAGE + A_BYTES + (wave * NB + j) * 1024);
+            dma_1kb<false>(is_bbase, b_voff[j], lds0 + is_buf * STAGE + A_BYTES + (wave * NB + j) * 1024);
         }
     };
     auto issue_end = [&]() __attribute__((always_inline)) {
@@ -504,36 +532,34 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
         }
     };
 
-    for (int st = 0; st < S - 1; ++st) {
+    for (int st = 0; st < D; ++st) {
         issue_begin();
 #pragma unroll
         for (int idx = 0; idx < LPS; ++idx) issue_part(idx);
         issue_end();
     }
 
-    // operand read offsets of this lane inside a stage (bytes)
-    int a_off[KS], b_off[KS];
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk) {
-        const int c = kk * 2 + (lane >> 5);
-        const int sw = (c ^ swz<BK>(fr & 15)) << 4;
-        a_off[kk] = (wm * TM * 32 + fr) * ROWB + sw;
-        b_off[kk] = A_BYTES + (wn * TN * 32 + fr) * ROWB + sw;
-    }
+    // Operand read offsets of this lane inside a stage (bytes) for k-step 0.  K-step kk reads the
+    // chunks 2 kk and 2 kk + 1 of a row, i.e. chunk slot (2 kk + lane / 32) ^ swz: its offset is the
+    // k-step 0 offset with 32 kk XOR-ed in (the row part is a multiple of the row size, above it).
+    const int sw0 = ((lane >> 5) ^ swz<BK>(fr & 15)) << 4;
+    const int a_off0 = (wm * TM * 32 + fr) * ROWB + sw0;
+    const int b_off0 = A_BYTES + (wn * TN * 32 + fr) * ROWB + sw0;
+    static_assert((KS - 1) * 32 < ROWB && A_BYTES % ROWB == 0, "k-step offset stays inside the row");
     uint4 fa[2][TM], fb[2][TN];
     auto read_frag = [&](int slot, const unsigned char *sbase, int kk, int idx) __attribute__((always_inline)) {
         // in the order the MFMAs need them: A0, all of B, then A1..
         if (idx == 0 || idx > TN) {
             const int i = idx == 0 ? 0 : idx - TN;
-            fa[slot][i] = *reinterpret_cast<const uint4 *>(sbase + a_off[kk] + i * 32 * ROWB);
+            fa[slot][i] = *reinterpret_cast<const uint4 *>(sbase + (a_off0 ^ (kk << 5)) + i * 32 * ROWB);
         } else {
             const int j = idx - 1;
-            fb[slot][j] = *reinterpret_cast<const uint4 *>(sbase + b_off[kk] + j * 32 * ROWB);
+            fb[slot][j] = *reinterpret_cast<const uint4 *>(sbase + (b_off0 ^ (kk << 5)) + j * 32 * ROWB);
         }
     };
 
     // stage 0 must be in LDS before the first operand read
-    wait_vmcnt<LPS *(S - 2)>();
+    wait_vmcnt<LPS *(D - 1)>();
     __syncthreads();
 #pragma unroll
     for (int idx = 0; idx < NR; ++idx) read_frag(0, smem, 0, idx);
@@ -570,11 +596,11 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
                 const unsigned char *nsb = last_kk ? smem + nbuf * STAGE : sb;
                 const int nkk = last_kk ? 0 : kk + 1;
                 // side instructions of this k-step: the operand reads of the next k-step (for the
-                // last k-step: of the next stage), then the global->LDS loads (k-step 1 only)
-                // (the rendezvous sits inside k-step 0; the query part of the strip is requested
-                // after it in k-step 0, the datastore part in k-step 1)
-                const int nd = kk == 1 ? NA : (kk == 0 ? NB : 0);
-                const int d0 = kk == 1 ? 0 : NA;
+                // last k-step: of the next stage), then the global->LDS loads (the rendezvous sits
+                // inside k-step RK; the query part of the strip is requested after it in that
+                // k-step, the datastore part in the next)
+                const int nd = kk == RK + 1 ? NA : (kk == RK ? NB : 0);
+                const int d0 = kk == RK + 1 ? 0 : NA;
                 f32x16 outs[LAG + 1];
                 RALM_SCHED_FENCE();
 #pragma unroll
@@ -603,14 +629,17 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
                         read_frag(cur ^ 1, nsb, nkk, m);
                     else if (m - NR < nd)
                         issue_part(d0 + m - NR);
-                    if (kk == 0 && m == RV) {
+                    if (kk == RK && m == RV) {
                         // Rendezvous.  After it: the next stage is complete in LDS for every
-                        // wave, and every wave has finished reading the previous stage, whose
-                        // slot is refilled by the loads issued from here on.  No LDS data is
-                        // written by ds instructions that another wave reads without a later
-                        // full barrier, so no LDS fence is needed; the asm statements keep the
-                        // compiler from moving memory operations across the barrier.
-                        wait_vmcnt<LPS *(S - 3)>();
+                        // wave, and every wave has finished reading the slot that the loads
+                        // issued from here on refill: the previous stage's (D = S - 1), or this
+                        // stage's own (D = S; its last operand reads were issued just above
+                        // and are awaited first).  No LDS data is written by ds instructions
+                        // that another wave reads without a later full barrier, so no LDS fence
+                        // is needed; the asm statements keep the compiler from moving memory
+                        // operations across the barrier.
+                        wait_vmcnt<LPS *(D - 2)>();
+                        if constexpr (D == S) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                         asm volatile("" ::: "memory");
                         __builtin_amdgcn_s_barrier();
                         asm volatile("" ::: "memory");
@@ -624,7 +653,7 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
                     }
                     RALM_SCHED_FENCE();
                 }
-                if (kk == 1) issue_end();
+                if (kk == RK + 1) issue_end();
                 RALM_SCHED_FENCE();
             }
             buf = nbuf;
@@ -636,15 +665,16 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
         auto stage_idle = [&]() __attribute__((always_inline)) {
             const int nbuf = buf + 1 == S ? 0 : buf + 1;
             RALM_SCHED_FENCE();
-            wait_vmcnt<LPS *(S - 3)>();
+            wait_vmcnt<LPS *(D - 2)>();
+            if constexpr (D == S) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // its last reads of the slot
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             issue_begin();
 #pragma unroll
-            for (int idx = NA; idx < LPS; ++idx) issue_part(idx);   // query part, as in k-step 0
+            for (int idx = NA; idx < LPS; ++idx) issue_part(idx);   // query part, as in k-step RK
 #pragma unroll
-            for (int idx = 0; idx < NA; ++idx) issue_part(idx);     // datastore part, as in k-step 1
+            for (int idx = 0; idx < NA; ++idx) issue_part(idx);     // datastore part, as in k-step RK + 1
             issue_end();
 #pragma unroll
             for (int idx = 0; idx < NR; ++idx) read_frag(((KS - 1) & 1) ^ 1, smem + nbuf * STAGE, 0, idx);
@@ -687,14 +717,14 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     wait_vmcnt<0>();   // the run-ahead loads must land before this workgroup's LDS is released
 }
 
-template <bool F16, int WM, int WN, int TM, int TN, int BK, int S>
+template <bool F16, int WM, int WN, int TM, int TN, int BK, int S, bool NTA, int D = S - 1, int RK = 0>
 hipError_t launch_dma_variant(const ScanParams &p, int n_cu, hipStream_t stream)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t ring = (size_t)S * (BM + BN) * BK * 2;
     constexpr size_t smem = ring + (size_t)tau_lds_q(BN) * 8 + (size_t)PARK_CAP * 12 + 16 + WM * WN * SLOW_SLOTS * 64;
     static_assert(smem <= 160 * 1024, "LDS budget");
-    auto kern = scan_dma_kernel<F16, WM, WN, TM, TN, BK, S>;
+    auto kern = scan_dma_kernel<F16, WM, WN, TM, TN, BK, S, NTA, D, RK>;
     const int tau_in_lds = p.Q <= tau_lds_q(BN) ? 1 : 0;
     static std::atomic<bool> attr_done{false};   // per instantiation; setting it twice is harmless
     if (!attr_done.load(std::memory_order_acquire)) {
@@ -720,10 +750,17 @@ hipError_t launch_dma(const ScanParams &p, int n_cu, hipStream_t stream)
 {
     const int bn = scan_bn_for(p.Q);
     switch (bn) {
-        case 32: return launch_dma_variant<F16, 4, 1, 2, 1, 64, 4>(p, n_cu, stream);
-        case 64: return launch_dma_variant<F16, 4, 1, 1, 2, 64, 6>(p, n_cu, stream);
-        case 128: return launch_dma_variant<F16, 2, 2, 4, 2, 32, 6>(p, n_cu, stream);
-        default: return launch_dma_variant<F16, 2, 4, 4, 2, 32, 4>(p, n_cu, stream);
+        // One query tile: nobody shares the rows through L2, they are streamed non-temporally
+        // (strips of whole 128-byte lines; with 64-byte strips a line would be requested twice, a
+        // stage apart, and would have to stay in L2 in between).
+        case 32: return launch_dma_variant<F16, 4, 1, 2, 1, 64, 4, true>(p, n_cu, stream);
+        case 64: return launch_dma_variant<F16, 4, 1, 1, 2, 64, 6, true>(p, n_cu, stream);
+        case 128: return launch_dma_variant<F16, 2, 2, 4, 2, 64, 3, true, 3, 2>(p, n_cu, stream);
+        default:
+            // two slots of 64-element strips, refilled in place (D = S): same LDS as four 32-element
+            // slots, half the rendezvous and half the L2 requests per multiply
+            if (p.Q <= 256) return launch_dma_variant<F16, 2, 4, 4, 2, 64, 2, true, 2, 2>(p, n_cu, stream);
+            return launch_dma_variant<F16, 2, 4, 4, 2, 64, 2, false, 2, 2>(p, n_cu, stream);
     }
 }
 

@@ -42,16 +42,42 @@ def cluster_centres(n_clusters: int, d: int, seed: int, device="cpu") -> torch.T
                        dtype=torch.float32)
 
 
+ROW_ORDERS = ("iid", "cluster", "corpus")
+CORPUS_RUN = 32  # mean length of a run of rows that share a cluster in "corpus" order
+
+
+def _assignments(n: int, r0: int, N: int, n_clusters: int, order: str, g: torch.Generator, device) -> torch.Tensor:
+    """Cluster of each of the rows r0 .. r0+n-1 (int64) for the given row order."""
+    if order == "iid":
+        return torch.randint(0, n_clusters, (n,), generator=g, device=device)
+    if order == "cluster":
+        # rows sorted by cluster, clusters of (nearly) equal size
+        j = torch.arange(r0, r0 + n, device=device, dtype=torch.int64)
+        return (j * n_clusters) // N
+    if order == "corpus":
+        # runs of geometric length (mean CORPUS_RUN) of one cluster each, as consecutive passages
+        # of a document or consecutive tokens of a text are near each other
+        start = torch.rand(n, generator=g, device=device) < (1.0 / CORPUS_RUN)
+        start[0] = True
+        run = torch.cumsum(start.to(torch.int64), 0) - 1
+        of_run = torch.randint(0, n_clusters, (int(run[-1]) + 1,), generator=g, device=device)
+        return of_run[run]
+    raise ValueError(f"row order {order!r} not in {ROW_ORDERS}")
+
+
 def clustered_datastore(N: int, d: int, n_clusters: int, seed: int, *, sigma: float = 0.3,
                         normalise: bool = True, device="cpu",
                         out: Optional[torch.Tensor] = None,
-                        dtype: torch.dtype = torch.float32
+                        dtype: torch.dtype = torch.float32, order: str = "iid"
                         ) -> Tuple[torch.Tensor, torch.Tensor]:
     """Rows = centre[assign] + N(0, sigma^2 I), optionally L2-normalised.
 
-    Returns (X [N, d] of ``dtype``, assign [N] int32).  Rows are in random
-    cluster order (assign is iid uniform), so any prefix or strided subset of
-    the datastore is an unbiased sample of it.
+    Returns (X [N, d] of ``dtype``, assign [N] int32).  ``order``: "iid" - rows in
+    random cluster order (assign is iid uniform), so any prefix or strided subset of
+    the datastore is an unbiased sample of it; "cluster" - rows sorted by cluster;
+    "corpus" - runs of about 32 consecutive rows share a cluster (spatial locality of
+    a datastore stored in corpus order, which the paper's next-n cache update for
+    KNN-LM relies on, Section 5.3).
     """
     centres = cluster_centres(n_clusters, d, seed, device)
     if out is None:
@@ -61,7 +87,7 @@ def clustered_datastore(N: int, d: int, n_clusters: int, seed: int, *, sigma: fl
     for ci, r0 in enumerate(range(0, N, ROW_CHUNK)):
         r1 = min(N, r0 + ROW_CHUNK)
         g = _gen(device, seed * 1000003 + 17 + ci)
-        a = torch.randint(0, n_clusters, (r1 - r0,), generator=g, device=device)
+        a = _assignments(r1 - r0, r0, N, n_clusters, order, g, device)
         x = torch.randn(r1 - r0, d, generator=g, device=device, dtype=torch.float32)
         x.mul_(sigma).add_(centres[a])
         if normalise:
@@ -164,12 +190,12 @@ def speculation_caches(N: int, R: int, C: int, q_offsets: torch.Tensor,
 
 def knnlm_datastore(N: int, d: int, n_clusters: int, seed: int, *, sigma: float = 0.5,
                     vocab: int = 50000, device="cpu",
-                    out: Optional[torch.Tensor] = None
+                    out: Optional[torch.Tensor] = None, order: str = "iid"
                     ) -> Tuple[torch.Tensor, torch.Tensor]:
     """KNN-LM style datastore: fp16 keys [N, d] (centre + N(0, sigma^2 I), raw, not
     normalised) and int32 values [N] in [0, vocab)."""
     keys, _ = clustered_datastore(N, d, n_clusters, seed, sigma=sigma, normalise=False,
-                                  device=device, out=out, dtype=torch.float16)
+                                  device=device, out=out, dtype=torch.float16, order=order)
     vals = torch.randint(0, vocab, (N,), generator=_gen(device, seed + 99), device=device,
                          dtype=torch.int32)
     return keys, vals
