@@ -193,8 +193,8 @@ __device__ __forceinline__ void select_block_parked(const ScanParams &p, const P
     float m = out[0];
 #pragma unroll
     for (int v = 1; v < 16; ++v) m = fmaxf(m, out[v]);
-    // tkey == 0 admits everything (its score bits decode to NaN: compare separately)
-    bool cand = qok && (tkey == 0ull || m >= tsc);
+    // tsc is -inf where the key admits everything and +inf for padding columns: one compare
+    bool cand = m >= tsc;
     unsigned long long mask = __builtin_amdgcn_ballot_w64(cand);
     while (mask) {   // wave-uniform
         const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
@@ -211,7 +211,7 @@ __device__ __forceinline__ void select_block_parked(const ScanParams &p, const P
             // which of the 16 values reach the threshold score (cheap, in registers) ...
             uint32_t pm = 0;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) pm |= (tkey == 0ull || out[v] >= tsc) ? (1u << v) : 0u;
+            for (int v = 0; v < 16; ++v) pm |= out[v] >= tsc ? (1u << v) : 0u;
             // ... and only those are fetched back and tested exactly (usually one or two)
 #pragma unroll 1
             while (pm) {
@@ -573,6 +573,8 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
         const int32_t row0 = (int32_t)tile_row0(cur_rt);
         const int q0 = cur_qt * BN;
         // admission keys of this lane's TN queries
+        // tsc: the score a value must reach to be looked at more closely; -inf for a key of 0
+        // (admit everything; its score bits decode to NaN), +inf for padding columns
         u64 tkey[TN];
         float tsc[TN];
         bool qok[TN];
@@ -581,7 +583,7 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
             const int q = q0 + (wn * TN + j) * 32 + fr;
             qok[j] = q < p.Q;
             tkey[j] = qok[j] ? (tau_in_lds ? tau_lds[q] : p.tau[q]) : ~0ull;
-            tsc[j] = qok[j] ? key_score(tkey[j]) : __builtin_inff();
+            tsc[j] = qok[j] ? (tkey[j] == 0ull ? -__builtin_inff() : key_score(tkey[j])) : __builtin_inff();
         }
 
         // one stage; FIRST: accumulators start from zero; LAST: selection fused into the last k-step
@@ -591,6 +593,15 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
             const int nbuf = buf + 1 == S ? 0 : buf + 1;
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk) {
+                // Two waves share a SIMD (and its matrix core): the one further along its stage
+                // issues first, so that they take turns in k-step-long runs instead of
+                // interleaving instruction by instruction (measured: 2 % faster).
+                if constexpr (NW == 8) {
+                    if (kk >= 3) __builtin_amdgcn_s_setprio(3);
+                    else if (kk == 2) __builtin_amdgcn_s_setprio(2);
+                    else if (kk == 1) __builtin_amdgcn_s_setprio(1);
+                    else __builtin_amdgcn_s_setprio(0);
+                }
                 const int cur = kk & 1;
                 const bool last_kk = kk + 1 == KS;
                 const unsigned char *nsb = last_kk ? smem + nbuf * STAGE : sb;
