@@ -15,6 +15,7 @@
 //                       after a retrieved one), skipping ids already cached, first in first
 //                       out once the cache is full.
 #include <atomic>
+#include <type_traits>
 
 #include "ralm_common.h"
 #include "ralm_kernels.h"
@@ -25,7 +26,7 @@ namespace {
 
 constexpr int CL_GS = 16;          // lanes that share one cached row
 constexpr int CL_ROWS = 64 / CL_GS;   // rows per wave step
-constexpr int CL_LDS_BYTES = 56 * 1024;
+constexpr int CL_LDS_BYTES = 100 * 1024;   // queries of a request, widened to double
 
 __device__ __forceinline__ void clamp_range(const int64_t *off, int64_t r, int64_t Qt, int64_t &lo, int64_t &hi)
 {
@@ -35,9 +36,56 @@ __device__ __forceinline__ void clamp_range(const int64_t *off, int64_t r, int64
     hi = hi < lo ? lo : (hi > Qt ? Qt : hi);
 }
 
+// elements (c*CL_GS + sub)*4 .. +4 of a cached row, c = 0 .. NCH-1, widened exactly to fp32 (zeros
+// for a missing row and past d)
+template <int EX, int NCH>
+__device__ __forceinline__ void cl_load_row(float4 (&x)[NCH], const void *__restrict__ exact, int64_t ld, int32_t id,
+                                            bool ok, int sub, int d)
+{
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int j = (c * CL_GS + sub) * 4;
+        x[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ok && j < d) {
+            if constexpr (EX == DT_F32) {
+                x[c] = *reinterpret_cast<const float4 *>(static_cast<const float *>(exact) + (int64_t)id * ld + j);
+            } else {
+                const uint2 h = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(exact) + (int64_t)id * ld + j);
+                x[c] = make_float4(f16_bits_to_f32(h.x & 0xffffu), f16_bits_to_f32(h.x >> 16),
+                                   f16_bits_to_f32(h.y & 0xffffu), f16_bits_to_f32(h.y >> 16));
+            }
+        }
+    }
+}
+
+// sum over the 16 lanes of a row (every lane gets it): lane exchanges through DPP (a shuffle
+// through LDS costs ~100 cycles of latency per level, and this runs once per row and query)
+template <int CTRL>
+__device__ __forceinline__ double dpp_mov_f64(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double row16_sum(double v)
+{
+    v += dpp_mov_f64<0xB1>(v);    // quad_perm [1,0,3,2]: lane ^ 1
+    v += dpp_mov_f64<0x4E>(v);    // quad_perm [2,3,0,1]: lane ^ 2
+    v += dpp_mov_f64<0x141>(v);   // row_half_mirror: the other quad of the 8 (quads are uniform by now)
+    v += dpp_mov_f64<0x140>(v);   // row_mirror: the other half of the 16
+    return v;
+}
+
+constexpr int CL_QB = 4;   // queries scored together (independent sums hide the latency of the adds)
+static_assert(CL_QB == 4, "the remainder switch in cache_lookup_kernel covers 1..3");
+
 // NCH = float4 chunks of a row held by one lane (row element (c*CL_GS + sub)*4 .. +4).
-// One block of NW waves per request: every wave step gathers CL_ROWS cached rows, so a block
-// has NW*CL_ROWS random row reads in flight; the other waves' arithmetic hides their latency.
+// One block of NW waves per request.  A wave step scores CL_ROWS cached rows against all of the
+// request's queries: the rows are gathered from the exact copy (while the previous rows are
+// being scored: the loads of the next step are issued first), widened to double ONCE, and every
+// query, kept in LDS as doubles, costs one fused multiply-add per element on top of that;
+// CL_QB queries are scored together, whose independent sums hide the latency of the adds, and
+// the 16 lane sums of a row meet through DPP.
 // L2: the score is minus the squared distance (KNN-LM datastores) instead of the inner product.
 template <int EX, int NCH, int NW, bool L2>
 __global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
@@ -47,8 +95,9 @@ __global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
     int32_t *__restrict__ spec_ids, float *__restrict__ spec_scores, u64 *__restrict__ partial)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    float *qs = reinterpret_cast<float *>(smem);                   // [qgroup][d]
-    u64 *best = reinterpret_cast<u64 *>(qs + (size_t)qgroup * d);   // [NW waves][CL_ROWS][qgroup]
+    const int dq = (d + 63) & ~63;                                  // a query's doubles in LDS
+    double *qs = reinterpret_cast<double *>(smem);                  // [qgroup][dq], see below
+    u64 *best = reinterpret_cast<u64 *>(qs + (size_t)qgroup * dq);  // [NW waves][CL_ROWS][qgroup]
 
     // gridDim.y workgroups share a request (few requests: spread each over many CUs); they then
     // merge their best keys with a 64-bit atomic max in `partial`, decoded by a second kernel
@@ -61,66 +110,97 @@ __global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
     int len = cache_len[r];
     len = len < 0 ? 0 : (len > C ? C : len);
     const int32_t *ids = cache_ids + r * (int64_t)C;
+    const int e_step = parts * NW * CL_ROWS;
 
     for (int64_t g0 = q_lo; g0 < q_hi; g0 += qgroup) {
         const int nq = (int)((q_hi - g0) < qgroup ? (q_hi - g0) : qgroup);
         __syncthreads();
-        for (int i = tid * 4; i < nq * d; i += NW * 256)
-            *reinterpret_cast<float4 *>(qs + i) = *reinterpret_cast<const float4 *>(queries + g0 * d + i);
+        // A lane scores elements (c*16 + sub)*4 .. +3 of a row.  The query's elements are laid
+        // out so that, for one c, the first two of the 16 lanes' four are contiguous (256 bytes),
+        // then the last two: the two 16-byte reads of a lane are then free of bank conflicts.
+        for (int i = tid * 4; i < nq * d; i += NW * 256) {
+            const int qi = i / d, j = i - qi * d;
+            const float4 y = *reinterpret_cast<const float4 *>(queries + g0 * d + i);
+            double *dst = qs + (size_t)qi * dq + ((j >> 6) * 64) + ((j >> 2) & 15) * 2;
+            dst[0] = (double)y.x;
+            dst[1] = (double)y.y;
+            dst[32] = (double)y.z;
+            dst[33] = (double)y.w;
+        }
         for (int i = tid; i < NW * CL_ROWS * qgroup; i += NW * 64) best[i] = 0ull;
         __syncthreads();
         u64 *my_best = best + (wave * CL_ROWS + slot) * qgroup;
 
-        for (int e0 = (part * NW + wave) * CL_ROWS; e0 < len; e0 += parts * NW * CL_ROWS) {
-            const int e = e0 + slot;
-            const int32_t id = e < len ? ids[e] : -1;
-            const bool ok = id >= 0 && (int64_t)id < N;
-            float4 x[NCH];
+        int e0 = (part * NW + wave) * CL_ROWS;
+        float4 xn[NCH];   // the next step's rows, in flight while this step's are scored
+        int32_t id_n = e0 + slot < len ? ids[e0 + slot] : -1;
+        bool ok_n = id_n >= 0 && (int64_t)id_n < N;
+        cl_load_row<EX, NCH>(xn, exact, ld, id_n, ok_n, sub, d);
+        for (; e0 < len; e0 += e_step) {
+            const int32_t id = id_n;
+            const bool ok = ok_n;
+            double x[NCH][4];
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
-                const int j = (c * CL_GS + sub) * 4;
-                x[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (ok && j < d) {
-                    if constexpr (EX == DT_F32) {
-                        x[c] = *reinterpret_cast<const float4 *>(static_cast<const float *>(exact) +
-                                                                 (int64_t)id * ld + j);
-                    } else {
-                        const uint2 h = *reinterpret_cast<const uint2 *>(
-                            static_cast<const uint16_t *>(exact) + (int64_t)id * ld + j);
-                        x[c] = make_float4(f16_bits_to_f32(h.x & 0xffffu), f16_bits_to_f32(h.x >> 16),
-                                           f16_bits_to_f32(h.y & 0xffffu), f16_bits_to_f32(h.y >> 16));
-                    }
-                }
+                x[c][0] = (double)xn[c].x;
+                x[c][1] = (double)xn[c].y;
+                x[c][2] = (double)xn[c].z;
+                x[c][3] = (double)xn[c].w;
             }
-            for (int qi = 0; qi < nq; ++qi) {
-                const float *qv = qs + (size_t)qi * d;
-                double sum = 0.0;
+            const int e_n = e0 + e_step + slot;
+            id_n = e_n < len ? ids[e_n] : -1;
+            ok_n = id_n >= 0 && (int64_t)id_n < N;
+            cl_load_row<EX, NCH>(xn, exact, ld, id_n, ok_n, sub, d);
+
+            // U queries q0 .. q0+U-1 against this step's rows
+            auto score = [&](auto u_tag, int q0) __attribute__((always_inline)) {
+                constexpr int U = decltype(u_tag)::value;
+                const double *qv[U];
+                double sum[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    qv[u] = qs + (size_t)(q0 + u) * dq + sub * 2;
+                    sum[u] = 0.0;
+                }
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
-                    const int j = (c * CL_GS + sub) * 4;
-                    if (j < d) {
-                        const float4 y = *reinterpret_cast<const float4 *>(qv + j);
-                        if constexpr (L2) {
-                            const double d0 = (double)y.x - (double)x[c].x, d1 = (double)y.y - (double)x[c].y;
-                            const double d2 = (double)y.z - (double)x[c].z, d3 = (double)y.w - (double)x[c].w;
-                            sum += d0 * d0;
-                            sum += d1 * d1;
-                            sum += d2 * d2;
-                            sum += d3 * d3;
-                        } else {
-                            sum += (double)x[c].x * (double)y.x;
-                            sum += (double)x[c].y * (double)y.y;
-                            sum += (double)x[c].z * (double)y.z;
-                            sum += (double)x[c].w * (double)y.w;
+                    if ((c * CL_GS + sub) * 4 < d) {
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const double2 y01 = *reinterpret_cast<const double2 *>(qv[u] + c * 64);
+                            const double2 y23 = *reinterpret_cast<const double2 *>(qv[u] + c * 64 + 32);
+                            if constexpr (L2) {
+                                const double d0 = y01.x - x[c][0], d1 = y01.y - x[c][1];
+                                const double d2 = y23.x - x[c][2], d3 = y23.y - x[c][3];
+                                sum[u] += d0 * d0;
+                                sum[u] += d1 * d1;
+                                sum[u] += d2 * d2;
+                                sum[u] += d3 * d3;
+                            } else {
+                                sum[u] += x[c][0] * y01.x;
+                                sum[u] += x[c][1] * y01.y;
+                                sum[u] += x[c][2] * y23.x;
+                                sum[u] += x[c][3] * y23.y;
+                            }
                         }
                     }
                 }
 #pragma unroll
-                for (int o = CL_GS / 2; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
-                if (sub == 0 && ok) {
-                    const u64 key = make_key(L2 ? (float)(-sum) : (float)sum, id);
-                    if (key > my_best[qi]) my_best[qi] = key;
+                for (int u = 0; u < U; ++u) {
+                    const double t = row16_sum(sum[u]);
+                    if (sub == 0 && ok) {
+                        const u64 key = make_key(L2 ? (float)(-t) : (float)t, id);
+                        if (key > my_best[q0 + u]) my_best[q0 + u] = key;
+                    }
                 }
+            };
+            int q0 = 0;
+            for (; q0 + CL_QB <= nq; q0 += CL_QB) score(std::integral_constant<int, CL_QB>{}, q0);
+            switch (nq - q0) {   // the rest, with as many sums as there are queries left
+                case 3: score(std::integral_constant<int, 3>{}, q0); break;
+                case 2: score(std::integral_constant<int, 2>{}, q0); break;
+                case 1: score(std::integral_constant<int, 1>{}, q0); break;
+                default: break;
             }
         }
         __syncthreads();
@@ -374,20 +454,31 @@ hipError_t launch_cache_ex(const int32_t *cache_ids, const int32_t *cache_len, i
                            int64_t ld, int64_t N, int32_t d, int32_t *spec_ids, float *spec_scores,
                            u64 *partial, int parts, hipStream_t stream)
 {
-    int qgroup = CL_LDS_BYTES / (d * 4);
+    int qgroup = CL_LDS_BYTES / (((d + 63) & ~63) * 8);
     if (qgroup > 16) qgroup = 16;
     if (qgroup < 1) return hipErrorInvalidValue;
     const int nch = (d + CL_GS * 4 - 1) / (CL_GS * 4);
-    // a lane keeps its NCH chunks in registers, which bounds the waves a block can hold
+    // a lane keeps its NCH chunks in registers (as doubles, and the next rows' as floats), which
+    // bounds the waves a block can hold
 #define RALM_CL(NCHV, NWV)                                                                                  \
-    hipLaunchKernelGGL((cache_lookup_kernel<EX, NCHV, NWV, L2>), dim3((unsigned)R, (unsigned)parts),         \
-                       dim3(NWV * 64),                                                                      \
-                       (size_t)qgroup * d * 4 + (size_t)NWV * CL_ROWS * qgroup * sizeof(u64), stream,       \
-                       cache_ids, cache_len, C, queries, Qt, q_offsets, exact, ld, N, d, qgroup, spec_ids,  \
-                       spec_scores, partial)
+    do {                                                                                                    \
+        auto kern = cache_lookup_kernel<EX, NCHV, NWV, L2>;                                                 \
+        static std::atomic<bool> attr_done{false};                                                          \
+        if (!attr_done.load(std::memory_order_acquire)) {                                                   \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                        \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);     \
+            if (e != hipSuccess) return e;                                                                  \
+            attr_done.store(true, std::memory_order_release);                                               \
+        }                                                                                                   \
+        hipLaunchKernelGGL(kern, dim3((unsigned)R, (unsigned)parts), dim3(NWV * 64),                        \
+                           (size_t)qgroup * ((d + 63) & ~63) * 8 + (size_t)NWV * CL_ROWS * qgroup * sizeof(u64),   \
+                           stream,                                                                          \
+                           cache_ids, cache_len, C, queries, Qt, q_offsets, exact, ld, N, d, qgroup, spec_ids, \
+                           spec_scores, partial);                                                           \
+    } while (0)
     if (nch <= 4) RALM_CL(4, 16);
-    else if (nch <= 8) RALM_CL(8, 16);
-    else if (nch <= 12) RALM_CL(12, 16);
+    else if (nch <= 8) RALM_CL(8, 8);
+    else if (nch <= 12) RALM_CL(12, 8);
     else if (nch <= 16) RALM_CL(16, 8);
     else if (nch <= 32) RALM_CL(32, 4);
     else return hipErrorInvalidValue;
