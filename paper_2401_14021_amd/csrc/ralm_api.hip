@@ -139,6 +139,9 @@ ralm_status check_datastore(const ralm_datastore_t *ds, bool need_scan)
     if (es < ds->d) return fail(RALM_ERR_SHAPE, "exact_stride < d");
     if (!aligned16(ds->exact) || (es * elem_bytes(ds->exact_dtype)) % 16)
         return fail(RALM_ERR_ALIGN, "exact copy: base and row pitch must be multiples of 16 bytes");
+    // without a scan copy the exact copy is scanned, and the scan's 24-bit offset arithmetic applies to it
+    if (need_scan && !ds->scan && es * elem_bytes(ds->exact_dtype) >= (1 << 24))
+        return fail(RALM_ERR_SHAPE, "exact_stride: row pitch of a scanned copy must be below 16 MiB");
     if (ds->metric != RALM_METRIC_IP && ds->metric != RALM_METRIC_L2) return fail(RALM_ERR_DTYPE, "metric unknown");
     if (need_scan && ds->metric == RALM_METRIC_L2) {
         if (!ds->scan) return fail(RALM_ERR_NULL, "the squared-distance metric needs a scan copy built by ralm_build_scan_copy_l2");
@@ -428,11 +431,13 @@ ralm_status ralm_retrieve_topk(const float *queries, int64_t Q, const float *dat
     std::lock_guard<std::mutex> lock(g_simple_mutex);
     if (!simple_reserve(&g_simple_ws, &g_simple_ws_bytes, pl.total))
         return fail(RALM_ERR_DEVICE, "no device memory for %zu bytes of workspace", pl.total);
-    // Scanning fp32 rows directly reads twice the bytes through the slower staged kernel; a
-    // bf16 copy (one read, one write, redone on every call: the rows may have changed) pays for
-    // itself within the same call.  If the device has no room for it the rows are scanned as
-    // they are: same result either way, the staged kernel rounds to bf16 on the fly.
-    if (simple_reserve(&g_simple_scan, &g_simple_scan_bytes, (size_t)N * d * 2) &&
+    // Batches of up to 64 queries are limited by HBM either way: the scan streams the fp32 rows
+    // as they are (one pass over 4 bytes per element beats a conversion pass plus a scan of the
+    // copy) and no copy is held.  Larger batches are limited by the matrix cores, which the
+    // pipelined bf16 kernel feeds far better: they get a bf16 copy (one read, one write, redone on
+    // every call: the rows may have changed), kept between calls; if the device has no room for
+    // it the rows are scanned as they are by the staged kernel.  Same result either way.
+    if (Q > 64 && simple_reserve(&g_simple_scan, &g_simple_scan_bytes, (size_t)N * d * 2) &&
         launch_convert_rows(datastore, d, g_simple_scan, RALM_BF16, d, N, d, nullptr) == hipSuccess) {
         ds.scan = g_simple_scan;
         ds.scan_dtype = RALM_BF16;

@@ -337,13 +337,26 @@ __global__ __launch_bounds__(256) void scan_staged_kernel(const ScanParams p, co
 // LDS chunk swizzle: row r of a strip stores its global 16-byte chunk c at chunk slot c ^ swz(r).
 // Chosen so that 8 or 16 consecutive rows reading the same global chunk touch distinct
 // 16-byte bank groups, for both 128 B and 256 B of LDS banking.
-template <int BK>
+// CPR = 16-byte chunks per strip row: 4 (64-byte rows), 8 (128-byte rows) or 16 (256-byte rows).
+template <int CPR>
 __device__ __forceinline__ int swz(int r)
 {
-    if constexpr (BK == 64)
+    static_assert(CPR == 4 || CPR == 8 || CPR == 16, "strip row of 64, 128 or 256 bytes");
+    if constexpr (CPR == 16)
+        return r & 15;
+    else if constexpr (CPR == 8)
         return (r ^ (r >> 3)) & 7;
     else
         return ((r >> 2) & 1) | ((((r >> 1) ^ (r >> 3)) & 1) << 1);
+}
+
+// eight fp32 values (two 16-byte chunks) -> eight bf16, round to nearest even, as an MFMA operand
+__device__ __forceinline__ uint4 round8_bf16(const uint4 &lo, const uint4 &hi)
+{
+    typedef float f32x8 __attribute__((ext_vector_type(8)));
+    const f32x8 f = {__uint_as_float(lo.x), __uint_as_float(lo.y), __uint_as_float(lo.z), __uint_as_float(lo.w),
+                     __uint_as_float(hi.x), __uint_as_float(hi.y), __uint_as_float(hi.z), __uint_as_float(hi.w)};
+    return __builtin_bit_cast(uint4, __builtin_convertvector(f, bf16x8));
 }
 
 // 64 lanes x 16 bytes, from  base + per-lane byte offset,  to 1 KB of LDS starting at lds_base
@@ -392,17 +405,24 @@ constexpr int PARK_CAP = 672;         // parked admitted scores per workgroup (1
 // sits in k-step RK, behind that k-step's operand reads; the query part of the new strip is
 // requested after it in the same k-step, the datastore part in the next k-step.  RK = KS - 2 is
 // the k-step whose reads are the stage's last, which D = S needs.
-template <bool F16, int WM, int WN, int TM, int TN, int BK, int S, bool NTA, int D = S - 1, int RK = 0>
+//
+// A32: the datastore rows are fp32 (a datastore scanned as it is).  They travel to LDS as they
+// are, twice the bytes per strip row, and are rounded to bf16 between the operand read and the
+// multiply (two 16-byte reads and four conversions per operand instead of one read).
+template <bool F16, int WM, int WN, int TM, int TN, int BK, int S, bool NTA, int D = S - 1, int RK = 0,
+          bool A32 = false>
 __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams p, const int nqt, const int tau_in_lds)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    constexpr int ROWB = BK * 2;                 // bytes of one strip row
-    constexpr int CPR = BK / 8;                  // 16-byte chunks per strip row
-    constexpr int RPI = 64 / CPR;                // rows covered by one wave load
+    constexpr int ESA = A32 ? 4 : 2;                       // bytes of a datastore element
+    constexpr int ROWB_A = BK * ESA, ROWB_B = BK * 2;      // bytes of one strip row (datastore, queries)
+    constexpr int CPR_A = ROWB_A / 16, CPR_B = ROWB_B / 16;   // 16-byte chunks per strip row
+    constexpr int RPI_A = 64 / CPR_A, RPI_B = 64 / CPR_B;  // rows covered by one wave load
     constexpr int NW = WM * WN, NT = NW * 64;     // waves (4: one per SIMD, 8: two per SIMD), threads
-    constexpr int NA = BM / RPI / NW, NB = BN / RPI / NW;   // wave loads per wave and stage
+    constexpr int NA = BM / RPI_A / NW, NB = BN / RPI_B / NW;   // wave loads per wave and stage
     constexpr int LPS = NA + NB;
-    constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
+    constexpr int A_BYTES = BM * ROWB_A, B_BYTES = BN * ROWB_B, STAGE = A_BYTES + B_BYTES;
+    static_assert(!(A32 && F16), "fp32 rows are rounded to bf16");
     constexpr int KS = BK / 16;
     constexpr int NM = TM * TN, NR = TM + TN;
     constexpr int LAG = NM > 2 ? 2 : NM - 1;     // selection runs this many MFMAs behind
@@ -428,7 +448,8 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int fr = lane & 31;
-    const int l_r = lane / CPR, l_c = lane % CPR;
+    const int la_r = lane / CPR_A, la_c = lane % CPR_A;   // row and chunk of this lane in a wave load
+    const int lb_r = lane / CPR_B, lb_c = lane % CPR_B;
 
     // item indices fit 32 bits: at most 2^23 row tiles times a few query tiles (host checks)
     const int G = (int)gridDim.x;
@@ -445,7 +466,7 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     if (n_mine == 0) return;
     const unsigned char *Xb = static_cast<const unsigned char *>(p.X);
     const unsigned char *Qb = reinterpret_cast<const unsigned char *>(p.Qs);
-    const uint32_t ldx2 = (uint32_t)p.ldx * 2u, dpad2 = (uint32_t)p.dpad * 2u;
+    const uint32_t ldx2 = (uint32_t)p.ldx * (uint32_t)ESA, dpad2 = (uint32_t)p.dpad * 2u;   // row pitches in bytes
     const int32_t n_rows = (int32_t)p.N;
 
     if (tid == 0) *pl.count = 0;
@@ -456,16 +477,16 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     // per-lane constants of the loads: byte offset (tile row, swizzled chunk) of each wave load
     // inside a strip that lies fully inside the datastore; strips at its edges are clamped instead
     uint32_t a_voff[NA], b_voff[NB];
-    auto a_tile_row = [&](int j) __attribute__((always_inline)) { return (uint32_t)((wave * NA + j) * RPI + l_r); };
+    auto a_tile_row = [&](int j) __attribute__((always_inline)) { return (uint32_t)((wave * NA + j) * RPI_A + la_r); };
     auto a_tile_chunk = [&](int j) __attribute__((always_inline)) {
-        return (uint32_t)((l_c ^ swz<BK>((int)a_tile_row(j) & 15)) << 4);
+        return (uint32_t)((la_c ^ swz<CPR_A>((int)a_tile_row(j) & 15)) << 4);
     };
 #pragma unroll
     for (int j = 0; j < NA; ++j) a_voff[j] = __umul24(a_tile_row(j), ldx2) + a_tile_chunk(j);   // row < 2^8, ldx2 < 2^24
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-        const int row = (wave * NB + j) * RPI + l_r;
-        b_voff[j] = (uint32_t)row * dpad2 + (uint32_t)((l_c ^ swz<BK>(row & 15)) << 4);
+        const int row = (wave * NB + j) * RPI_B + lb_r;
+        b_voff[j] = (uint32_t)row * dpad2 + (uint32_t)((lb_c ^ swz<CPR_B>(row & 15)) << 4);
     }
     // (row tile, query tile) of an item advance by (G / nqt, G % nqt) from one item of this
     // workgroup to its next: no division in the loop
@@ -489,17 +510,17 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
                 row0 = p.N - 1;
                 left = 0;
             }
-            is_abase = Xb + row0 * p.ldx * 2;
+            is_abase = Xb + row0 * p.ldx * ESA;
             is_bbase = Qb + (int64_t)is_qt * BN * p.dpad * 2;
             is_rowmax = (uint32_t)(left < BM - 1 ? left : BM - 1);
         }
         // chunks past d re-read the row's last valid one (the query side is zero there): inside a
         // strip by clamping the chunk offset, for a strip that lies past d entirely by stepping
         // the strip's base back to that chunk
-        const int kleft = (p.d - 8 - is_kt * BK) * 2;
-        is_kmax = (uint32_t)(kleft < 0 ? 0 : (kleft < ROWB - 16 ? kleft : ROWB - 16));
+        const int kleft = (p.d - 16 / ESA - is_kt * BK) * ESA;   // the row's last chunk, from the strip's start
+        is_kmax = (uint32_t)(kleft < 0 ? 0 : (kleft < ROWB_A - 16 ? kleft : ROWB_A - 16));
         is_aload = is_abase + (kleft < 0 ? kleft : 0);
-        is_inside = is_rowmax == (uint32_t)(BM - 1) && kleft >= ROWB - 16;
+        is_inside = is_rowmax == (uint32_t)(BM - 1) && kleft >= ROWB_A - 16;
         is_lds = lds0 + is_buf * STAGE + wave * (NA * 1024);
     };
     auto issue_part = [&](int idx) __attribute__((always_inline)) {
@@ -518,8 +539,8 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
         }
     };
     auto issue_end = [&]() __attribute__((always_inline)) {
-        is_abase += ROWB;
-        is_bbase += ROWB;
+        is_abase += ROWB_A;
+        is_bbase += ROWB_B;
         is_buf = is_buf + 1 == S ? 0 : is_buf + 1;
         if (++is_kt == KT) {
             is_kt = 0;
@@ -539,22 +560,31 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
         issue_end();
     }
 
-    // Operand read offsets of this lane inside a stage (bytes) for k-step 0.  K-step kk reads the
-    // chunks 2 kk and 2 kk + 1 of a row, i.e. chunk slot (2 kk + lane / 32) ^ swz: its offset is the
-    // k-step 0 offset with 32 kk XOR-ed in (the row part is a multiple of the row size, above it).
-    const int sw0 = ((lane >> 5) ^ swz<BK>(fr & 15)) << 4;
-    const int a_off0 = (wm * TM * 32 + fr) * ROWB + sw0;
-    const int b_off0 = A_BYTES + (wn * TN * 32 + fr) * ROWB + sw0;
-    static_assert((KS - 1) * 32 < ROWB && A_BYTES % ROWB == 0, "k-step offset stays inside the row");
+    // Operand read offsets of this lane inside a stage (bytes) for k-step 0.  A lane multiplies the
+    // 8 elements 16 kk + 8 (lane / 32) .. of its row in k-step kk: one 16-byte chunk of 2-byte
+    // elements, chunk slot (2 kk + lane / 32) ^ swz, or the two chunks 4 kk + 2 (lane / 32), + 1 of
+    // fp32 rows.  Either way the k-step's offset is the k-step 0 offset with (16 kk elements, in
+    // bytes) XOR-ed in: the row part is a multiple of the row size and lies above those bits.
+    const int hi = lane >> 5;
+    const int a_off0 = (wm * TM * 32 + fr) * ROWB_A + (((A32 ? 2 * hi : hi) ^ swz<CPR_A>(fr & 15)) << 4);
+    const int b_off0 = A_BYTES + (wn * TN * 32 + fr) * ROWB_B + ((hi ^ swz<CPR_B>(fr & 15)) << 4);
+    static_assert((KS - 1) * 16 * ESA < ROWB_A && (KS - 1) * 32 < ROWB_B && A_BYTES % ROWB_B == 0,
+                  "k-step offset stays inside the row");
     uint4 fa[2][TM], fb[2][TN];
     auto read_frag = [&](int slot, const unsigned char *sbase, int kk, int idx) __attribute__((always_inline)) {
         // in the order the MFMAs need them: A0, all of B, then A1..
         if (idx == 0 || idx > TN) {
             const int i = idx == 0 ? 0 : idx - TN;
-            fa[slot][i] = *reinterpret_cast<const uint4 *>(sbase + (a_off0 ^ (kk << 5)) + i * 32 * ROWB);
+            const unsigned char *at = sbase + (a_off0 ^ (kk * 16 * ESA)) + i * 32 * ROWB_A;
+            if constexpr (A32)
+                fa[slot][i] = round8_bf16(*reinterpret_cast<const uint4 *>(at),
+                                          *reinterpret_cast<const uint4 *>(sbase + ((a_off0 ^ (kk * 16 * ESA)) ^ 16) +
+                                                                           i * 32 * ROWB_A));
+            else
+                fa[slot][i] = *reinterpret_cast<const uint4 *>(at);
         } else {
             const int j = idx - 1;
-            fb[slot][j] = *reinterpret_cast<const uint4 *>(sbase + (b_off0 ^ (kk << 5)) + j * 32 * ROWB);
+            fb[slot][j] = *reinterpret_cast<const uint4 *>(sbase + (b_off0 ^ (kk << 5)) + j * 32 * ROWB_B);
         }
     };
 
@@ -728,14 +758,15 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     wait_vmcnt<0>();   // the run-ahead loads must land before this workgroup's LDS is released
 }
 
-template <bool F16, int WM, int WN, int TM, int TN, int BK, int S, bool NTA, int D = S - 1, int RK = 0>
+template <bool F16, int WM, int WN, int TM, int TN, int BK, int S, bool NTA, int D = S - 1, int RK = 0,
+          bool A32 = false>
 hipError_t launch_dma_variant(const ScanParams &p, int n_cu, hipStream_t stream)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    constexpr size_t ring = (size_t)S * (BM + BN) * BK * 2;
+    constexpr size_t ring = (size_t)S * (BM * (A32 ? 4 : 2) + BN * 2) * BK;
     constexpr size_t smem = ring + (size_t)tau_lds_q(BN) * 8 + (size_t)PARK_CAP * 12 + 16 + WM * WN * SLOW_SLOTS * 64;
     static_assert(smem <= 160 * 1024, "LDS budget");
-    auto kern = scan_dma_kernel<F16, WM, WN, TM, TN, BK, S, NTA, D, RK>;
+    auto kern = scan_dma_kernel<F16, WM, WN, TM, TN, BK, S, NTA, D, RK, A32>;
     const int tau_in_lds = p.Q <= tau_lds_q(BN) ? 1 : 0;
     static std::atomic<bool> attr_done{false};   // per instantiation; setting it twice is harmless
     if (!attr_done.load(std::memory_order_acquire)) {
@@ -826,7 +857,13 @@ hipError_t launch_scan(const ScanParams &p, int n_cu, hipStream_t stream)
     // Launches whose thresholds admit everything (the first, tiny stage of the ladder) append
     // nearly every score: they take the staged kernel, whose epilogue writes to the global lists
     // with one atomic per lane and block.  fp32 rows always do (they are rounded on the way in).
-    if (p.in_dtype == DT_F32) return launch_in<DT_F32>(p, n_cu, stream);
+    if (p.in_dtype == DT_F32) {
+        // fp32 rows: small batches (limited by HBM) stream them as they are and round on the way to
+        // the matrix cores; larger ones are better served by a bf16 copy and take the staged kernel
+        if (p.park_pushes && p.Q <= 32) return launch_dma_variant<false, 4, 1, 1, 1, 64, 4, true, 3, 0, true>(p, n_cu, stream);
+        if (p.park_pushes && p.Q <= 64) return launch_dma_variant<false, 4, 1, 1, 2, 64, 3, true, 3, 2, true>(p, n_cu, stream);
+        return launch_in<DT_F32>(p, n_cu, stream);
+    }
     if (!p.park_pushes) return p.in_dtype == DT_F16 ? launch_in<DT_F16>(p, n_cu, stream) : launch_in<DT_BF16>(p, n_cu, stream);
     return p.in_dtype == DT_F16 ? launch_dma<true>(p, n_cu, stream) : launch_dma<false>(p, n_cu, stream);
 }

@@ -96,6 +96,32 @@ def test_clustered_real_valued(B, oracle, scan_dtype, N, d, Q, k):
     assert LAST_COUNTERS["exact_pass"] == 0        # k' = 64 leaves a margin far above the scan's rounding
 
 
+@pytest.mark.parametrize("N,d,Q,k", [(70001, 768, 3, 20), (9000, 72, 40, 5), (33000, 136, 64, 64), (5000, 768, 100, 7)])
+def test_fp32_rows_scanned_as_they_are(B, oracle, N, d, Q, k):
+    """No scan copy: the scan streams the fp32 rows and rounds them to bf16 on the way to the
+    matrix cores (batches of up to 64 queries take the pipelined kernel, larger ones the staged
+    one).  Integer-valued rows must come out bit-exact, real-valued ones under the usual rule."""
+    from paper_2401_14021_amd import inputs
+    g = torch.Generator().manual_seed(N + d + Q)
+    X = torch.randint(-3, 4, (N, d), generator=g).float()
+    Qm = torch.randint(-3, 4, (Q, d), generator=g).float()
+    ds = B.Datastore(X.cuda(), None)
+    ws = B.alloc_workspace(Q, ds, k)
+    ids, sc = B.ralm_retrieve_topk_ex(Qm.cuda(), ds, k, workspace=ws)
+    c = B.ralm_workspace_counters(ws)
+    assert c["unanswered"] == 0 and c["exact_pass"] == 0 and c["ladder_overflows"] == 0, c
+    wi, wsc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), k)
+    assert np.array_equal(ids.cpu().numpy(), wi) and np.array_equal(sc.cpu().numpy(), wsc)
+    X, _ = inputs.clustered_datastore(N, d, 32, seed=N + d)
+    Qm = inputs.queries_near_rows(X, inputs.pick_rows(N, Q, seed=5), seed=6)
+    ds = B.Datastore(X.cuda(), None)
+    ids, sc = B.ralm_retrieve_topk_ex(Qm.cuda(), ds, k, workspace=ws)
+    assert B.ralm_workspace_counters(ws)["unanswered"] == 0
+    wi, wsc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), k)
+    exact, subs, total = check_topk(ids.cpu().numpy(), sc.cpu().numpy(), wi, wsc, _score_fn(oracle, Qm.numpy(), X.numpy()))
+    assert exact >= 0.99 * total
+
+
 def test_simple_form_fp32_datastore(B, oracle):
     from paper_2401_14021_amd import inputs
     X, _ = inputs.clustered_datastore(30000, 768, 32, seed=77)
