@@ -252,6 +252,82 @@ def main():
                   "note": "caches start empty; k = 20 retrieval and top-20 update with the verified steps; "
                           "queries drift N(0, 0.02^2 I) and are renormalised every round"}
 
+    # ---- asynchronous verification (stress workload only) ---------------------------------------
+    # The batched retrieval of one step on stream A, the cache lookup of the next speculation step
+    # on stream B (Section 3 "Asynchronous verification"; Section 4: (s-1) a + max(a, b) instead of
+    # s a + b).  a = lookup alone, b = retrieval alone, then both at once, without and with 8
+    # compute units (one per XCD) left free by the scan's persistent grid.
+    async_out = None
+    if args.workload == "specloop":
+        b = hb
+        q_next = inputs.drift_queries(b["Qm"], seed=w.seed + 999)
+        sA, sB = torch.cuda.Stream(), torch.cuda.Stream()
+        spec2 = torch.empty_like(b["spec"])
+        spec2_sc = torch.empty_like(b["spec_sc"])
+
+        def ev():
+            return torch.cuda.Event(enable_timing=True)
+
+        def timed(fn, stream, reps=5):
+            e0, e1 = ev(), ev()
+            with torch.cuda.stream(stream):
+                fn()
+                e0.record()
+                for _ in range(reps):
+                    fn()
+                e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        def retrieve():
+            B.ralm_retrieve_topk_ex(b["Qm"], ds, k, w.k_prime, workspace=b["ws"], out_ids=b["ids"], out_scores=b["sc"])
+
+        def lookup():
+            B.ralm_cache_lookup(b["cids"], b["clen"], q_next, b["off"], ds, spec2, spec2_sc, workspace=b["cl_ws"])
+
+        # a spin kernel that holds stream B back until the scan is under way (calibrated here)
+        torch.cuda._sleep(1000)
+        c0, c1 = ev(), ev()
+        c0.record()
+        torch.cuda._sleep(1_000_000)
+        c1.record()
+        torch.cuda.synchronize()
+        spin_per_ms = 1_000_000 / max(c0.elapsed_time(c1), 1e-3)
+        delay_ms = 5.0
+        async_out = {"lookup_issued_ms_after_retrieval": delay_ms,
+                     "note": "a, b measured alone; overlapped = makespan of the retrieval on stream A and a lookup issued "
+                             "on stream B 5 ms later (held back by a one-thread spin kernel, which itself occupies a "
+                             "compute unit: with no reserve one scan workgroup starts that much later)"}
+        for reserve in (0, 8):
+            B.ralm_scan_reserve_cus(reserve)
+            a_ms, b_ms = timed(lookup, sB), timed(retrieve, sA)
+            both, look = [], []
+            for _ in range(5):
+                torch.cuda.synchronize()
+                g0, a1, b0, b1 = ev(), ev(), ev(), ev()
+                g0.record()
+                sA.wait_event(g0)
+                sB.wait_event(g0)
+                with torch.cuda.stream(sA):
+                    retrieve()
+                    a1.record()
+                with torch.cuda.stream(sB):
+                    torch.cuda._sleep(int(delay_ms * spin_per_ms))
+                    b0.record()
+                    lookup()
+                    b1.record()
+                torch.cuda.synchronize()
+                both.append(max(g0.elapsed_time(a1), g0.elapsed_time(b1)))
+                look.append(b0.elapsed_time(b1))
+            both.sort()
+            look.sort()
+            async_out[f"reserve_{reserve}_cus"] = {
+                "lookup_alone_ms_a": round(a_ms, 3), "retrieval_alone_ms_b": round(b_ms, 3),
+                "serial_ms_a_plus_b": round(a_ms + b_ms, 3), "model_ms_max_a_b": round(max(a_ms, b_ms), 3),
+                "overlapped_ms": round(both[len(both) // 2], 3),
+                "lookup_latency_under_scan_ms": round(look[len(look) // 2], 3)}
+        B.ralm_scan_reserve_cus(0)
+
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
     # The same sample is also answered by the library (over the same prefix of the datastore)
     # and compared with the oracle rank by rank: exact matches, near-tie substitutions (a
@@ -331,6 +407,8 @@ def main():
     }
     if closed:
         out["closed_loop"] = closed
+    if async_out:
+        out["async_verification"] = async_out
     out["exactness"] = cert
     if parity:
         out["parity_vs_oracle_sample"] = parity

@@ -448,6 +448,21 @@ int32_t ralm_os3_next_stride(const int32_t *strides, const int32_t *matched, int
                              double gamma_max, int32_t s_max, int32_t async);
 
 /*
+ * Asynchronous verification (Section 3, "Asynchronous verification"; latency
+ * model of Section 4: a verification that overlaps the next speculation step
+ * costs (s-1) a + max(a, b) instead of s a + b).  Every call here is ordered on
+ * the caller's stream only, so the batched retrieval of step t and the cache
+ * lookup of step t+1 can be issued on two streams.  The scan, however, runs as
+ * a persistent grid with one workgroup per compute unit whose LDS it fills, so
+ * a kernel on another stream finds no free unit until a scan launch ends.
+ * ralm_scan_reserve_cus(n) makes every later retrieval call of the process
+ * leave n compute units free (n = 8: one per XCD; 0 restores the default); the
+ * scan slows down by about n / 256 and the other stream's kernels run beside
+ * it.  Process-wide setting, read when a call is issued.
+ */
+void ralm_scan_reserve_cus(int32_t n);
+
+/*
  * Timing aid for benchmarks.  While enabled, ralm_retrieve_topk_ex brackets
  * each launch of its scan kernel (a call makes several: together they read
  * every row of the datastore exactly once) with HIP events on the call's

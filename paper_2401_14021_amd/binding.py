@@ -91,6 +91,8 @@ def lib() -> ctypes.CDLL:
         L.ralm_os3_next_stride.restype = i32
         L.ralm_release_buffers.argtypes = []
         L.ralm_release_buffers.restype = None
+        L.ralm_scan_reserve_cus.argtypes = [i32]
+        L.ralm_scan_reserve_cus.restype = None
         L.ralm_profile_enable.argtypes = [i32]
         L.ralm_profile_enable.restype = None
         L.ralm_profile_scan_ms.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
@@ -381,6 +383,11 @@ def ralm_os3_next_stride(strides, matched, a_samples, b_samples, s_max: int, gam
     b = (ctypes.c_double * max(len(b_samples), 1))(*[float(v) for v in b_samples])
     return int(lib().ralm_os3_next_stride(s, m, w, a, len(a_samples), b, len(b_samples), gamma_max, s_max,
                                           1 if asynchronous else 0))
+
+
+def ralm_scan_reserve_cus(n: int) -> None:
+    """Compute units that later retrieval calls leave free for kernels on other streams."""
+    lib().ralm_scan_reserve_cus(int(n))
 
 
 def ralm_profile_enable(on: bool) -> None:

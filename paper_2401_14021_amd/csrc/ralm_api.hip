@@ -14,6 +14,7 @@
 //      a representative sample, so a stage admits only about k'*(g-1) scores per query.
 //   3. the k' keys left in each list are re-scored from the exact copy and ranked.
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <mutex>
 #include <stdarg.h>
 #include <stdio.h>
@@ -177,6 +178,9 @@ int device_cus()
     return cus;
 }
 
+// compute units that the scan's persistent grids leave free (ralm_scan_reserve_cus)
+std::atomic<int> g_scan_reserve{0};
+
 // ---- scan timing aid ------------------------------------------------------------------------
 constexpr int MAX_PROF = 2048;
 bool g_prof_on = false;
@@ -243,7 +247,9 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
     const int64_t scan_ld = ds->scan ? (ds->scan_stride ? ds->scan_stride : scan_cols(ds))
                                      : (ds->exact_stride ? ds->exact_stride : ds->d);
     const int mma_dt = scan_dt == RALM_F16 ? RALM_F16 : RALM_BF16;   // fp32 rows are rounded to bf16
-    const int n_cu = device_cus();
+    // the scan's grids are persistent: one workgroup per CU (two for the small tiles), minus the reserve
+    int n_cu = device_cus() - g_scan_reserve.load(std::memory_order_relaxed);
+    if (n_cu < 8) n_cu = 8;
 
     RALM_HIP(launch_query_prep(queries, Q, ds->d, qs, pl.Qpad, pl.dpad, mma_dt, ds->metric, stream));
     RALM_HIP(launch_fill_u64(tau, 0ull, pl.Qpad, stream));
@@ -664,6 +670,11 @@ ralm_status ralm_verify(const int32_t *spec_ids, const int32_t *true_ids, int64_
     RALM_HIP(launch_verify(spec_ids, true_ids, true_stride, Qt, q_offsets, R, first_mismatch,
                            static_cast<hipStream_t>(stream)));
     return RALM_OK;
+}
+
+void ralm_scan_reserve_cus(int32_t n)
+{
+    g_scan_reserve.store(n < 0 ? 0 : n, std::memory_order_relaxed);
 }
 
 void ralm_profile_enable(int32_t on)
