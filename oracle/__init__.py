@@ -24,7 +24,9 @@ _SRC = os.path.join(_HERE, "ralm_oracle.c")
 _LIB = os.path.join(_HERE, "libralm_oracle.so")
 
 F32, BF16, F16 = 0, 1, 2
-METRICS = {"ip": 0, "l2": 1}   # inner product; minus the squared Euclidean distance
+# inner product; minus the squared Euclidean distance; inner product accumulated the other plausible
+# way (products and running sum rounded to fp32, left to right), for counting reading-dependent answers
+METRICS = {"ip": 0, "l2": 1, "ip_f32_sequential": 2}
 _lib = None
 
 

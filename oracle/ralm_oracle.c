@@ -126,11 +126,29 @@ static float neg_sq_distance(const float *q, const void *X, int dtype, int64_t r
     return (float)(-sum);
 }
 
-enum { ORACLE_IP = 0, ORACLE_L2 = 1 };
+/*
+ * The other plausible reading of "fp32 inner product" (the paper does not say how
+ * its retriever accumulates): every product rounded to fp32, the d products
+ * added left to right in fp32.  Not what the library computes; kept so that
+ * tests can count how many answers depend on the reading (only near-ties do).
+ */
+static float inner_product_f32_sequential(const float *q, const void *X, int dtype, int64_t row,
+                                          int64_t ld, int32_t d)
+{
+    volatile float sum = 0.0f;   /* volatile: every partial sum is rounded to fp32, never kept wider */
+    for (int32_t c = 0; c < d; ++c) {
+        volatile float prod = q[c] * element(X, dtype, row * ld + c);
+        sum = sum + prod;
+    }
+    return sum;
+}
+
+enum { ORACLE_IP = 0, ORACLE_L2 = 1, ORACLE_IP_F32_SEQUENTIAL = 2 };
 
 static float score_of(int metric, const float *q, const void *X, int dtype, int64_t row, int64_t ld,
                       int32_t d)
 {
+    if (metric == ORACLE_IP_F32_SEQUENTIAL) return inner_product_f32_sequential(q, X, dtype, row, ld, d);
     return metric == ORACLE_L2 ? neg_sq_distance(q, X, dtype, row, ld, d)
                                : inner_product(q, X, dtype, row, ld, d);
 }

@@ -687,3 +687,33 @@ def test_cache_lookup_topk_rank_preservation(oracle):
     lens = np.full(4, 30, dtype=np.int32)
     ids, sc = oracle.cache_lookup_topk(cache, lens, Qm, off, X, 8)
     assert np.array_equal(ids, top) and np.array_equal(sc, top_sc)
+
+
+def test_sequential_fp32_accumulation_mode(oracle):
+    """The oracle's second reading of "fp32 inner product": products and running sum rounded to
+    fp32, left to right.  Pinned against the same recurrence in numpy float32 scalars; on integer
+    data (every step exact) it must equal the double-accumulation reading; on real data the two
+    readings differ in the last bits of scores, and in ids only at near-ties."""
+    rng = np.random.default_rng(77)
+    N, d, k = 3000, 40, 10
+    X = rng.standard_normal((N, d)).astype(np.float32)
+    Qm = rng.standard_normal((3, d)).astype(np.float32)
+    got = oracle.scores(Qm[0], X[:50], "ip_f32_sequential")
+    for j in range(50):
+        acc = np.float32(0)
+        for c in range(d):
+            acc = np.float32(acc + np.float32(Qm[0, c] * X[j, c]))
+        assert got[j] == acc
+    Xi = rng.integers(-3, 4, size=(N, d)).astype(np.float32)
+    Qi = rng.integers(-3, 4, size=(3, d)).astype(np.float32)
+    a = oracle.retrieve_topk(Qi, Xi, k)
+    b = oracle.retrieve_topk(Qi, Xi, k, metric="ip_f32_sequential")
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    ia, sa = oracle.retrieve_topk(Qm, X, k)
+    ib, sb = oracle.retrieve_topk(Qm, X, k, metric="ip_f32_sequential")
+    assert np.allclose(sa, sb, rtol=1e-5, atol=1e-5)
+    differ = ia != ib
+    # where the two readings disagree on an id, the double-accumulated scores at that rank are a near-tie
+    for i, r in zip(*np.nonzero(differ)):
+        other = oracle.scores(Qm[i], X[[ib[i, r]]])[0]
+        assert abs(other - sa[i, r]) <= 1e-5 * max(abs(sa[i, r]), 1e-30)
