@@ -148,7 +148,6 @@ enum { ORACLE_IP = 0, ORACLE_L2 = 1, ORACLE_IP_F32_SEQUENTIAL = 2 };
 static float score_of(int metric, const float *q, const void *X, int dtype, int64_t row, int64_t ld,
                       int32_t d)
 {
-    if (metric == ORACLE_IP_F32_SEQUENTIAL) return inner_product_f32_sequential(q, X, dtype, row, ld, d);
     return metric == ORACLE_L2 ? neg_sq_distance(q, X, dtype, row, ld, d)
                                : inner_product(q, X, dtype, row, ld, d);
 }
@@ -177,6 +176,12 @@ int ralm_oracle_threads(void)
 void ralm_oracle_scores_metric(const float *q, const void *X, int dtype, int64_t n, int32_t d,
                                int64_t ld, int metric, float *scores)
 {
+    if (metric == ORACLE_IP_F32_SEQUENTIAL) {
+#pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < n; ++j)
+            scores[j] = inner_product_f32_sequential(q, X, dtype, j, ld, d);
+        return;
+    }
 #pragma omp parallel for schedule(static)
     for (int64_t j = 0; j < n; ++j)
         scores[j] = score_of(metric, q, X, dtype, j, ld, d);
@@ -202,10 +207,18 @@ int ralm_oracle_retrieve_topk_metric(const float *queries, int64_t Q, const void
     if (!all) return -1;
     for (int64_t i = 0; i < Q; ++i) {
         const float *q = queries + i * (int64_t)d;
+        if (metric == ORACLE_IP_F32_SEQUENTIAL) {
 #pragma omp parallel for schedule(static)
-        for (int64_t j = 0; j < N; ++j) {
-            all[j].score = score_of(metric, q, X, dtype, j, ld, d);
-            all[j].id = (int32_t)j;
+            for (int64_t j = 0; j < N; ++j) {
+                all[j].score = inner_product_f32_sequential(q, X, dtype, j, ld, d);
+                all[j].id = (int32_t)j;
+            }
+        } else {
+#pragma omp parallel for schedule(static)
+            for (int64_t j = 0; j < N; ++j) {
+                all[j].score = score_of(metric, q, X, dtype, j, ld, d);
+                all[j].id = (int32_t)j;
+            }
         }
         qsort(all, (size_t)N, sizeof(scored_t), by_score_then_id);
         for (int32_t r = 0; r < k; ++r) {

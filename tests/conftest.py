@@ -17,3 +17,15 @@ def oracle():
     import oracle as _oracle
     _oracle.build()
     return _oracle
+
+
+@pytest.fixture(scope="session")
+def progress(request):
+    """say(msg): one line on the terminal past pytest's capture (the full-size tests run for
+    minutes; a runner that watches for output must see that they are alive)."""
+    capman = request.config.pluginmanager.getplugin("capturemanager")
+
+    def say(msg):
+        with capman.global_and_fixture_disabled():
+            print(msg, flush=True)
+    return say

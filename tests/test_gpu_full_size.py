@@ -61,7 +61,7 @@ def test_medium_batched_verification_every_query(B, oracle):
 
 
 @pytest.fixture(scope="module")
-def dense21m(B):
+def dense21m(B, progress):
     """21M x 768: the fp32 rows on the device (with their bf16 scan copy) and the very same bytes
     on the host for the oracle, copied back once."""
     from paper_2401_14021_amd import inputs
@@ -70,7 +70,7 @@ def dense21m(B):
     _, assign = inputs.clustered_datastore(w.N, w.d, w.n_clusters, w.seed, device="cuda", out=X)
     ds = B.Datastore.from_fp32(X)
     torch.cuda.synchronize()
-    print("dense21m: generated; copying the rows to the host ...", flush=True)
+    progress("dense21m: generated; copying the rows to the host ...")
     Xh = np.empty((w.N, w.d), dtype=np.float32)
     for r0 in range(0, w.N, CHUNK):
         r1 = min(w.N, r0 + CHUNK)
@@ -80,8 +80,10 @@ def dense21m(B):
     torch.cuda.empty_cache()
 
 
-def _host_chunks(Xh):
+def _host_chunks(Xh, say=None):
     for r0 in range(0, Xh.shape[0], CHUNK):
+        if say and (r0 // CHUNK) % 3 == 0:
+            say(f"oracle at row {r0} of {Xh.shape[0]}")
         yield r0, Xh[r0:r0 + CHUNK]
 
 
@@ -92,12 +94,12 @@ def _check_sample(oracle, Xh, qnp, k, got_ids, got_sc, want):
                       lambda i, g: oracle.scores(qnp[i], Xh[np.asarray(g, dtype=np.int64)]))
 
 
-def test_dense21m_sampled_queries(B, oracle, dense21m):
+def test_dense21m_sampled_queries(B, oracle, dense21m, progress):
     """21M x 768 bf16 scan + fp32 re-score, Q in {1, 8, 64, 256, 1024}, k in {1, 20}.  The oracle
-    ranks all 21M rows for 128 seeded queries: positions of the 1024-batch spread over its four
-    256-query tiles and all wave columns (64 of them in the first 256).  The first 64 of them ARE
+    ranks all 21M rows for 96 seeded queries: positions of the 1024-batch spread over its four
+    256-query tiles and all wave columns (48 of them in the first 256).  The first 64 of them ARE
     the batches of 1, 8 and 64 (every query checked); the batches of 256 and 1024 are prefixes of
-    the 1024 queries (64 and 128 of their queries checked).  Whatever the batch, a query's result must
+    the 1024 queries (48 and 96 of their queries checked).  Whatever the batch, a query's result must
     be the oracle's; margins must clear the scan's rounding by a wide factor at these sizes."""
     from paper_2401_14021_amd import inputs
     w, X, assign, ds, Xh = dense21m
@@ -105,17 +107,16 @@ def test_dense21m_sampled_queries(B, oracle, dense21m):
     rows = inputs.pick_rows(w.N, Qmax, seed=w.seed + 1)
     Qm = inputs.queries_near_rows(X, rows.cuda(), seed=w.seed + 2)
     g = torch.Generator().manual_seed(w.seed + 3)
-    first = torch.randperm(256, generator=g)[:64]
-    rest = 256 + torch.randperm(768, generator=g)[:64]
+    first = torch.randperm(256, generator=g)[:48]
+    rest = 256 + torch.randperm(768, generator=g)[:48]
     # the first 64 sampled positions (32 + 32) make up the small batches
     sample = torch.cat([first[:32], rest[:32], first[32:], rest[32:]]).tolist()
     for t in range(4):                                # every 256-query tile is sampled
-        assert sum(1 for i in sample if i // 256 == t) >= 10
-    assert len({(i % 256) // 64 for i in sample}) == 4 and len(set(sample)) == 128
+        assert sum(1 for i in sample if i // 256 == t) >= 8
+    assert len({(i % 256) // 64 for i in sample}) == 4 and len(set(sample)) == 96
     qs = Qm[sample].cpu().numpy()
-    print("dense21m: oracle ranks 21M rows for 128 queries ...", flush=True)
-    want = oracle.retrieve_topk_stream(qs, _host_chunks(Xh), 20)
-    print("dense21m: oracle done", flush=True)
+    progress("dense21m: the oracle ranks 21M rows for 96 queries ...")
+    want = oracle.retrieve_topk_stream(qs, _host_chunks(Xh, progress), 20)
     assert (want[1][:, 0] >= 0.5).all()               # the source row (or a better one) is found
     total_subs = 0
     for Q in (1, 8, 64, 256, 1024):
@@ -136,7 +137,7 @@ def test_dense21m_sampled_queries(B, oracle, dense21m):
             exact, subs, total = _check_sample(oracle, Xh, qs[here], k, ids.cpu().numpy()[pos], sc.cpu().numpy()[pos],
                                                (want[0][here], want[1][here]))
             total_subs += subs
-            assert len(here) >= min(Q, 64)
+            assert len(here) >= min(Q, 48)
             # every query, at any size: ids in range, distinct, scores ordered, margin clear of the
             # rounding of a bf16 scan of unit vectors (8 sigma of a noise model: 0.4 u |q||x| / sqrt(d)
             # per score)
@@ -150,7 +151,7 @@ def test_dense21m_sampled_queries(B, oracle, dense21m):
     assert total_subs <= 2          # near-tie substitutions over all checked (query, batch, k) cases
 
 
-def test_specloop_closed_loop_100_steps_full_size(B, oracle, dense21m):
+def test_specloop_closed_loop_100_steps_full_size(B, oracle, dense21m, progress):
     """Speculation loop stress shape, closed: 512 requests with their own 4096-entry caches that
     start EMPTY, strides uniform in 1..8 (about 2300 queries); per step a cache top-1 lookup, one
     batched exact top-1 retrieval, the first-mismatch compare and the top-1 cache update with the
@@ -195,7 +196,7 @@ def test_specloop_closed_loop_100_steps_full_size(B, oracle, dense21m):
         # integer stages against the oracle, everything
         assert np.array_equal(m_h, oracle.verify(spec_h, ids_h.reshape(-1), off_h, 1)), step
         if step in (0, 1, 10, 50, 99):
-            print(f"specloop: step {step}, hit rate {hit_rates[-1]:.2f}, oracle on 16 queries ...", flush=True)
+            progress(f"specloop: step {step}, hit rate {hit_rates[-1]:.2f}, the oracle ranks 21M rows for 16 queries ...")
             qnp = Qm.cpu().numpy()
             sample_q = torch.randperm(Q, generator=g)[:16].tolist()
             want = oracle.retrieve_topk_stream(qnp[sample_q], _host_chunks(Xh), 1)

@@ -23,14 +23,14 @@ def B():
     return binding
 
 
-def _stream_chunks(exact):
+def _stream_chunks(exact, say):
     """The keys, widened exactly to fp32 on the device (every fp16 value is an fp32 value), copied
     back in row chunks: the oracle then scores fp32 rows, which is what it does with fp16 rows
     after its own widening (pinned bit for bit on all 65536 patterns), only faster."""
     N = exact.shape[0]
     for r0 in range(0, N, CHUNK):
-        if (r0 // CHUNK) % 16 == 0:
-            print(f"knnlm100m: oracle at row {r0}", flush=True)
+        if (r0 // CHUNK) % 8 == 0:
+            say(f"knnlm100m: oracle at row {r0} of {N}")
         yield r0, exact[r0:min(N, r0 + CHUNK)].float().cpu().numpy()
 
 
@@ -41,7 +41,7 @@ def _score_of_rows(oracle, exact, queries_np):
     return f
 
 
-def test_knnlm_100m_fp16_large_k_sampled_queries(B, oracle):
+def test_knnlm_100m_fp16_large_k_sampled_queries(B, oracle, progress):
     """KNN-LM datastore shape at full size: 100M x 1024 fp16 keys resident in HBM (they are their
     own scan copy and the truth), 256 queries, k = 1024 (k' = 2048).  The oracle ranks all 100M
     keys for eight seeded queries (two per 64-query wave column of the 256-query tile) by
@@ -72,7 +72,7 @@ def test_knnlm_100m_fp16_large_k_sampled_queries(B, oracle):
     sample = [3, 40, 77, 100, 150, 180, 200, 251]
     assert sorted((i // 64 for i in sample)) == [0, 0, 1, 1, 2, 2, 3, 3]
     qs = Qm[sample].cpu().numpy()
-    wi, wsc = oracle.retrieve_topk_stream(qs, _stream_chunks(keys), w.k)
+    wi, wsc = oracle.retrieve_topk_stream(qs, _stream_chunks(keys, progress), w.k)
     exact, subs, total = check_topk(ids.cpu().numpy()[sample], sc.cpu().numpy()[sample], wi, wsc,
                                     _score_of_rows(oracle, keys, qs))
     assert exact >= 0.98 * total
