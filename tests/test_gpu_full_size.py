@@ -96,10 +96,10 @@ def _check_sample(oracle, Xh, qnp, k, got_ids, got_sc, want):
 
 def test_dense21m_sampled_queries(B, oracle, dense21m, progress):
     """21M x 768 bf16 scan + fp32 re-score, Q in {1, 8, 64, 256, 1024}, k in {1, 20}.  The oracle
-    ranks all 21M rows for 96 seeded queries: positions of the 1024-batch spread over its four
-    256-query tiles and all wave columns (48 of them in the first 256).  The first 64 of them ARE
+    ranks all 21M rows for 128 seeded queries: positions of the 1024-batch spread over its four
+    256-query tiles and all wave columns (64 of them in the first 256).  The first 64 of them ARE
     the batches of 1, 8 and 64 (every query checked); the batches of 256 and 1024 are prefixes of
-    the 1024 queries (48 and 96 of their queries checked).  Whatever the batch, a query's result must
+    the 1024 queries (64 and 128 of their queries checked).  Whatever the batch, a query's result must
     be the oracle's; margins must clear the scan's rounding by a wide factor at these sizes."""
     from paper_2401_14021_amd import inputs
     w, X, assign, ds, Xh = dense21m
@@ -107,15 +107,15 @@ def test_dense21m_sampled_queries(B, oracle, dense21m, progress):
     rows = inputs.pick_rows(w.N, Qmax, seed=w.seed + 1)
     Qm = inputs.queries_near_rows(X, rows.cuda(), seed=w.seed + 2)
     g = torch.Generator().manual_seed(w.seed + 3)
-    first = torch.randperm(256, generator=g)[:48]
-    rest = 256 + torch.randperm(768, generator=g)[:48]
+    first = torch.randperm(256, generator=g)[:64]
+    rest = 256 + torch.randperm(768, generator=g)[:64]
     # the first 64 sampled positions (32 + 32) make up the small batches
     sample = torch.cat([first[:32], rest[:32], first[32:], rest[32:]]).tolist()
     for t in range(4):                                # every 256-query tile is sampled
-        assert sum(1 for i in sample if i // 256 == t) >= 8
-    assert len({(i % 256) // 64 for i in sample}) == 4 and len(set(sample)) == 96
+        assert sum(1 for i in sample if i // 256 == t) >= 10
+    assert len({(i % 256) // 64 for i in sample}) == 4 and len(set(sample)) == 128
     qs = Qm[sample].cpu().numpy()
-    progress("dense21m: the oracle ranks 21M rows for 96 queries ...")
+    progress("dense21m: the oracle ranks 21M rows for 128 queries ...")
     want = oracle.retrieve_topk_stream(qs, _host_chunks(Xh, progress), 20)
     assert (want[1][:, 0] >= 0.5).all()               # the source row (or a better one) is found
     total_subs = 0
@@ -137,7 +137,7 @@ def test_dense21m_sampled_queries(B, oracle, dense21m, progress):
             exact, subs, total = _check_sample(oracle, Xh, qs[here], k, ids.cpu().numpy()[pos], sc.cpu().numpy()[pos],
                                                (want[0][here], want[1][here]))
             total_subs += subs
-            assert len(here) >= min(Q, 48)
+            assert len(here) >= min(Q, 64)
             # every query, at any size: ids in range, distinct, scores ordered, margin clear of the
             # rounding of a bf16 scan of unit vectors (8 sigma of a noise model: 0.4 u |q||x| / sqrt(d)
             # per score)
@@ -156,7 +156,7 @@ def test_specloop_closed_loop_100_steps_full_size(B, oracle, dense21m, progress)
     start EMPTY, strides uniform in 1..8 (about 2300 queries); per step a cache top-1 lookup, one
     batched exact top-1 retrieval, the first-mismatch compare and the top-1 cache update with the
     verified steps; queries drift between steps; 100 steps.  Integer stages (compare, update) are
-    checked against the oracle on everything at every step; the retrieval on 16 seeded queries and
+    checked against the oracle on everything at every step; the retrieval on 24 seeded queries and
     the cache lookup on 3 seeded requests at steps 0, 1, 10, 50 and 99; rank preservation
     (Section 3) on every query at every step."""
     from paper_2401_14021_amd import inputs
@@ -196,9 +196,9 @@ def test_specloop_closed_loop_100_steps_full_size(B, oracle, dense21m, progress)
         # integer stages against the oracle, everything
         assert np.array_equal(m_h, oracle.verify(spec_h, ids_h.reshape(-1), off_h, 1)), step
         if step in (0, 1, 10, 50, 99):
-            progress(f"specloop: step {step}, hit rate {hit_rates[-1]:.2f}, the oracle ranks 21M rows for 16 queries ...")
+            progress(f"specloop: step {step}, hit rate {hit_rates[-1]:.2f}, the oracle ranks 21M rows for 24 queries ...")
             qnp = Qm.cpu().numpy()
-            sample_q = torch.randperm(Q, generator=g)[:16].tolist()
+            sample_q = torch.randperm(Q, generator=g)[:24].tolist()
             want = oracle.retrieve_topk_stream(qnp[sample_q], _host_chunks(Xh), 1)
             _check_sample(oracle, Xh, qnp[sample_q], 1, ids_h[sample_q], sc.cpu().numpy()[sample_q], want)
             # cache lookup of sampled requests (the state before this step's update = the oracle's)
