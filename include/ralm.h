@@ -162,7 +162,7 @@ size_t ralm_workspace_bytes(int64_t Q, const ralm_datastore_t *ds, int32_t k, in
  * best k of the rows that reach the exact rank-k score found so far are
  * returned, which is the exact top k by construction.  The pass is skipped
  * when no query needs it; it reads the exact copy once per 8 such queries
- * (about 10 ms per 8 queries for 21M x 768 fp32).  With k_prime = k there is
+ * (21M x 768 fp32: about 13 ms for one query, 26 ms for 8).  With k_prime = k there is
  * no margin to speak of and nearly every query takes that pass.
  * ralm_workspace_counters reports how many did.
  *

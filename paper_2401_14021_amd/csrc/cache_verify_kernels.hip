@@ -58,24 +58,6 @@ __device__ __forceinline__ void cl_load_row(float4 (&x)[NCH], const void *__rest
     }
 }
 
-// sum over the 16 lanes of a row (every lane gets it): lane exchanges through DPP (a shuffle
-// through LDS costs ~100 cycles of latency per level, and this runs once per row and query)
-template <int CTRL>
-__device__ __forceinline__ double dpp_mov_f64(double v)
-{
-    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
-    return __hiloint2double(hi, lo);
-}
-__device__ __forceinline__ double row16_sum(double v)
-{
-    v += dpp_mov_f64<0xB1>(v);    // quad_perm [1,0,3,2]: lane ^ 1
-    v += dpp_mov_f64<0x4E>(v);    // quad_perm [2,3,0,1]: lane ^ 2
-    v += dpp_mov_f64<0x141>(v);   // row_half_mirror: the other quad of the 8 (quads are uniform by now)
-    v += dpp_mov_f64<0x140>(v);   // row_mirror: the other half of the 16
-    return v;
-}
-
 constexpr int CL_QB = 4;   // queries scored together (independent sums hide the latency of the adds)
 static_assert(CL_QB == 4, "the remainder switch in cache_lookup_kernel covers 1..3");
 

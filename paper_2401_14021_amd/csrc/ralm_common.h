@@ -71,4 +71,35 @@ __device__ __forceinline__ uint4 pack8(const float4 &a, const float4 &b)
     return r;
 }
 
+// ---- sums of doubles across lanes ------------------------------------------------------------
+// Lane exchanges through DPP and readlane: a shuffle through LDS costs ~100 cycles of latency per
+// level, and these sums sit at the end of every exact score.
+template <int CTRL>
+__device__ __forceinline__ double dpp_mov_f64(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+// sum over the 16 lanes of a row (lanes 16 r .. 16 r + 15); every lane gets its row's sum
+__device__ __forceinline__ double row16_sum(double v)
+{
+    v += dpp_mov_f64<0xB1>(v);    // quad_perm [1,0,3,2]: lane ^ 1
+    v += dpp_mov_f64<0x4E>(v);    // quad_perm [2,3,0,1]: lane ^ 2
+    v += dpp_mov_f64<0x141>(v);   // row_half_mirror: the other quad of the 8 (quads are uniform by now)
+    v += dpp_mov_f64<0x140>(v);   // row_mirror: the other half of the 16
+    return v;
+}
+__device__ __forceinline__ double readlane_f64(double v, int lane)
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane),
+                            __builtin_amdgcn_readlane(__double2loint(v), lane));
+}
+// sum over the 64 lanes of a wave, always in this order; every lane gets it
+__device__ __forceinline__ double wave64_sum(double v)
+{
+    v = row16_sum(v);
+    return (readlane_f64(v, 0) + readlane_f64(v, 16)) + (readlane_f64(v, 32) + readlane_f64(v, 48));
+}
+
 }  // namespace ralm

@@ -156,16 +156,13 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(u64 *__restrict__ c
     }
 }
 
-__device__ __forceinline__ double wave_sum(double x)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
-    return x;
-}
+// every exact score ends in this sum over the wave's 64 lane sums (fixed order: the re-score and
+// the exact pass must give a row the same number)
+__device__ __forceinline__ double wave_sum(double x) { return wave64_sum(x); }
 
-// The exact score, as every kernel of the library forms it: lane l of a wave takes the
+// The exact score, as the re-score and the exact pass form it: lane l of a wave takes the
 // elements 4l .. 4l+3, 256+4l .., adds their products (squared differences) to its sum in that
-// order, and the 64 lane sums are added by a butterfly (wave_sum).  Products and sums in double;
+// order, and the 64 lane sums are added in a fixed order (wave_sum).  Products and sums in double;
 // the caller rounds the total once to fp32.
 template <bool L2>
 __device__ __forceinline__ void exact_accum4(double &sum, const float4 &x, const float4 &y)
@@ -361,8 +358,9 @@ __global__ __launch_bounds__(XS_THREADS) void exact_scan_kernel(const float *__r
                                                                 uint32_t cap)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    float *qs = reinterpret_cast<float *>(smem);   // [qgroup][d]
+    float *qs = reinterpret_cast<float *>(smem);     // [qgroup][d]
     __shared__ u64 s_tau[XS_QG];
+    __shared__ float s_tsc[XS_QG];                   // score part of the bound: a cheap first test
     __shared__ int32_t s_q[XS_QG];
 
     const int F = flags[FLAG_FALLBACKS];
@@ -377,6 +375,7 @@ __global__ __launch_bounds__(XS_THREADS) void exact_scan_kernel(const float *__r
             const int32_t q = fb_list[g0 + tid];
             s_q[tid] = q;
             s_tau[tid] = tau_exact[q];
+            s_tsc[tid] = key_score(tau_exact[q]);
         }
         __syncthreads();
         for (int qi = 0; qi < nq; ++qi) {
@@ -405,8 +404,9 @@ __global__ __launch_bounds__(XS_THREADS) void exact_scan_kernel(const float *__r
             for (int qi = 0; qi < XS_QG; ++qi) {
                 if (qi < nq) {
                     const double t = wave_sum(sum[qi]);
-                    if (lane == 0) {
-                        const u64 key = make_key(L2 ? (float)(-t) : (float)t, (int32_t)row);
+                    const float sc = L2 ? (float)(-t) : (float)t;
+                    if (lane == 0 && sc >= s_tsc[qi]) {   // a key that reaches the bound has a score that does
+                        const u64 key = make_key(sc, (int32_t)row);
                         if (key >= s_tau[qi]) {
                             const int32_t q = s_q[qi];
                             const uint32_t at = atomicAdd(cnt + q, 1u);
