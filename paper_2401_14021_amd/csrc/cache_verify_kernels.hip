@@ -58,8 +58,8 @@ __device__ __forceinline__ void cl_load_row(float4 (&x)[NCH], const void *__rest
     }
 }
 
-constexpr int CL_QB = 4;   // queries scored together (independent sums hide the latency of the adds)
-static_assert(CL_QB == 4, "the remainder switch in cache_lookup_kernel covers 1..3");
+constexpr int CL_QB = 4;    // queries scored together (independent sums hide the latency of the adds)
+static_assert(CL_QB == 4, "the block dispatch in cache_lookup_kernel is written out for blocks of 4");
 
 // NCH = float4 chunks of a row held by one lane (row element (c*CL_GS + sub)*4 .. +4).
 // One block of NW waves per request.  A wave step scores CL_ROWS cached rows against all of the
@@ -69,7 +69,9 @@ static_assert(CL_QB == 4, "the remainder switch in cache_lookup_kernel covers 1.
 // CL_QB queries are scored together, whose independent sums hide the latency of the adds, and
 // the 16 lane sums of a row meet through DPP.
 // L2: the score is minus the squared distance (KNN-LM datastores) instead of the inner product.
-template <int EX, int NCH, int NW, bool L2>
+// MAXQ (8 or 16): queries of a request held in LDS at a time (more are served in groups); their
+// bests sit in registers, which is why wide rows take 8.
+template <int EX, int NCH, int NW, bool L2, int MAXQ>
 __global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
     const int32_t *__restrict__ cache_ids, const int32_t *__restrict__ cache_len, int C,
     const float *__restrict__ queries, int64_t Qt, const int64_t *__restrict__ q_offsets,
@@ -112,6 +114,15 @@ __global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
         for (int i = tid; i < NW * CL_ROWS * qgroup; i += NW * 64) best[i] = 0ull;
         __syncthreads();
         u64 *my_best = best + (wave * CL_ROWS + slot) * qgroup;
+        // best (score, id) per query so far, in registers of the row's first lane: the comparison
+        // is two float compares, and a key is formed only once, at the end
+        float best_sc[MAXQ];
+        int32_t best_id[MAXQ];
+#pragma unroll
+        for (int i = 0; i < MAXQ; ++i) {
+            best_sc[i] = -__builtin_inff();
+            best_id[i] = -1;
+        }
 
         int e0 = (part * NW + wave) * CL_ROWS;
         float4 xn[NCH];   // the next step's rows, in flight while this step's are scored
@@ -135,8 +146,8 @@ __global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
             cl_load_row<EX, NCH>(xn, exact, ld, id_n, ok_n, sub, d);
 
             // U queries q0 .. q0+U-1 against this step's rows
-            auto score = [&](auto u_tag, int q0) __attribute__((always_inline)) {
-                constexpr int U = decltype(u_tag)::value;
+            auto score = [&](auto u_tag, auto q0_tag) __attribute__((always_inline)) {
+                constexpr int U = decltype(u_tag)::value, q0 = decltype(q0_tag)::value;
                 const double *qv[U];
                 double sum[U];
 #pragma unroll
@@ -170,20 +181,34 @@ __global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const double t = row16_sum(sum[u]);
-                    if (sub == 0 && ok) {
-                        const u64 key = make_key(L2 ? (float)(-t) : (float)t, id);
-                        if (key > my_best[q0 + u]) my_best[q0 + u] = key;
-                    }
+                    const float sc = (L2 ? (float)(-t) : (float)t) + 0.0f;   // -0 counts as +0, as in a key
+                    // higher score, then lower id (ids of missing rows are -1 and never win)
+                    const bool better = ok && (sc > best_sc[q0 + u] || (sc == best_sc[q0 + u] && id < best_id[q0 + u]));
+                    best_sc[q0 + u] = better ? sc : best_sc[q0 + u];
+                    best_id[q0 + u] = better ? id : best_id[q0 + u];
                 }
             };
-            int q0 = 0;
-            for (; q0 + CL_QB <= nq; q0 += CL_QB) score(std::integral_constant<int, CL_QB>{}, q0);
-            switch (nq - q0) {   // the rest, with as many sums as there are queries left
-                case 3: score(std::integral_constant<int, 3>{}, q0); break;
-                case 2: score(std::integral_constant<int, 2>{}, q0); break;
-                case 1: score(std::integral_constant<int, 1>{}, q0); break;
-                default: break;
+            // query blocks of CL_QB, the last one with as many sums as there are queries left
+            // (block starts are compile-time constants: the bests are indexed statically)
+            auto block = [&](auto q0_tag) __attribute__((always_inline)) {
+                constexpr int q0 = decltype(q0_tag)::value;
+                const int left = nq - q0;
+                if (left >= 4) score(std::integral_constant<int, 4>{}, q0_tag);
+                else if (left == 3) score(std::integral_constant<int, 3>{}, q0_tag);
+                else if (left == 2) score(std::integral_constant<int, 2>{}, q0_tag);
+                else if (left == 1) score(std::integral_constant<int, 1>{}, q0_tag);
+            };
+            block(std::integral_constant<int, 0>{});
+            if (nq > 4) block(std::integral_constant<int, 4>{});
+            if constexpr (MAXQ > 8) {
+                if (nq > 8) block(std::integral_constant<int, 8>{});
+                if (nq > 12) block(std::integral_constant<int, 12>{});
             }
+        }
+        if (sub == 0) {
+#pragma unroll
+            for (int i = 0; i < MAXQ; ++i)
+                if (i < nq && best_id[i] >= 0) my_best[i] = make_key(best_sc[i], best_id[i]);
         }
         __syncthreads();
         for (int qi = tid; qi < nq; qi += NW * 64) {
@@ -437,14 +462,15 @@ hipError_t launch_cache_ex(const int32_t *cache_ids, const int32_t *cache_len, i
                            u64 *partial, int parts, hipStream_t stream)
 {
     int qgroup = CL_LDS_BYTES / (((d + 63) & ~63) * 8);
-    if (qgroup > 16) qgroup = 16;
-    if (qgroup < 1) return hipErrorInvalidValue;
     const int nch = (d + CL_GS * 4 - 1) / (CL_GS * 4);
+    const int maxq = nch <= 12 ? 16 : 8;
+    if (qgroup > maxq) qgroup = maxq;
+    if (qgroup < 1) return hipErrorInvalidValue;
     // a lane keeps its NCH chunks in registers (as doubles, and the next rows' as floats), which
     // bounds the waves a block can hold
-#define RALM_CL(NCHV, NWV)                                                                                  \
+#define RALM_CL(NCHV, NWV, MAXQV)                                                                           \
     do {                                                                                                    \
-        auto kern = cache_lookup_kernel<EX, NCHV, NWV, L2>;                                                 \
+        auto kern = cache_lookup_kernel<EX, NCHV, NWV, L2, MAXQV>;                                          \
         static std::atomic<bool> attr_done{false};                                                          \
         if (!attr_done.load(std::memory_order_acquire)) {                                                   \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                        \
@@ -458,11 +484,11 @@ hipError_t launch_cache_ex(const int32_t *cache_ids, const int32_t *cache_len, i
                            cache_ids, cache_len, C, queries, Qt, q_offsets, exact, ld, N, d, qgroup, spec_ids, \
                            spec_scores, partial);                                                           \
     } while (0)
-    if (nch <= 4) RALM_CL(4, 16);
-    else if (nch <= 8) RALM_CL(8, 8);
-    else if (nch <= 12) RALM_CL(12, 8);
-    else if (nch <= 16) RALM_CL(16, 8);
-    else if (nch <= 32) RALM_CL(32, 4);
+    if (nch <= 4) RALM_CL(4, 8, 16);
+    else if (nch <= 8) RALM_CL(8, 8, 16);
+    else if (nch <= 12) RALM_CL(12, 8, 16);
+    else if (nch <= 16) RALM_CL(16, 4, 8);
+    else if (nch <= 32) RALM_CL(32, 4, 8);
     else return hipErrorInvalidValue;
 #undef RALM_CL
     return hipGetLastError();
