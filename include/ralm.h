@@ -29,7 +29,8 @@
  *     ordinary call of the same shapes (the first launch of a kernel sets its
  *     attributes) it may be recorded into a HIP graph and replayed.
  *   - Matrices are row-major.  ids are int32 row numbers of the datastore
- *     (N <= 2^31 - 512); sizes are int64.
+ *     (N <= 2^31 - 512); sizes are int64.  A call takes at most 2^20 queries
+ *     and 2^22 requests (RALM_ERR_SHAPE beyond that).
  *   - The ranking is always (score descending, row id ascending): equal scores
  *     go to the lower id.  The paper does not define ties; this is this
  *     library's rule, at every stage.

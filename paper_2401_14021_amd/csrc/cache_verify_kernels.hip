@@ -416,34 +416,36 @@ __global__ __launch_bounds__(256) void l2_scan_copy_kernel(const void *src, int6
                                                             int in_place)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= N) return;
-    double sum = 0.0;
-    for (int c = lane * 8; c < d; c += 512) {
-        float4 a, b;
-        if constexpr (SRC == DT_F32) {
-            const float *s = static_cast<const float *>(src) + row * src_ld + c;
-            a = *reinterpret_cast<const float4 *>(s);
-            b = *reinterpret_cast<const float4 *>(s + 4);
-        } else {
-            const uint4 h = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(src) + row * src_ld + c);
-            a = make_float4(f16_bits_to_f32(h.x & 0xffffu), f16_bits_to_f32(h.x >> 16),
-                            f16_bits_to_f32(h.y & 0xffffu), f16_bits_to_f32(h.y >> 16));
-            b = make_float4(f16_bits_to_f32(h.z & 0xffffu), f16_bits_to_f32(h.z >> 16),
-                            f16_bits_to_f32(h.w & 0xffffu), f16_bits_to_f32(h.w >> 16));
+    // rows are strided over a bounded grid: one block per four rows would exceed the 2^32 work-items
+    // of a launch from 67M rows on
+    for (int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); row < N; row += (int64_t)gridDim.x * 4) {
+        double sum = 0.0;
+        for (int c = lane * 8; c < d; c += 512) {
+            float4 a, b;
+            if constexpr (SRC == DT_F32) {
+                const float *s = static_cast<const float *>(src) + row * src_ld + c;
+                a = *reinterpret_cast<const float4 *>(s);
+                b = *reinterpret_cast<const float4 *>(s + 4);
+            } else {
+                const uint4 h = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(src) + row * src_ld + c);
+                a = make_float4(f16_bits_to_f32(h.x & 0xffffu), f16_bits_to_f32(h.x >> 16),
+                                f16_bits_to_f32(h.y & 0xffffu), f16_bits_to_f32(h.y >> 16));
+                b = make_float4(f16_bits_to_f32(h.z & 0xffffu), f16_bits_to_f32(h.z >> 16),
+                                f16_bits_to_f32(h.w & 0xffffu), f16_bits_to_f32(h.w >> 16));
+            }
+            sum += (double)a.x * (double)a.x + (double)a.y * (double)a.y + (double)a.z * (double)a.z +
+                   (double)a.w * (double)a.w + (double)b.x * (double)b.x + (double)b.y * (double)b.y +
+                   (double)b.z * (double)b.z + (double)b.w * (double)b.w;
+            if (!in_place) *reinterpret_cast<uint4 *>(dst + row * dst_ld + c) = pack8<DT>(a, b);
         }
-        sum += (double)a.x * (double)a.x + (double)a.y * (double)a.y + (double)a.z * (double)a.z +
-               (double)a.w * (double)a.w + (double)b.x * (double)b.x + (double)b.y * (double)b.y +
-               (double)b.z * (double)b.z + (double)b.w * (double)b.w;
-        if (!in_place) *reinterpret_cast<uint4 *>(dst + row * dst_ld + c) = pack8<DT>(a, b);
-    }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
-    if (lane == 0) {
-        const uint32_t hi = f32_to_scan_bits<DT>((float)sum);
-        const float hi_f = DT == DT_F16 ? f16_bits_to_f32(hi) : __uint_as_float(hi << 16);
-        const uint32_t lo = f32_to_scan_bits<DT>((float)(sum - (double)hi_f));
-        *reinterpret_cast<uint4 *>(dst + row * dst_ld + d) = make_uint4(hi | (lo << 16), 0u, 0u, 0u);
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+        if (lane == 0) {
+            const uint32_t hi = f32_to_scan_bits<DT>((float)sum);
+            const float hi_f = DT == DT_F16 ? f16_bits_to_f32(hi) : __uint_as_float(hi << 16);
+            const uint32_t lo = f32_to_scan_bits<DT>((float)(sum - (double)hi_f));
+            *reinterpret_cast<uint4 *>(dst + row * dst_ld + d) = make_uint4(hi | (lo << 16), 0u, 0u, 0u);
+        }
     }
 }
 
@@ -591,7 +593,8 @@ hipError_t launch_l2_scan_copy(const void *src, int32_t src_dtype, int64_t src_l
 {
     if (N <= 0) return hipSuccess;
     const int in_place = src == dst ? 1 : 0;
-    const dim3 grid((unsigned)((N + 3) / 4)), block(256);
+    const int64_t blocks = (N + 3) / 4;
+    const dim3 grid((unsigned)(blocks < (1 << 20) ? blocks : (1 << 20))), block(256);
     uint16_t *out = static_cast<uint16_t *>(dst);
     if (src_dtype == DT_F16) {
         if (dst_dtype == DT_F16)

@@ -63,6 +63,9 @@ struct Plan {
 };
 
 // columns of a scan-copy row: the squared-distance metric keeps the row's squared norm behind it
+// one workgroup per request (or per four): keeps every launch below 2^32 work-items
+constexpr int64_t MAX_REQUESTS = 1 << 22;
+
 int32_t scan_cols(const ralm_datastore_t *ds) { return ds->d + (ds->metric == RALM_METRIC_L2 ? L2_EXTRA_COLS : 0); }
 
 int32_t default_k_prime(int32_t k)
@@ -507,7 +510,7 @@ ralm_status check_cache_lookup(const int32_t *cache_ids, const int32_t *cache_le
 {
     if (!cache_ids || !cache_len || !queries || !q_offsets || !spec_ids || !spec_scores)
         return fail(RALM_ERR_NULL, "a pointer is NULL");
-    if (R < 0 || R > 0x7fffffffLL || C < 1) return fail(RALM_ERR_SHAPE, "R=%lld, C=%d out of range", (long long)R, C);
+    if (R < 0 || R > MAX_REQUESTS || C < 1) return fail(RALM_ERR_SHAPE, "R=%lld, C=%d out of range", (long long)R, C);
     if (Qt < 0) return fail(RALM_ERR_RANGE, "Qt=%lld is negative", (long long)Qt);
     ralm_status st = check_datastore(ds, false);
     if (st != RALM_OK) return st;
@@ -597,7 +600,7 @@ ralm_status ralm_cache_insert(int32_t *cache_ids, int32_t *cache_len, int32_t *c
 {
     if (!cache_ids || !cache_len || !cache_head || !true_ids || !q_offsets)
         return fail(RALM_ERR_NULL, "a pointer is NULL");
-    if (R < 0 || R > 0x7fffffffLL || C < 1 || C > CACHE_INSERT_MAX_C)
+    if (R < 0 || R > MAX_REQUESTS || C < 1 || C > CACHE_INSERT_MAX_C)
         return fail(RALM_ERR_SHAPE, "R=%lld, C=%d out of range (C <= %d)", (long long)R, C, CACHE_INSERT_MAX_C);
     if (N < 1 || N > 0x7fffffffLL) return fail(RALM_ERR_SHAPE, "N=%lld out of [1, 2^31)", (long long)N);
     if (Qt < 0 || true_stride < 1) return fail(RALM_ERR_RANGE, "Qt >= 0 and true_stride >= 1 required");
@@ -613,7 +616,7 @@ ralm_status ralm_knnlm_probs(const int32_t *ids, const float *scores, int64_t Q,
                              int32_t *out_top_token, float *out_top_prob, void *stream)
 {
     if (!ids || !scores || !values || !out_tokens || !out_weights) return fail(RALM_ERR_NULL, "a pointer is NULL");
-    if (Q < 0 || Q > 0x7fffffffLL) return fail(RALM_ERR_SHAPE, "Q=%lld out of range", (long long)Q);
+    if (Q < 0 || Q > (1 << 20)) return fail(RALM_ERR_SHAPE, "Q=%lld out of [0, 2^20]", (long long)Q);
     if (N < 1 || N > 0x7fffffffLL) return fail(RALM_ERR_SHAPE, "N=%lld out of [1, 2^31)", (long long)N);
     if (k < 1 || k > RALM_MAX_K) return fail(RALM_ERR_K, "k=%d must be in [1, %d]", k, RALM_MAX_K);
     if (!(temperature > 0.f) || !(temperature < __builtin_inff()))
@@ -637,7 +640,7 @@ ralm_status ralm_cache_lookup_topk(const int32_t *cache_ids, const int32_t *cach
 {
     if (!cache_ids || !cache_len || !queries || !q_offsets || !out_ids || !out_scores)
         return fail(RALM_ERR_NULL, "a pointer is NULL");
-    if (R < 0 || R > 0x7fffffffLL || C < 1 || C > RALM_MAX_K_PRIME)
+    if (R < 0 || R > MAX_REQUESTS || C < 1 || C > RALM_MAX_K_PRIME)
         return fail(RALM_ERR_SHAPE, "R=%lld, C=%d out of range (C <= %d)", (long long)R, C, RALM_MAX_K_PRIME);
     if (Qt < 0 || Qt > (1 << 20)) return fail(RALM_ERR_RANGE, "Qt=%lld out of [0, 2^20]", (long long)Qt);
     if (k < 1 || k > RALM_MAX_K || k > C) return fail(RALM_ERR_K, "k=%d must be in [1, min(C, %d)]", k, RALM_MAX_K);
@@ -665,7 +668,7 @@ ralm_status ralm_verify(const int32_t *spec_ids, const int32_t *true_ids, int64_
                         const int64_t *q_offsets, int64_t R, int32_t *first_mismatch, void *stream)
 {
     if (!spec_ids || !true_ids || !q_offsets || !first_mismatch) return fail(RALM_ERR_NULL, "a pointer is NULL");
-    if (R < 0 || R > 0x7fffffffLL) return fail(RALM_ERR_SHAPE, "R=%lld out of range", (long long)R);
+    if (R < 0 || R > MAX_REQUESTS) return fail(RALM_ERR_SHAPE, "R=%lld out of range", (long long)R);
     if (Qt < 0 || true_stride < 1) return fail(RALM_ERR_RANGE, "Qt >= 0 and true_stride >= 1 required");
     RALM_HIP(launch_verify(spec_ids, true_ids, true_stride, Qt, q_offsets, R, first_mismatch,
                            static_cast<hipStream_t>(stream)));

@@ -78,3 +78,51 @@ def test_knnlm_100m_fp16_large_k_sampled_queries(B, oracle, progress):
     assert exact >= 0.98 * total
     del ds, keys
     torch.cuda.empty_cache()
+
+
+def test_knnlm_100m_squared_distance_in_place_norms(B, oracle, progress):
+    """The same datastore ranked by squared distance, as bench.py --workload knnlm100m --metric l2
+    lays it out: rows of 1024 fp16 keys at a pitch of 1088, the squared norms written in place into
+    the 8 columns behind each row (no second copy of 205 GB).  Every query must be certified by
+    the margin check, none handed to the exact pass (a row whose norm columns were not written
+    would out-score every true neighbour and show up exactly there); the oracle ranks all 100M
+    keys by distance for four seeded queries."""
+    from paper_2401_14021_amd import inputs
+    w = inputs.WORKLOADS["knnlm100m"]
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < 245e9:
+        pytest.skip("needs ~225 GB of free HBM")
+    cols = w.d + 64
+    store = torch.empty(w.N, cols, dtype=torch.float16, device="cuda")
+    keys = store[:, :w.d]
+    inputs.knnlm_datastore(w.N, w.d, w.n_clusters, w.seed, device="cuda", out=keys)
+    B._check(B.lib().ralm_build_scan_copy_l2(store.data_ptr(), B.RALM_F16, cols, store.data_ptr(), B.RALM_F16,
+                                             cols, w.N, w.d, None))
+    ds = B.Datastore(keys, store[:, :w.d + 8], B.RALM_METRIC_L2)
+    Q = 256
+    rows = inputs.pick_rows(w.N, Q, seed=w.seed + 1)
+    Qm = inputs.queries_near_rows(keys, rows.cuda(), seed=w.seed + 2, sigma=0.5)
+    # the norm columns of the last rows (the old one-workgroup-per-four-rows launch stopped at 2^32 work-items)
+    tail = store[-4096:]
+    assert torch.allclose(tail[:, w.d].float() + tail[:, w.d + 1].float(),
+                          (tail[:, :w.d].double() ** 2).sum(dim=1).float(), rtol=1e-6)
+    ws = B.alloc_workspace(Q, ds, w.k, w.k_prime)
+    ids, sc = B.ralm_retrieve_topk_ex(Qm, ds, w.k, w.k_prime, workspace=ws)
+    c = B.ralm_workspace_counters(ws)
+    assert c["unanswered"] == 0 and c["ladder_overflows"] == 0 and c["exact_pass"] == 0 and c["soft_certified"] == Q, c
+    assert int(ids.min()) >= 0 and int(ids.max()) < w.N
+    assert bool((sc[:, :-1] >= sc[:, 1:]).all())
+    sample = [17, 90, 130, 222]
+    qs = Qm[sample].cpu().numpy()
+    wi, wsc = oracle.retrieve_topk_stream(qs, _stream_chunks(keys, progress), w.k, metric="l2")
+
+    def score_of(i, r):
+        got = keys[torch.as_tensor(np.asarray(r, dtype=np.int64), device="cuda")].cpu().numpy()
+        return oracle.scores(qs[i], got, "l2")
+    exact, subs, total = check_topk(ids.cpu().numpy()[sample], sc.cpu().numpy()[sample], wi, wsc, score_of)
+    assert exact >= 0.98 * total
+    del ds, keys, store
+    torch.cuda.empty_cache()

@@ -651,6 +651,23 @@ def test_l2_on_fp16_keys_that_are_their_own_scan_copy(B, oracle):
     _check_probs(got, want)
 
 
+def test_l2_norm_columns_of_a_store_with_more_than_2_to_26_rows(B):
+    """One wave writes one row's squared norm; 70M rows are more waves than one launch can hold
+    as separate workgroups (2^32 work-items), so the rows are strided over a bounded grid.  Every
+    row's norm columns are compared with the same sum formed by torch."""
+    N, d = 70_000_000, 8
+    g = torch.Generator(device="cuda").manual_seed(7)
+    store = torch.zeros(N, d + 8, dtype=torch.float16, device="cuda")
+    store[:, :d] = torch.randint(-8, 9, (N, d), generator=g, device="cuda").to(torch.float16)
+    st = B.lib().ralm_build_scan_copy_l2(store.data_ptr(), B.RALM_F16, d + 8, store.data_ptr(), B.RALM_F16, d + 8,
+                                         N, d, None)
+    assert st == 0
+    torch.cuda.synchronize()
+    want = (store[:, :d].float() ** 2).sum(dim=1)            # integers <= 512: exact in fp16 and fp32
+    assert torch.equal(store[:, d].float(), want)
+    assert not bool(store[:, d + 1:].any())
+
+
 @pytest.mark.parametrize("Q", [5, 70, 140])
 def test_padding_columns_behind_the_rows_are_never_used(B, oracle, Q):
     """Both copies are stored with a pitch larger than d and NaN in the spare columns; d = 136 is
