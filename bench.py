@@ -9,7 +9,10 @@ the first-mismatch compare.  Inputs are resident in HBM before the timed region.
 Prints ONE JSON line: queries/s for the headline batch size, the roofline
 figures of the dominant kernel (the full-datastore scan) measured with HIP
 events inside the library, a sweep over the other batch sizes, and the CPU
-oracle timed on a bounded sample of the same workload.
+oracle timed on a bounded sample of the same workload.  The default run adds
+`other_workloads`: a few steps each of the stress loop (512 requests, ragged
+strides) and of the KNN-LM datastore shape (100M x 1024 fp16), measured the
+same way after the headline's tensors have been released.
 """
 from __future__ import annotations
 
@@ -43,11 +46,40 @@ def parse():
                     help="order of the datastore's rows: random cluster order (the headline), sorted by cluster, "
                          "or runs of ~32 rows per cluster (a datastore kept in corpus order)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="default run only: leave out the short runs of the specloop and knnlm100m workloads")
     return ap.parse_args()
 
 
 def main():
     args = parse()
+    out = measure(args)
+    if (args.workload == "dense21m" and not args.N and not args.Q and not args.k and args.metric == "ip"
+            and args.row_order == "iid" and not args.no_other_workloads):
+        # the other full-size configurations, a few steps each, after the headline's tensors are gone
+        import copy
+        import gc
+        import torch
+        out["other_workloads"] = []
+        for name in ("specloop", "knnlm100m"):
+            gc.collect()
+            torch.cuda.empty_cache()
+            a = copy.copy(args)
+            a.workload, a.sweep, a.no_cpu_baseline, a.steps, a.warmup = name, "none", True, min(args.steps, 5), 2
+            o = measure(a)
+            r = o["roofline"]
+            item = {"workload": o["config"]["workload"], "value": o["value"], "unit": o["unit"], "steps": o["steps"],
+                    "ms_per_step": o["ms_per_step"], "dtype": o["dtype"],
+                    "roofline": {key: r[key] for key in ("bound", "achieved", "peak", "unit", "frac", "kernel_ms")},
+                    "exactness": o["exactness"]}
+            for key in ("closed_loop", "async_verification"):
+                if key in o:
+                    item[key] = o[key]
+            out["other_workloads"].append(item)
+    print(json.dumps(out))
+
+
+def measure(args):
     if args.gpus != 1:
         print("bench.py: this build is a one-GPU kernel path; run with --gpus 1 "
               "(sharding the datastore by rows over several GPUs is a design note only, not built)", file=sys.stderr)
@@ -412,7 +444,7 @@ def main():
     out["exactness"] = cert
     if parity:
         out["parity_vs_oracle_sample"] = parity
-    print(json.dumps(out))
+    return out
 
 
 if __name__ == "__main__":
