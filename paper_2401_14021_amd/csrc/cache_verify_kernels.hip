@@ -8,6 +8,8 @@
 //                       one rounding to fp32), so a cached entry gets the same number from
 //                       both and "top-1 of the knowledge base is cached => it is the cache's
 //                       top-1" holds bit for bit.
+//  cache_lookup_mfma_kernel  the same lookup with the sums formed on the fp64 matrix cores
+//                       (inner product, rows that are whole 256-byte steps).
 //  verify_kernel        m = argmin_i (d^_i != d_i) of Alg. 1, per request.
 //  cache_insert_kernel  Q.insert(C.retrieve(..)) of Alg. 1: the ids a verification step
 //                       retrieved go into the request's cache (Section 3 "Batched
@@ -217,6 +219,181 @@ __global__ __launch_bounds__(NW * 64) void cache_lookup_kernel(
                 const u64 v = best[w * qgroup + qi];
                 b = v > b ? v : b;
             }
+            if (partial) {
+                if (b) atomicMax(reinterpret_cast<unsigned long long *>(partial + g0 + qi), b);
+            } else {
+                spec_ids[g0 + qi] = b ? key_id(b) : -1;
+                spec_scores[g0 + qi] = b ? key_score(b) : -__builtin_inff();
+            }
+        }
+    }
+}
+
+// ---- the same lookup on the fp64 matrix cores (inner-product metric) ---------------------------
+// v_mfma_f64_4x4x4 multiplies four independent 4x4x4 blocks: operand A of lane l is element
+// (i = l%4, k = l/16) of block (l/4)%4, operand B element (k = l/16, j = l%4) of that block, and
+// the lane receives D(i = l/16, j = l%4).  Block b takes cached rows 4b .. 4b+3 of a step of 16
+// rows and all blocks take the same 4 queries, so lane l feeds row l%16 and gets the score of row
+// 4*((l/4)%4) + l/16 against query l%4: a step of 16 rows x 4 queries x 4 elements per
+// instruction, sums in double, and no reduction across lanes.  A lane holds elements
+// 4*CH*u + CH*(l/16) .. + CH-1 of its row (CH elements per 16-byte load: whole 64-byte pieces of
+// a row per load instruction); the queries sit in LDS as doubles in the order the instructions
+// consume them ([group of 4][instruction][k][j]: a wave reads 128 contiguous bytes, no bank
+// conflicts).  More than 4 queries: one more instruction per group and element, same row operand.
+constexpr int CM_NW = 8;
+constexpr int CM_MAX_GROUPS = 4;     // groups of 4 queries whose doubles are in LDS at a time
+
+// SEG = 16-byte pieces of a row that a lane has in flight per buffer; it divides the number of
+// pieces per lane and row, d / (4 * CH).
+template <int EX, int SEG>
+__global__ __launch_bounds__(CM_NW * 64) void cache_lookup_mfma_kernel(
+    const int32_t *__restrict__ cache_ids, const int32_t *__restrict__ cache_len, int C,
+    const float *__restrict__ queries, int64_t Qt, const int64_t *__restrict__ q_offsets,
+    const void *__restrict__ exact, int64_t ld, int64_t N, int d, int ng_max,
+    int32_t *__restrict__ spec_ids, float *__restrict__ spec_scores, u64 *__restrict__ partial)
+{
+    constexpr int CH = EX == DT_F32 ? 4 : 8;        // elements per 16-byte piece
+    constexpr int ES = EX == DT_F32 ? 4 : 2;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int T = d / 4;                             // instructions per step and query group
+    double *bq = reinterpret_cast<double *>(smem);   // [ng_max][T][4 k][4 j]
+    u64 *best = reinterpret_cast<u64 *>(bq + (size_t)ng_max * T * 16);   // [4 * ng_max]
+
+    const int64_t r = blockIdx.x;
+    const int part = blockIdx.y, parts = gridDim.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, kq = lane >> 4;            // row of the step and k index this lane feeds
+    const int ro = ((lane >> 2) & 3) * 4 + (lane >> 4);   // row of the step whose score this lane receives
+    const int jq = lane & 3;                              // ... against this query of a group
+    int64_t q_lo, q_hi;
+    clamp_range(q_offsets, r, Qt, q_lo, q_hi);
+    int len = cache_len[r];
+    len = len < 0 ? 0 : (len > C ? C : len);
+    const int32_t *ids = cache_ids + r * (int64_t)C;
+    const int NC = d / (4 * CH);                          // pieces per lane and row
+    const int nsegs = NC / SEG;
+    const int nblk = (len + 15) / 16;
+    const int blk_step = parts * CM_NW;
+    const unsigned char *base = static_cast<const unsigned char *>(exact) + kq * 16;
+
+    for (int64_t g0 = q_lo; g0 < q_hi; g0 += 4 * ng_max) {
+        const int nq = (int)((q_hi - g0) < 4 * ng_max ? (q_hi - g0) : 4 * ng_max);
+        const int n_groups = (nq + 3) >> 2;
+        __syncthreads();
+        for (int i = tid; i < n_groups * 4 * d; i += CM_NW * 64) {
+            const int qi = i / d, e = i - qi * d;
+            const double v = qi < nq ? (double)queries[(g0 + qi) * d + e] : 0.0;
+            const int t = CH * (e / (4 * CH)) + e % CH, k = (e / CH) & 3;
+            bq[((size_t)(qi >> 2) * T + t) * 16 + k * 4 + (qi & 3)] = v;
+        }
+        for (int i = tid; i < 4 * ng_max; i += CM_NW * 64) best[i] = 0ull;
+        __syncthreads();
+
+        auto run = [&](auto ng_tag) __attribute__((always_inline)) {
+            constexpr int NG = decltype(ng_tag)::value;
+            float best_sc[NG];
+            int32_t best_id[NG];
+            double acc[NG];
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                best_sc[g] = -__builtin_inff();
+                best_id[g] = -1;
+                acc[g] = 0.0;
+            }
+            int blk = part * CM_NW + wave;
+            if (blk >= nblk) return;
+            // ids of the rows this lane feeds and receives, for this step and (ahead) the next
+            auto id_at = [&](int e) { return e < len ? ids[e] : -1; };
+            auto row_of = [&](int32_t id) {
+                const bool ok = id >= 0 && (int64_t)id < N;
+                return base + (int64_t)(ok ? id : 0) * ld * ES;
+            };
+            int32_t id_out = id_at(blk * 16 + ro);
+            const unsigned char *row = row_of(id_at(blk * 16 + r16));
+            int32_t id_feed_n = id_at((blk + blk_step) * 16 + r16), id_out_n = id_at((blk + blk_step) * 16 + ro);
+            int seg = 0;
+            uint4 buf0[SEG], buf1[SEG];
+            auto load = [&](uint4(&buf)[SEG], const unsigned char *rw, int sg) __attribute__((always_inline)) {
+#pragma unroll
+                for (int c = 0; c < SEG; ++c) buf[c] = *reinterpret_cast<const uint4 *>(rw + (size_t)(sg * SEG + c) * 64);
+            };
+            // one (step, segment) item: issue the next item's loads, multiply this one's pieces
+            auto item = [&](uint4(&cur)[SEG], uint4(&nxt)[SEG]) __attribute__((always_inline)) -> bool {
+                const bool last_seg = seg + 1 == nsegs;
+                const int blk_n = last_seg ? blk + blk_step : blk;
+                const bool more = blk_n < nblk;
+                const unsigned char *row_n = last_seg ? row_of(id_feed_n) : row;
+                if (more) load(nxt, row_n, last_seg ? 0 : seg + 1);
+                const double *bl = bq + (size_t)seg * (SEG * CH * 16) + kq * 4 + jq;
+#pragma unroll
+                for (int c = 0; c < SEG; ++c) {
+                    {
+                        double a[CH];
+                        if constexpr (EX == DT_F32) {
+                            a[0] = (double)__uint_as_float(cur[c].x);
+                            a[1] = (double)__uint_as_float(cur[c].y);
+                            a[2] = (double)__uint_as_float(cur[c].z);
+                            a[3] = (double)__uint_as_float(cur[c].w);
+                        } else {
+                            a[0] = (double)f16_bits_to_f32(cur[c].x & 0xffffu);
+                            a[1] = (double)f16_bits_to_f32(cur[c].x >> 16);
+                            a[2] = (double)f16_bits_to_f32(cur[c].y & 0xffffu);
+                            a[3] = (double)f16_bits_to_f32(cur[c].y >> 16);
+                            a[4] = (double)f16_bits_to_f32(cur[c].z & 0xffffu);
+                            a[5] = (double)f16_bits_to_f32(cur[c].z >> 16);
+                            a[6] = (double)f16_bits_to_f32(cur[c].w & 0xffffu);
+                            a[7] = (double)f16_bits_to_f32(cur[c].w >> 16);
+                        }
+#pragma unroll
+                        for (int e = 0; e < CH; ++e) {
+#pragma unroll
+                            for (int g = 0; g < NG; ++g)
+                                acc[g] = __builtin_amdgcn_mfma_f64_4x4x4f64(a[e], bl[((size_t)g * T + c * CH + e) * 16], acc[g], 0, 0, 0);
+                        }
+                    }
+                }
+                if (last_seg) {
+                    const bool ok = id_out >= 0 && (int64_t)id_out < N;
+#pragma unroll
+                    for (int g = 0; g < NG; ++g) {
+                        const float sc = (float)acc[g] + 0.0f;   // -0 counts as +0, as in a key
+                        // higher score, then lower id
+                        const bool better = ok && g * 4 + jq < nq &&
+                                            (sc > best_sc[g] || (sc == best_sc[g] && id_out < best_id[g]));
+                        best_sc[g] = better ? sc : best_sc[g];
+                        best_id[g] = better ? id_out : best_id[g];
+                        acc[g] = 0.0;
+                    }
+                    blk = blk_n;
+                    seg = 0;
+                    row = row_n;
+                    id_out = id_out_n;
+                    if (more) {
+                        id_feed_n = id_at((blk + blk_step) * 16 + r16);
+                        id_out_n = id_at((blk + blk_step) * 16 + ro);
+                    }
+                } else {
+                    ++seg;
+                }
+                return !more;
+            };
+            load(buf0, row, 0);
+            for (;;) {
+                if (item(buf0, buf1)) break;
+                if (item(buf1, buf0)) break;
+            }
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+                if (best_id[g] >= 0)
+                    atomicMax(reinterpret_cast<unsigned long long *>(best + g * 4 + jq), make_key(best_sc[g], best_id[g]));
+        };
+        if (n_groups == 1) run(std::integral_constant<int, 1>{});
+        else if (n_groups == 2) run(std::integral_constant<int, 2>{});
+        else if (n_groups == 3) run(std::integral_constant<int, 3>{});
+        else run(std::integral_constant<int, 4>{});
+        __syncthreads();
+        for (int qi = tid; qi < nq; qi += CM_NW * 64) {
+            const u64 b = best[qi];
             if (partial) {
                 if (b) atomicMax(reinterpret_cast<unsigned long long *>(partial + g0 + qi), b);
             } else {
@@ -496,6 +673,47 @@ hipError_t launch_cache_ex(const int32_t *cache_ids, const int32_t *cache_len, i
     return hipGetLastError();
 }
 
+// The matrix-core form of the lookup, for the shapes it is written for: inner product, rows of a
+// multiple of 16 sixteen-byte pieces (d % 64 == 0 for fp32 rows, d % 128 == 0 for fp16 rows).
+template <int EX>
+bool cache_mfma_fits(int32_t d)
+{
+    const int nc = d / (EX == DT_F32 ? 16 : 32);
+    return d % (EX == DT_F32 ? 64 : 128) == 0 && nc >= 4 && (size_t)d * 32 <= 64 * 1024;
+}
+
+template <int EX>
+hipError_t launch_cache_mfma(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
+                             const float *queries, int64_t Qt, const int64_t *q_offsets, const void *exact,
+                             int64_t ld, int64_t N, int32_t d, int32_t *spec_ids, float *spec_scores,
+                             u64 *partial, int parts, hipStream_t stream)
+{
+    const int nc = d / (EX == DT_F32 ? 16 : 32);
+    // a group of 4 queries takes d * 32 bytes of LDS; up to 64 KB, so that two requests share a CU
+    int ng = (int)((64 * 1024) / ((size_t)d * 32));
+    ng = ng > CM_MAX_GROUPS ? CM_MAX_GROUPS : ng;
+    const size_t smem = (size_t)ng * d * 32 + (size_t)4 * ng * sizeof(u64);
+#define RALM_CM(SEGV)                                                                                       \
+    do {                                                                                                    \
+        auto kern = cache_lookup_mfma_kernel<EX, SEGV>;                                                     \
+        static std::atomic<bool> attr_done{false};                                                          \
+        if (!attr_done.load(std::memory_order_acquire)) {                                                   \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                        \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);      \
+            if (e != hipSuccess) return e;                                                                  \
+            attr_done.store(true, std::memory_order_release);                                               \
+        }                                                                                                   \
+        hipLaunchKernelGGL(kern, dim3((unsigned)R, (unsigned)parts), dim3(CM_NW * 64), smem, stream, cache_ids, \
+                           cache_len, C, queries, Qt, q_offsets, exact, ld, N, d, ng, spec_ids, spec_scores,   \
+                           partial);                                                                        \
+    } while (0)
+    if (nc % 8 == 0) RALM_CM(8);
+    else if (nc % 6 == 0) RALM_CM(6);
+    else RALM_CM(4);
+#undef RALM_CM
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_cache_lookup(const int32_t *cache_ids, const int32_t *cache_len, int32_t C, int64_t R,
@@ -523,13 +741,19 @@ hipError_t launch_cache_lookup(const int32_t *cache_ids, const int32_t *cache_le
 #define RALM_CACHE(EXV, L2V)                                                                           \
     e = launch_cache_ex<EXV, L2V>(cache_ids, cache_len, C, R, queries, Qt, q_offsets, exact, ld, N, d, \
                                   spec_ids, spec_scores, partial, parts, stream)
+#define RALM_CACHE_MFMA(EXV)                                                                             \
+    e = launch_cache_mfma<EXV>(cache_ids, cache_len, C, R, queries, Qt, q_offsets, exact, ld, N, d, spec_ids, \
+                               spec_scores, partial, parts, stream)
     if (exact_dtype == DT_F16) {
         if (metric == METRIC_L2) RALM_CACHE(DT_F16, true);
+        else if (cache_mfma_fits<DT_F16>(d)) RALM_CACHE_MFMA(DT_F16);
         else RALM_CACHE(DT_F16, false);
     } else {
         if (metric == METRIC_L2) RALM_CACHE(DT_F32, true);
+        else if (cache_mfma_fits<DT_F32>(d)) RALM_CACHE_MFMA(DT_F32);
         else RALM_CACHE(DT_F32, false);
     }
+#undef RALM_CACHE_MFMA
 #undef RALM_CACHE
     if (e != hipSuccess || !partial) return e;
     hipLaunchKernelGGL(cache_lookup_finish_kernel, dim3((unsigned)((R + 3) / 4)), dim3(256), 0, stream, partial, Qt,

@@ -837,6 +837,36 @@ def test_cache_lookup_split_over_workgroups_equals_one_per_request(B, oracle, R,
     assert np.array_equal(b_ids.cpu().numpy(), w_ids) and np.array_equal(b_sc.cpu().numpy(), w_sc)
 
 
+@pytest.mark.parametrize("dtype,d,smax", [("f32", 64, 3), ("f32", 128, 9), ("f32", 384, 5), ("f32", 1024, 20),
+                                          ("f32", 2048, 6), ("f16", 128, 7), ("f16", 1024, 12), ("f16", 768, 4),
+                                          ("f32", 80, 5), ("f32", 1992, 3)])
+def test_cache_lookup_row_lengths_of_the_matrix_core_form_and_beside_it(B, oracle, dtype, d, smax):
+    """The inner-product lookup runs on the fp64 matrix cores when a row is a whole number of 256-byte
+    steps (d % 64 == 0 for fp32 rows, d % 128 == 0 for fp16 rows, up to 2048 elements) and on the
+    vector units otherwise; both must give the oracle's ids and scores, with more queries per
+    request than one pass holds and ragged cache lengths."""
+    from paper_2401_14021_amd import inputs
+    N, R, C = 6000, 11, 150
+    rng = np.random.default_rng(d + smax)
+    if dtype == "f16":
+        X, _ = inputs.knnlm_datastore(N, d, 8, seed=d)
+    else:
+        X, _ = inputs.clustered_datastore(N, d, 8, seed=d)
+    strides = [int(v) for v in rng.integers(0, smax + 1, size=R)]
+    strides[0], strides[1] = smax, 1
+    off = inputs.stride_offsets(strides)
+    rows = inputs.pick_rows(N, int(off[-1]), seed=5)
+    Qm = inputs.queries_near_rows(X, rows, seed=6, sigma=0.3)
+    cids = torch.from_numpy(rng.integers(0, N, size=(R, C)).astype(np.int32))
+    clen = torch.from_numpy(rng.choice([0, 1, 15, 16, 17, C // 2, C], size=R).astype(np.int32))
+    clen[0] = C
+    ds = B.Datastore(X.cuda(), None)
+    for use_ws in (False, True):
+        ids, sc = B.ralm_cache_lookup(cids.cuda(), clen.cuda(), Qm.cuda(), off.cuda(), ds, use_workspace=use_ws)
+        w_ids, w_sc = oracle.cache_lookup(cids.numpy(), clen.numpy(), Qm.numpy(), off.numpy(), X.numpy())
+        assert np.array_equal(ids.cpu().numpy(), w_ids) and np.array_equal(sc.cpu().numpy(), w_sc)
+
+
 def _random_shapes(n, seed):
     rng = np.random.default_rng(seed)
     out = []
