@@ -34,6 +34,50 @@ def _stream_chunks(exact, say):
         yield r0, exact[r0:min(N, r0 + CHUNK)].float().cpu().numpy()
 
 
+L2_SAMPLE = [17, 90, 130, 222]
+_ORACLE_L2 = {}     # the squared-distance ranking of L2_SAMPLE, left here by the first test's pass over the keys
+
+
+def _oracle_two_metrics(oracle, keys, q_ip, q_l2, k, say):
+    """ONE pass over the streamed keys feeds two oracle rankings (inner product for q_ip, squared
+    distance for q_l2): each ranking runs in a thread of its own and takes the chunks from a queue
+    of length one, so a chunk is copied back from the device once and freed after both have
+    scored it.  Copying the 100M keys back is what takes the time, not the scoring."""
+    import queue
+    import threading
+    queues = [queue.Queue(maxsize=1) for _ in range(2)]
+    out, err = [None, None], []
+
+    def chunks_from(qu):
+        while True:
+            item = qu.get()
+            if item is None:
+                return
+            yield item
+
+    def rank(i, queries, metric):
+        try:
+            out[i] = oracle.retrieve_topk_stream(queries, chunks_from(queues[i]), k, metric=metric)
+        except BaseException as e:          # reported by the caller; keep draining so the feeder never blocks
+            err.append(e)
+            for _ in chunks_from(queues[i]):
+                pass
+
+    threads = [threading.Thread(target=rank, args=(0, q_ip, "ip")), threading.Thread(target=rank, args=(1, q_l2, "l2"))]
+    for t in threads:
+        t.start()
+    for item in _stream_chunks(keys, say):
+        for qu in queues:
+            qu.put(item)
+    for qu in queues:
+        qu.put(None)
+    for t in threads:
+        t.join()
+    if err:
+        raise err[0]
+    return out
+
+
 def _score_of_rows(oracle, exact, queries_np):
     def f(i, ids):
         rows = exact[torch.as_tensor(np.asarray(ids, dtype=np.int64), device=exact.device)].cpu().numpy()
@@ -72,7 +116,10 @@ def test_knnlm_100m_fp16_large_k_sampled_queries(B, oracle, progress):
     sample = [3, 40, 77, 100, 150, 180, 200, 251]
     assert sorted((i // 64 for i in sample)) == [0, 0, 1, 1, 2, 2, 3, 3]
     qs = Qm[sample].cpu().numpy()
-    wi, wsc = oracle.retrieve_topk_stream(qs, _stream_chunks(keys, progress), w.k)
+    # the same pass also ranks the next test's queries by squared distance (same keys, same queries)
+    qs_l2 = Qm[L2_SAMPLE].cpu().numpy()
+    (wi, wsc), l2_result = _oracle_two_metrics(oracle, keys, qs, qs_l2, w.k, progress)
+    _ORACLE_L2["queries"], _ORACLE_L2["result"] = qs_l2, l2_result
     exact, subs, total = check_topk(ids.cpu().numpy()[sample], sc.cpu().numpy()[sample], wi, wsc,
                                     _score_of_rows(oracle, keys, qs))
     assert exact >= 0.98 * total
@@ -86,7 +133,8 @@ def test_knnlm_100m_squared_distance_in_place_norms(B, oracle, progress):
     the 8 columns behind each row (no second copy of 205 GB).  Every query must be certified by
     the margin check, none handed to the exact pass (a row whose norm columns were not written
     would out-score every true neighbour and show up exactly there); the oracle ranks all 100M
-    keys by distance for four seeded queries."""
+    keys by distance for four seeded queries (during the previous test's pass over the keys when
+    that test ran, in a pass of its own otherwise)."""
     from paper_2401_14021_amd import inputs
     w = inputs.WORKLOADS["knnlm100m"]
     import gc
@@ -115,9 +163,12 @@ def test_knnlm_100m_squared_distance_in_place_norms(B, oracle, progress):
     assert c["unanswered"] == 0 and c["ladder_overflows"] == 0 and c["exact_pass"] == 0 and c["soft_certified"] == Q, c
     assert int(ids.min()) >= 0 and int(ids.max()) < w.N
     assert bool((sc[:, :-1] >= sc[:, 1:]).all())
-    sample = [17, 90, 130, 222]
+    sample = L2_SAMPLE
     qs = Qm[sample].cpu().numpy()
-    wi, wsc = oracle.retrieve_topk_stream(qs, _stream_chunks(keys, progress), w.k, metric="l2")
+    if "result" in _ORACLE_L2 and np.array_equal(_ORACLE_L2["queries"], qs):
+        wi, wsc = _ORACLE_L2["result"]          # ranked during the first test's pass over the same keys
+    else:
+        wi, wsc = oracle.retrieve_topk_stream(qs, _stream_chunks(keys, progress), w.k, metric="l2")
 
     def score_of(i, r):
         got = keys[torch.as_tensor(np.asarray(r, dtype=np.int64), device="cuda")].cpu().numpy()
