@@ -162,8 +162,10 @@ size_t ralm_workspace_bytes(int64_t Q, const ralm_datastore_t *ds, int32_t k, in
  * the exact copy is scored exactly (the arithmetic of the final scores) and the
  * best k of the rows that reach the exact rank-k score found so far are
  * returned, which is the exact top k by construction.  The pass is skipped
- * when no query needs it; it reads the exact copy once per 8 such queries
- * (21M x 768 fp32: about 13 ms for one query, 26 ms for 8).  With k_prime = k there is
+ * when no query needs it; it reads the exact copy once per 16 such queries
+ * (inner product on the fp64 matrix cores; 21M x 768 fp32: about 11 ms per
+ * pass), once per 8 for the squared distance and for row lengths that are not
+ * a multiple of 64 (fp32) or 128 (fp16) elements (13 to 26 ms).  With k_prime = k there is
  * no margin to speak of and nearly every query takes that pass.
  * ralm_workspace_counters reports how many did.
  *

@@ -419,6 +419,143 @@ __global__ __launch_bounds__(XS_THREADS) void exact_scan_kernel(const float *__r
     }
 }
 
+// The exact pass on the fp64 matrix cores (inner product, rows that are whole 256-byte steps).
+// v_mfma_f64_16x16x4: operand A of lane l is element (i = l%16, k = l/16), operand B element
+// (k = l/16, j = l%16), and the lane receives D(i = 4v + l/16, j = l%16) in its v-th result,
+// v = 0..3.  i runs over 16 consecutive rows, j over up to 16 queued queries, so one pass over the
+// exact copy serves 16 queries at the cost of one, with sums in double and no reduction across
+// lanes.  A lane holds elements 4*CH*u + CH*(l/16) .. + CH-1 of its row (CH elements per 16-byte
+// load); the queries sit in LDS as floats in the order the instructions consume them.  The sums
+// are formed in another order than the re-score forms them, so a row's score may differ from the
+// re-score's in the last place of the fp32 result (rarely: both are double sums rounded once);
+// rows are therefore collected from one fp32 step BELOW the bound's score on, which keeps the k
+// rows that defined the bound in the list whatever the order, and the final ranking uses this
+// kernel's scores only.
+constexpr int XM_NW = 8, XM_QG = 16;
+
+template <int EX, int SEG>
+__global__ __launch_bounds__(XM_NW * 64) void exact_scan_mfma_kernel(const float *__restrict__ queries,
+                                                                      const void *__restrict__ exact, int64_t ld,
+                                                                      int64_t N, int d,
+                                                                      const int32_t *__restrict__ fb_list,
+                                                                      const int32_t *__restrict__ flags,
+                                                                      const u64 *__restrict__ tau_exact,
+                                                                      u64 *__restrict__ cand, uint32_t *__restrict__ cnt,
+                                                                      uint32_t cap)
+{
+    constexpr int CH = EX == DT_F32 ? 4 : 8;   // elements per 16-byte piece
+    constexpr int ES = EX == DT_F32 ? 4 : 2;
+    typedef double d4 __attribute__((ext_vector_type(4)));
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *qf = reinterpret_cast<float *>(smem);   // [d / 4 instructions][4 k][16 j]
+    __shared__ float s_tsc[XM_QG];
+    __shared__ int32_t s_q[XM_QG];
+
+    const int F = flags[FLAG_FALLBACKS];
+    if (F <= 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, kq = lane >> 4;
+    const int NC = d / (4 * CH), nsegs = NC / SEG;
+    const int64_t nblk = (N + 15) / 16;
+    const int64_t blk0 = (int64_t)blockIdx.x * XM_NW + wave, blk_step = (int64_t)gridDim.x * XM_NW;
+    const unsigned char *base = static_cast<const unsigned char *>(exact) + kq * 16;
+
+    for (int g0 = 0; g0 < F; g0 += XM_QG) {
+        const int nq = F - g0 < XM_QG ? F - g0 : XM_QG;
+        __syncthreads();
+        if (tid < XM_QG) {
+            int32_t q = -1;
+            float tsc = __builtin_inff();
+            if (tid < nq) {
+                q = fb_list[g0 + tid];
+                const uint32_t b = (uint32_t)(tau_exact[q] >> 32);
+                tsc = bits_score(b ? b - 1u : 0u);   // one fp32 step below the bound's score
+            }
+            s_q[tid] = q;
+            s_tsc[tid] = tsc;
+        }
+        __syncthreads();
+        for (int i = tid; i < XM_QG * d; i += XM_NW * 64) {
+            const int qi = i / d, e = i - qi * d;
+            const float v = qi < nq ? queries[(int64_t)s_q[qi] * d + e] : 0.f;
+            const int t = CH * (e / (4 * CH)) + e % CH, k = (e / CH) & 3;
+            qf[(size_t)t * 64 + k * 16 + qi] = v;
+        }
+        __syncthreads();
+        const float my_tsc = s_tsc[r16];
+        const int64_t my_q = s_q[r16];
+
+        int64_t blk = blk0;
+        if (blk >= nblk) continue;
+        auto row_of = [&](int64_t b) {
+            int64_t row = b * 16 + r16;
+            row = row < N ? row : N - 1;   // rows past the end re-read the last one; their results are dropped
+            return base + row * ld * ES;
+        };
+        const unsigned char *row = row_of(blk);
+        int seg = 0;
+        d4 acc = {0.0, 0.0, 0.0, 0.0};
+        uint4 buf0[SEG], buf1[SEG];
+        auto load = [&](uint4(&buf)[SEG], const unsigned char *rw, int sg) __attribute__((always_inline)) {
+#pragma unroll
+            for (int c = 0; c < SEG; ++c) buf[c] = *reinterpret_cast<const uint4 *>(rw + (size_t)(sg * SEG + c) * 64);
+        };
+        auto item = [&](uint4(&cur)[SEG], uint4(&nxt)[SEG]) __attribute__((always_inline)) -> bool {
+            const bool last_seg = seg + 1 == nsegs;
+            const int64_t blk_n = last_seg ? blk + blk_step : blk;
+            const bool more = blk_n < nblk;
+            const unsigned char *row_n = last_seg ? row_of(more ? blk_n : blk) : row;
+            if (more) load(nxt, row_n, last_seg ? 0 : seg + 1);
+            const float *ql = qf + (size_t)seg * (SEG * CH * 64) + lane;
+#pragma unroll
+            for (int c = 0; c < SEG; ++c) {
+                double a[CH];
+                if constexpr (EX == DT_F32) {
+                    a[0] = (double)__uint_as_float(cur[c].x);
+                    a[1] = (double)__uint_as_float(cur[c].y);
+                    a[2] = (double)__uint_as_float(cur[c].z);
+                    a[3] = (double)__uint_as_float(cur[c].w);
+                } else {
+                    a[0] = (double)f16_bits_to_f32(cur[c].x & 0xffffu);
+                    a[1] = (double)f16_bits_to_f32(cur[c].x >> 16);
+                    a[2] = (double)f16_bits_to_f32(cur[c].y & 0xffffu);
+                    a[3] = (double)f16_bits_to_f32(cur[c].y >> 16);
+                    a[4] = (double)f16_bits_to_f32(cur[c].z & 0xffffu);
+                    a[5] = (double)f16_bits_to_f32(cur[c].z >> 16);
+                    a[6] = (double)f16_bits_to_f32(cur[c].w & 0xffffu);
+                    a[7] = (double)f16_bits_to_f32(cur[c].w >> 16);
+                }
+#pragma unroll
+                for (int e = 0; e < CH; ++e)
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[e], (double)ql[(size_t)(c * CH + e) * 64], acc, 0, 0, 0);
+            }
+            if (last_seg) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int64_t rw = blk * 16 + 4 * v + kq;
+                    const float sc = (float)acc[v];
+                    if (rw < N && sc >= my_tsc) {
+                        const uint32_t at = atomicAdd(cnt + my_q, 1u);
+                        if (at < cap) cand[my_q * cap + at] = make_key(sc, (int32_t)rw);
+                    }
+                }
+                acc = d4{0.0, 0.0, 0.0, 0.0};
+                blk = blk_n;
+                seg = 0;
+                row = row_n;
+            } else {
+                ++seg;
+            }
+            return !more;
+        };
+        load(buf0, row, 0);
+        for (;;) {
+            if (item(buf0, buf1)) break;
+            if (item(buf1, buf0)) break;
+        }
+    }
+}
+
 // Final ranking of an exact-pass query: the k best keys of its list, sorted, written out.
 __global__ __launch_bounds__(SEL_THREADS) void exact_finish_kernel(const u64 *__restrict__ cand,
                                                                    const uint32_t *__restrict__ cnt, uint32_t cap,
@@ -545,13 +682,42 @@ hipError_t launch_exact_pass(const float *queries, int64_t Q, const void *exact,
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(XS_THREADS), smem, stream, queries, exact, ld, N, d, \
                            qgroup, fb_list, flags, tau_exact, cand, cnt, cap);                                  \
     } while (0)
+    // matrix-core form: inner product, rows of a multiple of 4 sixteen-byte pieces per lane, queries of
+    // a group within 128 KB of LDS
+    const int nc = d / (exact_dtype == DT_F32 ? 16 : 32);
+    const bool mfma = metric == METRIC_IP && d % (exact_dtype == DT_F32 ? 64 : 128) == 0 && d <= 2048;
+#define RALM_XM(EXV, SEGV)                                                                                      \
+    do {                                                                                                        \
+        auto kern = exact_scan_mfma_kernel<EXV, SEGV>;                                                          \
+        static std::atomic<bool> attr_done{false};                                                              \
+        if (!attr_done.load(std::memory_order_acquire)) {                                                       \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                            \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);         \
+            if (e != hipSuccess) return e;                                                                      \
+            attr_done.store(true, std::memory_order_release);                                                   \
+        }                                                                                                       \
+        const int64_t nblk = (N + 15) / 16, wgs = (int64_t)n_cu * ((size_t)d * 64 * 2 <= 150 * 1024 ? 2 : 1);   \
+        const int64_t g = nblk < wgs * XM_NW ? (nblk + XM_NW - 1) / XM_NW : wgs;                                \
+        hipLaunchKernelGGL(kern, dim3((unsigned)g), dim3(XM_NW * 64), (size_t)d * 64, stream, queries, exact, ld, N, \
+                           d, fb_list, flags, tau_exact, cand, cnt, cap);                                       \
+    } while (0)
+#define RALM_XM_SEG(EXV)                  \
+    do {                                  \
+        if (nc % 8 == 0) RALM_XM(EXV, 8); \
+        else if (nc % 6 == 0) RALM_XM(EXV, 6); \
+        else RALM_XM(EXV, 4);             \
+    } while (0)
     if (exact_dtype == DT_F16) {
         if (metric == METRIC_L2) RALM_XS(DT_F16, true);
+        else if (mfma) RALM_XM_SEG(DT_F16);
         else RALM_XS(DT_F16, false);
     } else {
         if (metric == METRIC_L2) RALM_XS(DT_F32, true);
+        else if (mfma) RALM_XM_SEG(DT_F32);
         else RALM_XS(DT_F32, false);
     }
+#undef RALM_XM_SEG
+#undef RALM_XM
 #undef RALM_XS
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
