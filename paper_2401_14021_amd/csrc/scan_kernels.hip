@@ -796,8 +796,10 @@ hipError_t launch_dma(const ScanParams &p, int n_cu, hipStream_t stream)
         // (strips of whole 128-byte lines; with 64-byte strips a line would be requested twice, a
         // stage apart, and would have to stay in L2 in between).
         case 32: return launch_dma_variant<F16, 4, 1, 2, 1, 64, 4, true>(p, n_cu, stream);
-        case 64: return launch_dma_variant<F16, 4, 1, 1, 2, 64, 6, true>(p, n_cu, stream);
-        case 128: return launch_dma_variant<F16, 2, 2, 4, 2, 64, 3, true, 3, 2>(p, n_cu, stream);
+        // 64 and 128 queries: 8 waves (two per SIMD, wave tiles of 64 x 32 and 128 x 32), so that one wave's
+        // waits are covered by the other's multiplies; with 4 waves of twice the width they were 5 % and 3 % slower
+        case 64: return launch_dma_variant<F16, 4, 2, 2, 1, 64, 3, true, 3, 2>(p, n_cu, stream);
+        case 128: return launch_dma_variant<F16, 2, 4, 4, 1, 64, 3, true, 3, 2>(p, n_cu, stream);
         default:
             // two slots of 64-element strips, refilled in place (D = S): same LDS as four 32-element
             // slots, half the rendezvous and half the L2 requests per multiply

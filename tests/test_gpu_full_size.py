@@ -156,7 +156,7 @@ def test_specloop_closed_loop_100_steps_full_size(B, oracle, dense21m, progress)
     start EMPTY, strides uniform in 1..8 (about 2300 queries); per step a cache top-1 lookup, one
     batched exact top-1 retrieval, the first-mismatch compare and the top-1 cache update with the
     verified steps; queries drift between steps; 100 steps.  Integer stages (compare, update) are
-    checked against the oracle on everything at every step; the retrieval on 24 seeded queries and
+    checked against the oracle on everything at every step; the retrieval on 32 seeded queries and
     the cache lookup on 3 seeded requests at steps 0, 1, 10, 50 and 99; rank preservation
     (Section 3) on every query at every step."""
     from paper_2401_14021_amd import inputs
@@ -196,9 +196,9 @@ def test_specloop_closed_loop_100_steps_full_size(B, oracle, dense21m, progress)
         # integer stages against the oracle, everything
         assert np.array_equal(m_h, oracle.verify(spec_h, ids_h.reshape(-1), off_h, 1)), step
         if step in (0, 1, 10, 50, 99):
-            progress(f"specloop: step {step}, hit rate {hit_rates[-1]:.2f}, the oracle ranks 21M rows for 24 queries ...")
+            progress(f"specloop: step {step}, hit rate {hit_rates[-1]:.2f}, the oracle ranks 21M rows for 32 queries ...")
             qnp = Qm.cpu().numpy()
-            sample_q = torch.randperm(Q, generator=g)[:24].tolist()
+            sample_q = torch.randperm(Q, generator=g)[:32].tolist()
             want = oracle.retrieve_topk_stream(qnp[sample_q], _host_chunks(Xh), 1)
             _check_sample(oracle, Xh, qnp[sample_q], 1, ids_h[sample_q], sc.cpu().numpy()[sample_q], want)
             # cache lookup of sampled requests (the state before this step's update = the oracle's)
