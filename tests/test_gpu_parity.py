@@ -96,7 +96,8 @@ def test_clustered_real_valued(B, oracle, scan_dtype, N, d, Q, k):
     assert LAST_COUNTERS["exact_pass"] == 0        # k' = 64 leaves a margin far above the scan's rounding
 
 
-@pytest.mark.parametrize("N,d,Q,k", [(70001, 768, 3, 20), (9000, 72, 40, 5), (33000, 136, 64, 64), (5000, 768, 100, 7)])
+@pytest.mark.parametrize("N,d,Q,k", [(70001, 768, 3, 20), (9000, 72, 40, 5), (33000, 136, 64, 64), (5000, 768, 100, 7),
+                                      (20011, 200, 130, 5), (7001, 768, 256, 20), (5000, 40, 200, 3), (30000, 1024, 129, 1)])
 def test_fp32_rows_scanned_as_they_are(B, oracle, N, d, Q, k):
     """No scan copy: the scan streams the fp32 rows and rounds them to bf16 on the way to the
     matrix cores (batches of up to 64 queries take the pipelined kernel, larger ones the staged
