@@ -87,8 +87,8 @@ typedef enum { RALM_METRIC_IP = 0, RALM_METRIC_L2 = 1 } ralm_metric;
  *   scan   the copy the full scan reads: bf16 or fp16 roundings of the exact
  *          keys (build with ralm_build_scan_copy), or the exact copy itself
  *          (fp32 is rounded to bf16 on the fly: at or near the HBM rate for
- *          batches of up to 256 queries, slowly for larger ones; fp16 is used
- *          as is).
+ *          batches of up to 256 queries, at about half the speed of a bf16
+ *          copy for larger ones; fp16 is used as is).
  *          NULL means "use the exact copy".
  *   *_stride  row pitch in ELEMENTS (0 = d).  Pitch in bytes and both base
  *          pointers must be multiples of 16.  d must be a multiple of 8.
@@ -126,11 +126,11 @@ typedef struct {
  * Runs on the default stream and synchronises before returning.  It uses
  * buffers of its own, kept between calls and grown on demand (allocating tens
  * of gigabytes per call is slow); ralm_release_buffers() frees them: the
- * workspace and, for batches of more than 256 queries only, a bf16 copy of the
+ * workspace and, for batches of more than 768 queries only, a bf16 copy of the
  * datastore for the scan (N*d*2 bytes, rebuilt on every call; skipped if the
- * device has no room for it).  Batches of up to 256 queries scan the fp32 rows
+ * device has no room for it).  Batches of up to 768 queries scan the fp32 rows
  * as they are (21M x 768: about 9.3 ms for up to 64 queries, the rate at which
- * HBM delivers the rows; 14.4 ms for 256), and hold no copy.  Calls are serialised.  Meant for convenience; a caller that
+ * HBM delivers the rows; 14.4 ms for 256, 25 ms for 512), and hold no copy.  Calls are serialised.  Meant for convenience; a caller that
  * retrieves large batches repeatedly keeps a scan copy and uses the full form.
  * A query that the full form would leave unanswered (see
  * ralm_retrieve_topk_ex) makes the call retry through ralm_retrieve_topk_seq;

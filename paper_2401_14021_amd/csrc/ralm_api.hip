@@ -440,14 +440,14 @@ ralm_status ralm_retrieve_topk(const float *queries, int64_t Q, const float *dat
     std::lock_guard<std::mutex> lock(g_simple_mutex);
     if (!simple_reserve(&g_simple_ws, &g_simple_ws_bytes, pl.total))
         return fail(RALM_ERR_DEVICE, "no device memory for %zu bytes of workspace", pl.total);
-    // Batches of up to 256 queries (one query tile) are limited by HBM or close to it either way:
-    // the scan streams the fp32 rows as they are (one pass over 4 bytes per element beats a
-    // conversion pass plus a scan of the copy) and no copy is held.  Larger batches, whose query
-    // tiles share the rows through L2, are limited by the matrix cores, which the
+    // Batches of up to 768 queries (three query tiles) scan the fp32 rows as they are: one pass over
+    // 4 bytes per element, 9 to 14 ms per query tile at 21M x 768, beats a conversion pass (19.5 ms)
+    // plus a scan of the copy (6.5 ms per tile), and no copy is held.  Larger batches are limited
+    // by the matrix cores, which the
     // pipelined bf16 kernel feeds far better: they get a bf16 copy (one read, one write, redone on
     // every call: the rows may have changed), kept between calls; if the device has no room for
     // it the rows are scanned as they are by the staged kernel.  Same result either way.
-    if (Q > 256 && simple_reserve(&g_simple_scan, &g_simple_scan_bytes, (size_t)N * d * 2) &&
+    if (Q > 768 && simple_reserve(&g_simple_scan, &g_simple_scan_bytes, (size_t)N * d * 2) &&
         launch_convert_rows(datastore, d, g_simple_scan, RALM_BF16, d, N, d, nullptr) == hipSuccess) {
         ds.scan = g_simple_scan;
         ds.scan_dtype = RALM_BF16;

@@ -97,11 +97,11 @@ def test_clustered_real_valued(B, oracle, scan_dtype, N, d, Q, k):
 
 
 @pytest.mark.parametrize("N,d,Q,k", [(70001, 768, 3, 20), (9000, 72, 40, 5), (33000, 136, 64, 64), (5000, 768, 100, 7),
-                                      (20011, 200, 130, 5), (7001, 768, 256, 20), (5000, 40, 200, 3), (30000, 1024, 129, 1)])
+                                      (20011, 200, 130, 5), (7001, 768, 256, 20), (5000, 40, 200, 3), (30000, 1024, 129, 1),
+                                      (12000, 768, 300, 5), (6000, 104, 520, 2)])
 def test_fp32_rows_scanned_as_they_are(B, oracle, N, d, Q, k):
     """No scan copy: the scan streams the fp32 rows and rounds them to bf16 on the way to the
-    matrix cores (batches of up to 64 queries take the pipelined kernel, larger ones the staged
-    one).  Integer-valued rows must come out bit-exact, real-valued ones under the usual rule."""
+    matrix cores, for one query tile and for several.  Integer-valued rows must come out bit-exact, real-valued ones under the usual rule."""
     from paper_2401_14021_amd import inputs
     g = torch.Generator().manual_seed(N + d + Q)
     X = torch.randint(-3, 4, (N, d), generator=g).float()
