@@ -193,7 +193,9 @@ size_t ralm_workspace_bytes(int64_t Q, const ralm_datastore_t *ds, int32_t k, in
  * tile holding the best matches), the list keeps what it has, the scan goes
  * on, and the query is answered by the exact pass, whose list holds only rows
  * that reach the exact rank-k score of the candidates that survived.  Only if
- * that list overflows too (more than 16384 rows tie with or beat that score)
+ * that list overflows too (more than 16384 rows beat that score, tie with it,
+ * or fall short of it by no more than one fp32 step: the pass forms its double
+ * sums in another order than the re-score and leaves that much room)
  * are the query's outputs set to id -1 / score NaN; ralm_workspace_overflows()
  * counts those, and ralm_retrieve_topk_seq answers them.
  */
