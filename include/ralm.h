@@ -197,7 +197,9 @@ size_t ralm_workspace_bytes(int64_t Q, const ralm_datastore_t *ds, int32_t k, in
  * or fall short of it by no more than one fp32 step: the pass forms its double
  * sums in another order than the re-score and leaves that much room)
  * are the query's outputs set to id -1 / score NaN; ralm_workspace_overflows()
- * counts those, and ralm_retrieve_topk_seq answers them.
+ * counts those.  (Such a datastore holds tens of thousands of rows that no
+ * fp32 score separates from the query's k-th best; a larger k would be the
+ * honest request.)
  */
 ralm_status ralm_retrieve_topk_ex(const float *queries, int64_t Q, const ralm_datastore_t *ds,
                                   int32_t k, int32_t k_prime, int32_t *out_ids, float *out_scores,
