@@ -10,7 +10,7 @@ Prints ONE JSON line: queries/s for the headline batch size, the roofline
 figures of the dominant kernel (the full-datastore scan) measured with HIP
 events inside the library, a sweep over the other batch sizes, and the CPU
 oracle timed on a bounded sample of the same workload.  The default run adds
-`other_workloads`: a few steps each of the stress loop (512 requests, ragged
+`other_workloads`: a few steps each of the medium batched-verification case, the stress loop (512 requests, ragged
 strides) and of the KNN-LM datastore shape (100M x 1024 fp16), measured the
 same way after the headline's tensors have been released.
 """
@@ -61,7 +61,7 @@ def main():
         import gc
         import torch
         out["other_workloads"] = []
-        for name in ("specloop", "knnlm100m"):
+        for name in ("medium", "specloop", "knnlm100m"):
             gc.collect()
             torch.cuda.empty_cache()
             a = copy.copy(args)
