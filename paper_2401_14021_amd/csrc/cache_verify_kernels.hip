@@ -5,9 +5,10 @@
 //                       retriever's own metric (Section 3 "Speculative retrieval", Fig. 2)
 //                       and return the top one.  Scores are formed exactly as the final
 //                       scores of the knowledge-base retrieval (double products and sum,
-//                       one rounding to fp32), so a cached entry gets the same number from
-//                       both and "top-1 of the knowledge base is cached => it is the cache's
-//                       top-1" holds bit for bit.
+//                       one rounding to fp32; only the order of the double additions
+//                       differs), so a cached entry gets the same number from both and
+//                       "top-1 of the knowledge base is cached => it is the cache's top-1"
+//                       holds.
 //  cache_lookup_mfma_kernel  the same lookup with the sums formed on the fp64 matrix cores
 //                       (inner product, rows that are whole 256-byte steps).
 //  verify_kernel        m = argmin_i (d^_i != d_i) of Alg. 1, per request.
