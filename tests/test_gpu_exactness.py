@@ -130,6 +130,30 @@ def test_fp16_keys_as_their_own_scan_copy(B, oracle):
     assert np.array_equal(ids, wi) and np.array_equal(sc, wsc)
 
 
+@pytest.mark.parametrize("store,d", [("f32", 64), ("f32", 200), ("f32", 384), ("f32", 96), ("f32", 2048),
+                                     ("f16", 128), ("f16", 192), ("f16", 2048)])
+def test_exact_pass_row_lengths_on_the_matrix_cores_and_beside_them(B, oracle, store, d):
+    """k' = k sends every query to the exact pass: it runs on the fp64 matrix cores when a row is a
+    whole number of 256-byte steps (d % 64 == 0 in fp32, d % 128 == 0 in fp16, up to 2048 elements)
+    and on the vector units otherwise; 20 queries are more than one pass of 16 (or of 8) serves.
+    Ids and scores must be the oracle's either way."""
+    from paper_2401_14021_amd import inputs
+    N, Q, k = 20000, 20, 10
+    if store == "f16":
+        X, _ = inputs.knnlm_datastore(N, d, 16, seed=d)
+        ds = B.Datastore(X.cuda(), None)
+        sigma = 0.5
+    else:
+        X, _ = inputs.clustered_datastore(N, d, 16, seed=d)
+        ds = B.Datastore.from_fp32(X.cuda())
+        sigma = 0.05
+    Qm = inputs.queries_near_rows(X, inputs.pick_rows(N, Q, seed=3), seed=4, sigma=sigma)
+    ids, sc, c, mg = _run(B, ds, Qm, k, k)
+    wi, wsc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), k)
+    assert c["exact_pass"] == Q and c["unanswered"] == 0, c
+    assert np.array_equal(ids, wi) and np.array_equal(sc, wsc)
+
+
 def test_more_rows_reach_the_bound_than_a_list_holds(B, oracle):
     """100000 copies of one vector below the scan's resolution: the exact pass would have to
     collect far more than the 16384 rows a list holds.  Such a query is not answered wrongly: it
