@@ -7,20 +7,22 @@
 // accumulation) and each one is compared at once with its query's admission key; the few
 // that pass are appended to that query's candidate list.
 //
-// Tiling: a workgroup of 4 or 8 waves owns a 256-row (for one variant: 128-row) x BN-query
-// tile; the reduction dimension is walked in strips of BK elements.  Datastore rows are the A operand of v_mfma_f32_32x32x16,
-// queries the B operand, so every accumulator register of a lane belongs to ONE query
-// (column = lane % 32) and the lane can hold that query's threshold in a register.
+// Tiling: a workgroup of 4 or 8 waves owns a 256-row x BN-query tile (BN = 32 on 4 waves; 64,
+// 128 and 256 on 8 waves, two per SIMD); the reduction dimension is walked in strips of BK
+// elements.  Datastore rows are the A operand of v_mfma_f32_32x32x16, queries the B operand, so
+// every accumulator register of a lane belongs to ONE query (column = lane % 32) and the lane
+// can hold that query's threshold in a register.
 //
 // Two kernels share that tiling and the epilogue:
-//   scan_dma_kernel     bf16 / fp16 datastore copies.  Strips go from global memory straight
+//   scan_dma_kernel     bf16 / fp16 datastore copies, and fp32 rows as they are (rounded to
+//                       bf16 between the operand read and the multiply).  Strips go from global memory straight
 //                       into LDS (global_load_lds_dwordx4, no VGPR staging) through a ring of
 //                       S stages that runs ahead of the multiply and keeps running across tile
 //                       boundaries; the 16-byte chunks of a row are XOR-swizzled on the way in
 //                       (by choosing which global chunk each lane fetches) so that the MFMA
 //                       operand reads (32 rows, same chunk) are free of bank conflicts.
-//   scan_staged_kernel  global -> registers -> LDS, double buffered: fp32 datastores (rows are
-//                       rounded to bf16 on the way) and the stages that keep every score.
+//   scan_staged_kernel  global -> registers -> LDS, double buffered: the stages that keep
+//                       every score (the first, small one of a ladder).
 //
 // Work items (row tile, query tile) are dealt to a persistent grid so that workgroups that
 // run at the same time on one XCD (workgroup b lands on XCD b % 8) hold consecutive items:
