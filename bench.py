@@ -237,7 +237,10 @@ def measure(args):
             "exact_pass_fallbacks": cn["exact_pass"], "ladder_overflows": cn["ladder_overflows"],
             "unanswered": cn["unanswered"],
             "margin_min": round(float(fin.min().item()), 6) if fin.numel() else None,
-            "margin_median": round(float(fin.median().item()), 6) if fin.numel() else None}
+            "margin_median": round(float(fin.median().item()), 6) if fin.numel() else None,
+            # per ladder stage: entries in the candidate lists when the stage ended, per query (the at most
+            # k' kept before plus what the stage admitted)
+            "list_entries_per_query_by_stage": [round(v / hb["Q"], 1) for v in B.ralm_workspace_stage_entries(hb["ws"])]}
 
     # fraction of cycles in which the matrix cores were busy, and the shader clock, from rocprofv3
     # counters of the same command (summary under profiles/); absent if not measured for this case

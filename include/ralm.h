@@ -248,6 +248,22 @@ typedef struct {
 ralm_status ralm_workspace_counters(const void *workspace, void *stream, ralm_counters_t *out);
 
 /*
+ * How full the candidate lists got in the LAST ralm_retrieve_topk_ex / _seq
+ * call on this workspace: entries[i] = over all queries, the entries their
+ * lists held when stage i of the ladder ended (the at most k' kept from the
+ * stages before plus the scores the stage admitted), i < *n_stages; the other
+ * elements are set to 0.  entries is a HOST array of RALM_MAX_LADDER_STAGES
+ * elements; of a longer ladder (the sequential form) the first
+ * RALM_MAX_LADDER_STAGES stages are reported.  Synchronises `stream`.  A
+ * diagnostic: with rows in an order that the strided samples represent well a
+ * stage that multiplies the rows scanned by g admits about k' (g - 1) scores
+ * per query.
+ */
+#define RALM_MAX_LADDER_STAGES 40
+ralm_status ralm_workspace_stage_entries(const void *workspace, void *stream, int32_t *n_stages,
+                                         int64_t *entries);
+
+/*
  * Build the low-precision scan copy of a datastore: dst[j, c] = round-to-
  * nearest-even(src[j, c]) in dst_dtype (RALM_BF16 or RALM_F16).  src is device
  * fp32 [N, d] with pitch src_stride elements, dst device [N, d] with pitch

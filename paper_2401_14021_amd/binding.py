@@ -67,6 +67,7 @@ def lib() -> ctypes.CDLL:
         L.ralm_retrieve_topk_seq.argtypes = L.ralm_retrieve_topk_ex.argtypes
         L.ralm_workspace_overflows.argtypes = [vp, vp, ctypes.POINTER(i32)]
         L.ralm_workspace_counters.argtypes = [vp, vp, ctypes.POINTER(ralm_counters_t)]
+        L.ralm_workspace_stage_entries.argtypes = [vp, vp, ctypes.POINTER(i32), ctypes.POINTER(i64)]
         L.ralm_build_scan_copy.argtypes = [vp, i64, vp, i32, i64, i64, i32, vp]
         L.ralm_build_scan_copy_l2.argtypes = [vp, i32, i64, vp, i32, i64, i64, i32, vp]
         L.ralm_cache_lookup.argtypes = [vp, vp, i32, i64, vp, i64, vp, dsp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -97,7 +98,7 @@ def lib() -> ctypes.CDLL:
         L.ralm_profile_enable.restype = None
         L.ralm_profile_scan_ms.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         for name in ("ralm_retrieve_topk", "ralm_retrieve_topk_ex", "ralm_retrieve_topk_seq", "ralm_workspace_overflows",
-                     "ralm_workspace_counters",
+                     "ralm_workspace_counters", "ralm_workspace_stage_entries",
                      "ralm_build_scan_copy", "ralm_build_scan_copy_l2", "ralm_cache_lookup", "ralm_cache_lookup_static",
                      "ralm_cache_lookup_topk", "ralm_verify", "ralm_cache_insert", "ralm_knnlm_probs",
                      "ralm_profile_scan_ms"):
@@ -225,6 +226,19 @@ def ralm_workspace_counters(workspace: torch.Tensor) -> dict:
     c = ralm_counters_t()
     _check(lib().ralm_workspace_counters(ws_ptr, _stream(), ctypes.byref(c)))
     return {name: int(getattr(c, name)) for name, _ in ralm_counters_t._fields_}
+
+
+RALM_MAX_LADDER_STAGES = 40
+
+
+def ralm_workspace_stage_entries(workspace: torch.Tensor) -> list:
+    """Entries that the candidate lists held at the end of each ladder stage of the last retrieval
+    call on this workspace, summed over the queries."""
+    ws_ptr, _ = _ws_view(workspace)
+    n = ctypes.c_int32(0)
+    arr = (ctypes.c_int64 * RALM_MAX_LADDER_STAGES)()
+    _check(lib().ralm_workspace_stage_entries(ws_ptr, _stream(), ctypes.byref(n), arr))
+    return [int(arr[i]) for i in range(n.value)]
 
 
 def ralm_retrieve_topk(queries: torch.Tensor, datastore: torch.Tensor, k: int

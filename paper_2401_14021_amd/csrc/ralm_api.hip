@@ -120,7 +120,7 @@ ralm_status make_plan(int64_t Q, const ralm_datastore_t *ds, int32_t k, int32_t 
     for (int i = 0; i < n; ++i) pl.stride[i] = rev[n - 1 - i];
 
     size_t off = 0;
-    pl.off_flags = off;  off += 256;   // always first: the counters of the last call (FLAG_*)
+    pl.off_flags = off;  off += FLAG_BLOCK_BYTES;   // always first: the counters of the last call (FLAG_*)
     pl.off_q = off;      off += up256((size_t)pl.Qpad * pl.dpad * 2);
     pl.off_tau = off;    off += up256((size_t)pl.Qpad * 8);
     pl.off_cnt = off;    off += up256((size_t)pl.Qpad * 4);
@@ -259,7 +259,7 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
 
     RALM_HIP(launch_query_prep(queries, Q, ds->d, qs, pl.Qpad, pl.dpad, mma_dt, ds->metric, stream));
     RALM_HIP(launch_fill_u64(tau, 0ull, pl.Qpad, stream));
-    RALM_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(flags), 0u, 64, stream));
+    RALM_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(flags), 0u, FLAG_BLOCK_BYTES / 4, stream));
     RALM_HIP(launch_fill_u32(cnt, 0u, (int64_t)(pl.off_fb - pl.off_cnt) / 4, stream));   // cnt and lost
 
     ScanParams sp;
@@ -267,6 +267,7 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
     sp.Qs = qs; sp.dpad = pl.dpad; sp.Q = (int32_t)Q;
     sp.tau = tau; sp.cand = cand; sp.cnt = cnt; sp.cap = pl.cap;
     // one stage: scan the tiles sp describes, then cut every list down to its k' best
+    int32_t stage_no = 0;
     auto run_stage = [&]() -> ralm_status {
         if (sp.n_row_tiles <= 0) return RALM_OK;
         const bool prof = g_prof_on && g_prof_n < MAX_PROF;
@@ -283,7 +284,7 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
             RALM_HIP(hipEventRecord(g_prof_ev[g_prof_n][1], stream));
             ++g_prof_n;
         }
-        RALM_HIP(launch_select(cand, cnt, pl.cap, pl.k_prime, Q, tau, sel, lost, flags, stream));
+        RALM_HIP(launch_select(cand, cnt, pl.cap, pl.k_prime, Q, tau, sel, lost, flags, stage_no++, stream));
         return RALM_OK;
     };
 
@@ -366,6 +367,23 @@ ralm_status ralm_workspace_overflows(const void *workspace, void *stream_, int32
     RALM_HIP(hipStreamSynchronize(stream));
     RALM_HIP(hipMemcpy(count, static_cast<const int32_t *>(workspace) + FLAG_UNANSWERED, sizeof(int32_t),
                        hipMemcpyDeviceToHost));
+    return RALM_OK;
+}
+
+static_assert(MAX_STAGE_SUMS == RALM_MAX_LADDER_STAGES, "the flag block holds one sum per reported stage");
+
+ralm_status ralm_workspace_stage_entries(const void *workspace, void *stream_, int32_t *n_stages, int64_t *entries)
+{
+    if (!workspace || !n_stages || !entries) return fail(RALM_ERR_NULL, "workspace/n_stages/entries is NULL");
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    unsigned char block[FLAG_BLOCK_BYTES];
+    RALM_HIP(hipStreamSynchronize(stream));
+    RALM_HIP(hipMemcpy(block, workspace, sizeof(block), hipMemcpyDeviceToHost));
+    int32_t n = reinterpret_cast<const int32_t *>(block)[FLAG_STAGES];
+    n = n < 0 ? 0 : (n > MAX_STAGE_SUMS ? MAX_STAGE_SUMS : n);
+    *n_stages = n;
+    const unsigned long long *sums = reinterpret_cast<const unsigned long long *>(block + STAGE_SUMS_BYTE);
+    for (int i = 0; i < RALM_MAX_LADDER_STAGES; ++i) entries[i] = i < n ? (int64_t)sums[i] : 0;
     return RALM_OK;
 }
 

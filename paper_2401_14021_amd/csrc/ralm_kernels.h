@@ -48,13 +48,17 @@ hipError_t launch_l2_scan_copy(const void *src, int32_t src_dtype, int64_t src_l
 hipError_t launch_convert_rows(const float *src, int64_t src_ld, void *dst, int32_t dst_dtype,
                                int64_t dst_ld, int64_t N, int32_t d, hipStream_t stream);
 
-// Words of a retrieval call's flag block (first 256 bytes of its workspace), all counts of queries.
+// A retrieval call's flag block (first FLAG_BLOCK_BYTES of its workspace): 32-bit words FLAG_*,
+// counts of queries; from byte STAGE_SUMS_BYTE on, one 64-bit sum per ladder stage (entries that
+// the lists held when the stage ended, over all queries).
+constexpr int FLAG_BLOCK_BYTES = 1024, STAGE_SUMS_BYTE = 256, MAX_STAGE_SUMS = 40;
 enum {
     FLAG_UNANSWERED = 0,        // answered with id -1 / score NaN
     FLAG_LADDER_OVERFLOWS = 1,  // candidate list lost entries during the scan (answered by the exact pass)
     FLAG_HARD_CERTIFIED = 2,    // margin above the deterministic rounding bound
     FLAG_SOFT_CERTIFIED = 3,    // margin above 8x the rounding spread seen on the candidates (includes the above)
-    FLAG_FALLBACKS = 4          // answered by the exact pass
+    FLAG_FALLBACKS = 4,         // answered by the exact pass
+    FLAG_STAGES = 5             // stages of the ladder whose sums were recorded
 };
 
 // What the re-score needs to check its own result and to queue a query for the exact pass; all
@@ -72,8 +76,9 @@ struct CertifyParams {
 // to its k' best keys (cnt[q] <- min(cnt[q], k')).  tmp is scratch of [Q, k'] keys.  A list
 // that was sent more than cap keys holds the first cap of them: lost[q] is set and the query
 // counted once in flags[FLAG_LADDER_OVERFLOWS].
+// stage >= 0: the lists' lengths before the cut are added to the stage's sum in the flag block.
 hipError_t launch_select(u64 *cand, uint32_t *cnt, uint32_t cap, int32_t k_prime, int64_t Q, u64 *tau,
-                         u64 *tmp, uint32_t *lost, int32_t *flags, hipStream_t stream);
+                         u64 *tmp, uint32_t *lost, int32_t *flags, int32_t stage, hipStream_t stream);
 
 // per query: exact scores of the (at most k') rows left in its list, final ranking, top k out;
 // with cert.flags: the result is checked and queries that fail are queued for launch_exact_pass

@@ -109,7 +109,7 @@ __device__ u64 radix_kth(const u64 *__restrict__ c, uint32_t n, uint32_t rank, R
 __global__ __launch_bounds__(SEL_THREADS) void select_kernel(u64 *__restrict__ cand, uint32_t *__restrict__ cnt,
                                                              uint32_t cap, int k_prime, u64 *__restrict__ tau,
                                                              u64 *__restrict__ tmp, uint32_t *__restrict__ lost,
-                                                             int32_t *__restrict__ flags)
+                                                             int32_t *__restrict__ flags, int stage)
 {
     __shared__ RadixShared sh;
     __shared__ uint32_t s_out;
@@ -118,6 +118,12 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(u64 *__restrict__ c
     const int tid = threadIdx.x;
     uint32_t n = cnt[q];
     u64 *c = cand + q * (int64_t)cap;
+    // entries the scan sent to this list in the stage that just ended, plus the (at most k') kept before
+    if (tid == 0 && stage >= 0 && stage < MAX_STAGE_SUMS) {
+        unsigned long long *sums = reinterpret_cast<unsigned long long *>(reinterpret_cast<unsigned char *>(flags) + STAGE_SUMS_BYTE);
+        atomicAdd(sums + stage, (unsigned long long)n);
+        if (q == 0) flags[FLAG_STAGES] = stage + 1;
+    }
 
     if (n > cap) {
         n = cap;
@@ -623,11 +629,11 @@ __global__ __launch_bounds__(SEL_THREADS) void exact_finish_kernel(const u64 *__
 }  // namespace
 
 hipError_t launch_select(u64 *cand, uint32_t *cnt, uint32_t cap, int32_t k_prime, int64_t Q, u64 *tau, u64 *tmp,
-                         uint32_t *lost, int32_t *flags, hipStream_t stream)
+                         uint32_t *lost, int32_t *flags, int32_t stage, hipStream_t stream)
 {
     if (Q <= 0) return hipSuccess;
     hipLaunchKernelGGL(select_kernel, dim3((unsigned)Q), dim3(SEL_THREADS), 0, stream, cand, cnt, cap, k_prime, tau, tmp,
-                       lost, flags);
+                       lost, flags, stage);
     return hipGetLastError();
 }
 

@@ -136,6 +136,10 @@ def test_argument_errors_return_status_without_a_device(L):
     assert L.ralm_build_scan_copy(P, 0, P, 0, 0, 10, 768, None) == 4             # fp32 is not a scan copy
     assert L.ralm_build_scan_copy(P, 0, P, 1, 0, 10, 12, None) == 2
     assert L.ralm_build_scan_copy(P, 0, None, 1, 0, 10, 768, None) == 1
+    n, arr = ctypes.c_int32(0), (ctypes.c_int64 * b.RALM_MAX_LADDER_STAGES)()
+    assert L.ralm_workspace_stage_entries(None, None, ref(n), arr) == 1             # accessors check their pointers
+    assert L.ralm_workspace_stage_entries(P, None, None, arr) == 1
+    assert L.ralm_workspace_counters(None, None, ref(b.ralm_counters_t())) == 1
 
 
 def test_binding_refuses_to_run_without_the_library(monkeypatch):

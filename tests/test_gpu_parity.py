@@ -239,6 +239,29 @@ def test_list_overflow_is_recovered_by_the_exact_pass_and_the_sequential_ladder_
     assert np.array_equal(ids.cpu().numpy(), wi) and np.array_equal(sc.cpu().numpy(), wsc)
 
 
+def test_list_entries_per_stage_are_reported(B, oracle):
+    """The ladder's diagnostic: per stage, the entries the lists held when it ended.  Stage 0 keeps
+    every score of the rows it visits, so its sum is exactly rows visited x Q; every later stage holds
+    at least the k' kept before, and with rows in random order about k' (g - 1) more."""
+    from paper_2401_14021_amd import inputs
+    N, d, Q, k = 300000, 64, 70, 5
+    X, _ = inputs.clustered_datastore(N, d, 64, seed=3)
+    Qm = inputs.queries_near_rows(X, inputs.pick_rows(N, Q, seed=4), seed=5)
+    ds = B.Datastore.from_fp32(X.cuda())
+    ws = B.alloc_workspace(Q, ds, k)
+    B.ralm_retrieve_topk_ex(Qm.cuda(), ds, k, workspace=ws)
+    e = B.ralm_workspace_stage_entries(ws)
+    tiles = (N + 255) // 256
+    assert len(e) >= 2
+    assert e[0] % Q == 0 and e[0] // Q <= 16384 and e[0] // Q >= 16384 // 8
+    for v in e[1:]:
+        assert 64 * Q <= v <= 16384 * Q
+    # the sequential ladder has more stages than are reported: the first 40 come back
+    B.ralm_retrieve_topk_ex(Qm.cuda(), ds, k, workspace=ws, sequential=True)
+    e2 = B.ralm_workspace_stage_entries(ws)
+    assert len(e2) == min(40, -(-tiles // ((16384 - 64) // 256)))
+
+
 @pytest.mark.parametrize("Q,k", [(4, 20), (150, 100)])
 def test_sequential_ladder_equals_the_strided_one(B, oracle, Q, k):
     from paper_2401_14021_amd import inputs
