@@ -891,6 +891,49 @@ def test_cache_lookup_row_lengths_of_the_matrix_core_form_and_beside_it(B, oracl
         assert np.array_equal(ids.cpu().numpy(), w_ids) and np.array_equal(sc.cpu().numpy(), w_sc)
 
 
+def _random_lookup_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        d = int(rng.choice([64, 128, 192, 256, 320, 512, 576, 768, 1024, 1536, 72, 200, 1000]))
+        R = int(rng.choice([1, 2, 7, 33, 127, 128, 200]))
+        C = int(rng.choice([1, 15, 16, 17, 31, 64, 100, 257]))
+        smax = int(rng.choice([1, 3, 4, 5, 8, 9, 17]))
+        out.append((d, R, C, smax, bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("d,R,C,smax,f16", _random_lookup_shapes(24, seed=77))
+def test_cache_lookup_random_shapes(B, oracle, d, R, C, smax, f16):
+    """Seeded random shapes of the lookup around its block sizes (16 cached rows per matrix-core
+    step, 4 and 8 queries per pass, one workgroup or several per request), fp32 and fp16 rows,
+    integer-valued (every sum exact: ids and scores bit for bit, ties by id) and real-valued."""
+    from paper_2401_14021_amd import inputs
+    N = 3000
+    rng = np.random.default_rng(d * 31 + R * 7 + C)
+    g = torch.Generator().manual_seed(d + R + C + smax)
+    strides = [int(v) for v in rng.integers(0, smax + 1, size=R)]
+    strides[0] = smax
+    off = inputs.stride_offsets(strides)
+    Qt = int(off[-1])
+    cids = torch.from_numpy(rng.integers(0, N, size=(R, C)).astype(np.int32))
+    clen = torch.from_numpy(rng.integers(0, C + 1, size=R).astype(np.int32))
+    clen[0] = C
+    for real in (False, True):
+        if real:
+            X, _ = inputs.clustered_datastore(N, d, 8, seed=d)
+            Qm = inputs.queries_near_rows(X, inputs.pick_rows(N, Qt, seed=5), seed=6, sigma=0.3)
+        else:
+            X = torch.randint(-3, 4, (N, d), generator=g).float()
+            Qm = torch.randint(-3, 4, (Qt, d), generator=g).float()
+        if f16:
+            X = X.half()
+        ds = B.Datastore(X.cuda(), None)
+        ids, sc = B.ralm_cache_lookup(cids.cuda(), clen.cuda(), Qm.cuda(), off.cuda(), ds)
+        w_ids, w_sc = oracle.cache_lookup(cids.numpy(), clen.numpy(), Qm.numpy(), off.numpy(), X.numpy())
+        assert np.array_equal(ids.cpu().numpy(), w_ids) and np.array_equal(sc.cpu().numpy(), w_sc)
+
+
 def _random_shapes(n, seed):
     rng = np.random.default_rng(seed)
     out = []
