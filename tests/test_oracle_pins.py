@@ -178,6 +178,16 @@ def test_chunk_streamed_retrieval_with_ties_across_chunks_in_any_order(oracle):
             chunks = [(int(parts[c][0]), X[parts[c]]) for c in order]
             ids_s, sc_s = oracle.retrieve_topk_stream(Qm, chunks, k)
             assert np.array_equal(ids_s, want_ids) and np.array_equal(sc_s, want_sc), (n_parts, order)
+    # the same under the squared-distance metric (the streamed form is also used with it at 100M rows)
+    want_ids, want_sc = oracle.retrieve_topk(Qm, X, k, metric="l2")
+    for i in range(4):
+        ranked = sorted(range(N), key=lambda j: (sum((a - b) ** 2 for a, b in zip(qi[i], xi[j])), j))[:k]
+        assert ranked == want_ids[i].tolist()
+    parts = np.array_split(np.arange(N), 7)
+    for order in (list(range(7)), rng.permutation(7).tolist()):
+        chunks = [(int(parts[c][0]), X[parts[c]]) for c in order]
+        ids_s, sc_s = oracle.retrieve_topk_stream(Qm, chunks, k, metric="l2")
+        assert np.array_equal(ids_s, want_ids) and np.array_equal(sc_s, want_sc), order
 
 
 def test_transposed_or_misindexed_operands_would_fail(oracle):
