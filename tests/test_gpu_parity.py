@@ -141,6 +141,21 @@ def test_simple_form_fp32_datastore(B, oracle):
     B.ralm_release_buffers()
 
 
+@pytest.mark.parametrize("Q", [65, 300, 768, 800])
+def test_simple_form_batches_on_both_sides_of_the_copy_threshold(B, oracle, Q):
+    """Up to 768 queries the simple form scans the caller's fp32 rows as they are (one to three
+    query tiles); beyond that it builds a bf16 copy per call.  Same answers either way."""
+    from paper_2401_14021_amd import inputs
+    N, d, k = 9000, 256, 5
+    X, _ = inputs.clustered_datastore(N, d, 16, seed=Q)
+    Qm = inputs.queries_near_rows(X, inputs.pick_rows(N, Q, seed=1), seed=2)
+    ids, sc = B.ralm_retrieve_topk(Qm.cuda(), X.cuda(), k)
+    wi, wsc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), k)
+    exact, subs, total = check_topk(ids.cpu().numpy(), sc.cpu().numpy(), wi, wsc, _score_fn(oracle, Qm.numpy(), X.numpy()))
+    assert exact >= 0.99 * total
+    B.ralm_release_buffers()
+
+
 def test_fp16_keys_are_the_truth_large_k(B, oracle):
     """KNN-LM shape at reduced N: fp16 keys (no fp32 copy), raw inner product, k = 1024."""
     from paper_2401_14021_amd import inputs
