@@ -554,11 +554,16 @@ __global__ void fill_u64_kernel(u64 *p, u64 v, int64_t n)
 // query preparation: queries rounded to the scan dtype, zero padded to [Qpad, dpad]
 // L2: the scan scores a row as 2<q, x> - |x|^2, its squared norm being stored behind the row as the
 // sum of two scan-dtype numbers (columns d and d+1): the query is doubled and gets -1 in both.
+// The same launch clears two ranges of 32-bit words (the call's counters and list lengths), which
+// saves three tiny launches per retrieval call.
 template <int DT, bool L2>
 __global__ void query_prep_kernel(const float *__restrict__ q, int64_t Q, int d, uint16_t *__restrict__ out,
-                                  int64_t Qpad, int dpad)
+                                  int64_t Qpad, int dpad, uint32_t *__restrict__ z0, int64_t n0,
+                                  uint32_t *__restrict__ z1, int64_t n1)
 {
     const int64_t n = Qpad * dpad;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n0; i += (int64_t)gridDim.x * blockDim.x) z0[i] = 0u;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n1; i += (int64_t)gridDim.x * blockDim.x) z1[i] = 0u;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
         const int64_t row = i / dpad;
         const int col = (int)(i % dpad);
@@ -836,21 +841,22 @@ hipError_t launch_l2_scan_copy(const void *src, int32_t src_dtype, int64_t src_l
 }
 
 hipError_t launch_query_prep(const float *q, int64_t Q, int32_t d, uint16_t *out, int64_t Qpad, int32_t dpad,
-                             int32_t scan_dtype, int32_t metric, hipStream_t stream)
+                             int32_t scan_dtype, int32_t metric, uint32_t *z0, int64_t n0, uint32_t *z1, int64_t n1,
+                             hipStream_t stream)
 {
     const int64_t n = Qpad * dpad;
     if (n <= 0) return hipSuccess;
     const dim3 grid(grid_for(n, 256)), block(256);
     if (scan_dtype == DT_F16) {
         if (metric == METRIC_L2)
-            hipLaunchKernelGGL((query_prep_kernel<DT_F16, true>), grid, block, 0, stream, q, Q, d, out, Qpad, dpad);
+            hipLaunchKernelGGL((query_prep_kernel<DT_F16, true>), grid, block, 0, stream, q, Q, d, out, Qpad, dpad, z0, n0, z1, n1);
         else
-            hipLaunchKernelGGL((query_prep_kernel<DT_F16, false>), grid, block, 0, stream, q, Q, d, out, Qpad, dpad);
+            hipLaunchKernelGGL((query_prep_kernel<DT_F16, false>), grid, block, 0, stream, q, Q, d, out, Qpad, dpad, z0, n0, z1, n1);
     } else {
         if (metric == METRIC_L2)
-            hipLaunchKernelGGL((query_prep_kernel<DT_BF16, true>), grid, block, 0, stream, q, Q, d, out, Qpad, dpad);
+            hipLaunchKernelGGL((query_prep_kernel<DT_BF16, true>), grid, block, 0, stream, q, Q, d, out, Qpad, dpad, z0, n0, z1, n1);
         else
-            hipLaunchKernelGGL((query_prep_kernel<DT_BF16, false>), grid, block, 0, stream, q, Q, d, out, Qpad, dpad);
+            hipLaunchKernelGGL((query_prep_kernel<DT_BF16, false>), grid, block, 0, stream, q, Q, d, out, Qpad, dpad, z0, n0, z1, n1);
     }
     return hipGetLastError();
 }

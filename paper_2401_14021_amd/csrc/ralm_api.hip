@@ -257,10 +257,11 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
     int n_cu = device_cus() - g_scan_reserve.load(std::memory_order_relaxed);
     if (n_cu < 8) n_cu = 8;
 
-    RALM_HIP(launch_query_prep(queries, Q, ds->d, qs, pl.Qpad, pl.dpad, mma_dt, ds->metric, stream));
-    RALM_HIP(launch_fill_u64(tau, 0ull, pl.Qpad, stream));
-    RALM_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(flags), 0u, FLAG_BLOCK_BYTES / 4, stream));
-    RALM_HIP(launch_fill_u32(cnt, 0u, (int64_t)(pl.off_fb - pl.off_cnt) / 4, stream));   // cnt and lost
+    // the same launch clears the flag block and, behind the queries, the admission keys, the list
+    // lengths and the lost marks (contiguous in the workspace)
+    RALM_HIP(launch_query_prep(queries, Q, ds->d, qs, pl.Qpad, pl.dpad, mma_dt, ds->metric,
+                               reinterpret_cast<uint32_t *>(flags), FLAG_BLOCK_BYTES / 4,
+                               reinterpret_cast<uint32_t *>(tau), (int64_t)(pl.off_fb - pl.off_tau) / 4, stream));
 
     ScanParams sp;
     sp.X = scan; sp.ldx = scan_ld; sp.N = ds->N; sp.d = scan_cols(ds); sp.in_dtype = scan_dt;

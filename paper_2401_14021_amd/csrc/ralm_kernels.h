@@ -40,8 +40,10 @@ hipError_t launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t strea
 hipError_t launch_fill_u64(u64 *p, u64 v, int64_t n, hipStream_t stream);
 
 // fp32 [Q, d] -> scan dtype [Qpad, dpad], zero padded
+// also clears the n0 words at z0 and the n1 words at z1
 hipError_t launch_query_prep(const float *q, int64_t Q, int32_t d, uint16_t *out, int64_t Qpad,
-                             int32_t dpad, int32_t scan_dtype, int32_t metric, hipStream_t stream);
+                             int32_t dpad, int32_t scan_dtype, int32_t metric, uint32_t *z0, int64_t n0,
+                             uint32_t *z1, int64_t n1, hipStream_t stream);
 hipError_t launch_l2_scan_copy(const void *src, int32_t src_dtype, int64_t src_ld, void *dst, int32_t dst_dtype,
                                int64_t dst_ld, int64_t N, int32_t d, hipStream_t stream);
 
