@@ -100,6 +100,7 @@ ralm_status make_plan(int64_t Q, const ralm_datastore_t *ds, int32_t k, int32_t 
     const int64_t safety = k_prime <= 256 ? 4 : 2;
     pl.cap = (uint32_t)(safety * k_prime * (g_coarse - 1) + k_prime);
     if (pl.cap < 16384u) pl.cap = 16384u;
+    pl.cap = (pl.cap + 1u) & ~1u;   // even: lists start on 16-byte boundaries
     pl.Qpad = (Q + SCAN_QPAD - 1) / SCAN_QPAD * SCAN_QPAD;
     pl.dpad = (scan_cols(ds) + SCAN_BK - 1) / SCAN_BK * SCAN_BK;
 
@@ -267,6 +268,7 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
     sp.X = scan; sp.ldx = scan_ld; sp.N = ds->N; sp.d = scan_cols(ds); sp.in_dtype = scan_dt;
     sp.Qs = qs; sp.dpad = pl.dpad; sp.Q = (int32_t)Q;
     sp.tau = tau; sp.cand = cand; sp.cnt = cnt; sp.cap = pl.cap;
+    sp.lists_empty = 0;
     // one stage: scan the tiles sp describes, then cut every list down to its k' best
     int32_t stage_no = 0;
     auto run_stage = [&]() -> ralm_status {
@@ -310,12 +312,14 @@ ralm_status retrieve_impl(const float *queries, int64_t Q, const ralm_datastore_
                 sp.tile_skip = 0;                                   // every multiple of the stride
                 sp.n_row_tiles = (tiles + stride - 1) / stride;
                 sp.park_pushes = 0;                                 // admits everything
+                sp.lists_empty = 1;
             } else {
                 const int64_t m_max = (tiles + stride - 1) / stride - 1;   // multiples m >= 1 with m*stride < tiles
                 const int64_t g = pl.stride[s - 1] / stride;        // ... that no earlier stage visited
                 sp.tile_skip = (int32_t)g;
                 sp.n_row_tiles = m_max - m_max / g;
                 sp.park_pushes = 1;
+                sp.lists_empty = 0;
             }
             st = run_stage();
             if (st != RALM_OK) return st;

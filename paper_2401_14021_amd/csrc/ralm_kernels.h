@@ -30,6 +30,8 @@ struct ScanParams {
     int32_t tile_skip;      // if tile_skip == 0, else the t-th positive integer that is no multiple of tile_skip
     int64_t tile_begin;
     int32_t park_pushes;    // 1: thresholds are selective, collect admitted scores in LDS first
+    int32_t lists_empty;    // 1 (with park_pushes == 0): every list is empty and every score of this launch is
+                            // kept, so list positions follow from the row's place in the launch (no atomics)
 };
 
 // query tile width chosen for Q

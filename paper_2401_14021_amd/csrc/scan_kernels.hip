@@ -21,8 +21,11 @@
 //                       boundaries; the 16-byte chunks of a row are XOR-swizzled on the way in
 //                       (by choosing which global chunk each lane fetches) so that the MFMA
 //                       operand reads (32 rows, same chunk) are free of bank conflicts.
-//   scan_staged_kernel  global -> registers -> LDS, double buffered: the stages that keep
-//                       every score (the first, small one of a ladder).
+//   scan_staged_kernel  global -> registers -> LDS, double buffered: launches that keep every
+//                       score (the first, small stage of a ladder for up to 64 queries or fp32
+//                       rows; the blocks of the sequential ladder).  For more than 64 queries
+//                       the first stage runs in scan_dma_kernel<.., ALL>, which writes each
+//                       score to the list slot that its row's place in the launch determines.
 //
 // Work items (row tile, query tile) are dealt to a persistent grid so that workgroups that
 // run at the same time on one XCD (workgroup b lands on XCD b % 8) hold consecutive items:
@@ -238,6 +241,26 @@ __device__ __forceinline__ void select_block_parked(const ScanParams &p, const P
     }
 }
 
+// Epilogue of a launch that keeps every score into empty lists (the first stage of a ladder): the
+// score of the launch's r-th row goes to slot r of its query's list, no atomics.  A lane's 16
+// values are 4 runs of 4 consecutive rows: 8 stores of two keys each.
+__device__ __forceinline__ void store_block_all(const ScanParams &p, const f32x16 &out, int32_t row_id0, int64_t pos0,
+                                                int q, bool qok)
+{
+    if (!qok) return;
+    u64 *dst = p.cand + (int64_t)q * p.cap + pos0;
+    typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int v = c * 4 + h * 2;
+            const u64x2 two = {make_key(out[v], row_id0 + c * 8 + h * 2), make_key(out[v + 1], row_id0 + c * 8 + h * 2 + 1)};
+            *reinterpret_cast<u64x2 *>(dst + c * 8 + h * 2) = two;
+        }
+    }
+}
+
 // IN: dtype of the datastore copy being scanned.  WM x WN waves, each TM x TN MFMA blocks.
 template <int IN, int WM, int WN, int TM, int TN>
 __global__ __launch_bounds__(256) void scan_staged_kernel(const ScanParams p, const int nqt)
@@ -411,8 +434,9 @@ constexpr int PARK_CAP = 672;         // parked admitted scores per workgroup (1
 // A32: the datastore rows are fp32 (a datastore scanned as it is).  They travel to LDS as they
 // are, twice the bytes per strip row, and are rounded to bf16 between the operand read and the
 // multiply (two 16-byte reads and four conversions per operand instead of one read).
+// ALL: a launch into empty lists that keeps every score (see store_block_all); no thresholds.
 template <bool F16, int WM, int WN, int TM, int TN, int BK, int S, bool NTA, int D = S - 1, int RK = 0,
-          bool A32 = false>
+          bool A32 = false, bool ALL = false>
 __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams p, const int nqt, const int tau_in_lds)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
@@ -465,6 +489,11 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
     };
     const int KT = p.dpad / BK;
     const int n_mine = vb < total ? (total - vb + G - 1) / G : 0;
+    if constexpr (ALL) {
+        // every list ends up with one entry per row of the launch (all of its tiles are full: host check)
+        if (blockIdx.x == 0)
+            for (int q = tid; q < p.Q; q += NT) p.cnt[q] = (uint32_t)n_tiles * BM;
+    }
     if (n_mine == 0) return;
     const unsigned char *Xb = static_cast<const unsigned char *>(p.X);
     const unsigned char *Qb = reinterpret_cast<const unsigned char *>(p.Qs);
@@ -690,9 +719,14 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
                     }
                     if (LAST && last_kk && m >= LAG && m - LAG < NM) {
                         const int mm = m - LAG, i = mm / TN, j = mm % TN;
-                        select_block_parked(p, pl, wave_slots, outs[mm % (LAG + 1)],
-                                            row0 + (wm * TM + i) * 32 + (lane >> 5) * 4, n_rows,
-                                            q0 + (wn * TN + j) * 32 + fr, qok[j], tkey[j], tsc[j]);
+                        if constexpr (ALL)
+                            store_block_all(p, outs[mm % (LAG + 1)], row0 + (wm * TM + i) * 32 + (lane >> 5) * 4,
+                                            (int64_t)cur_rt * BM + (wm * TM + i) * 32 + (lane >> 5) * 4,
+                                            q0 + (wn * TN + j) * 32 + fr, qok[j]);
+                        else
+                            select_block_parked(p, pl, wave_slots, outs[mm % (LAG + 1)],
+                                                row0 + (wm * TM + i) * 32 + (lane >> 5) * 4, n_rows,
+                                                q0 + (wn * TN + j) * 32 + fr, qok[j], tkey[j], tsc[j]);
                     }
                     RALM_SCHED_FENCE();
                 }
@@ -761,14 +795,14 @@ __global__ __launch_bounds__(WM *WN * 64) void scan_dma_kernel(const ScanParams 
 }
 
 template <bool F16, int WM, int WN, int TM, int TN, int BK, int S, bool NTA, int D = S - 1, int RK = 0,
-          bool A32 = false>
+          bool A32 = false, bool ALL = false>
 hipError_t launch_dma_variant(const ScanParams &p, int n_cu, hipStream_t stream)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t ring = (size_t)S * (BM * (A32 ? 4 : 2) + BN * 2) * BK;
     constexpr size_t smem = ring + (size_t)tau_lds_q(BN) * 8 + (size_t)PARK_CAP * 12 + 16 + WM * WN * SLOW_SLOTS * 64;
     static_assert(smem <= 160 * 1024, "LDS budget");
-    auto kern = scan_dma_kernel<F16, WM, WN, TM, TN, BK, S, NTA, D, RK, A32>;
+    auto kern = scan_dma_kernel<F16, WM, WN, TM, TN, BK, S, NTA, D, RK, A32, ALL>;
     const int tau_in_lds = p.Q <= tau_lds_q(BN) ? 1 : 0;
     static std::atomic<bool> attr_done{false};   // per instantiation; setting it twice is harmless
     if (!attr_done.load(std::memory_order_acquire)) {
@@ -873,7 +907,23 @@ hipError_t launch_scan(const ScanParams &p, int n_cu, hipStream_t stream)
         if (p.park_pushes) return launch_dma_variant<false, 2, 4, 4, 2, 32, 2, false, 2, 0, true>(p, n_cu, stream);
         return launch_in<DT_F32>(p, n_cu, stream);
     }
-    if (!p.park_pushes) return p.in_dtype == DT_F16 ? launch_in<DT_F16>(p, n_cu, stream) : launch_in<DT_BF16>(p, n_cu, stream);
+    if (!p.park_pushes) {
+        // The first stage of a ladder (every score kept, lists empty) for more than 64 queries: the
+        // pipelined kernel with stores to fixed list positions; its tiles must all be full and fit
+        // the lists.  (One 256 x 256 tile takes the staged kernel 125 us, mostly its epilogue's
+        // atomics and its shallow pipeline.)
+        const int64_t last_tile = (p.tile_begin + p.n_row_tiles - 1) * p.tile_stride;
+        if (p.lists_empty && p.tile_skip == 0 && p.Q > 64 && p.n_row_tiles > 0 &&
+            (last_tile + 1) * SCAN_BM <= p.N && p.n_row_tiles * SCAN_BM <= (int64_t)p.cap && p.cap % 2 == 0) {
+            const bool wide = p.Q > 128;
+            if (p.in_dtype == DT_F16)
+                return wide ? launch_dma_variant<true, 2, 4, 4, 2, 64, 2, false, 2, 2, false, true>(p, n_cu, stream)
+                            : launch_dma_variant<true, 2, 4, 4, 1, 64, 3, false, 3, 2, false, true>(p, n_cu, stream);
+            return wide ? launch_dma_variant<false, 2, 4, 4, 2, 64, 2, false, 2, 2, false, true>(p, n_cu, stream)
+                        : launch_dma_variant<false, 2, 4, 4, 1, 64, 3, false, 3, 2, false, true>(p, n_cu, stream);
+        }
+        return p.in_dtype == DT_F16 ? launch_in<DT_F16>(p, n_cu, stream) : launch_in<DT_BF16>(p, n_cu, stream);
+    }
     return p.in_dtype == DT_F16 ? launch_dma<true>(p, n_cu, stream) : launch_dma<false>(p, n_cu, stream);
 }
 
