@@ -22,8 +22,8 @@
 //                       (by choosing which global chunk each lane fetches) so that the MFMA
 //                       operand reads (32 rows, same chunk) are free of bank conflicts.
 //   scan_staged_kernel  global -> registers -> LDS, double buffered: launches that keep every
-//                       score (the first, small stage of a ladder for up to 64 queries or fp32
-//                       rows; the blocks of the sequential ladder).  For more than 64 queries
+//                       score: the first, small stage of a ladder over fp32 rows or with a
+//                       partial last tile, and the blocks of the sequential ladder.  Otherwise
 //                       the first stage runs in scan_dma_kernel<.., ALL>, which writes each
 //                       score to the list slot that its row's place in the launch determines.
 //
@@ -908,19 +908,24 @@ hipError_t launch_scan(const ScanParams &p, int n_cu, hipStream_t stream)
         return launch_in<DT_F32>(p, n_cu, stream);
     }
     if (!p.park_pushes) {
-        // The first stage of a ladder (every score kept, lists empty) for more than 64 queries: the
+        // The first stage of a ladder (every score kept, lists empty): the
         // pipelined kernel with stores to fixed list positions; its tiles must all be full and fit
         // the lists.  (One 256 x 256 tile takes the staged kernel 125 us, mostly its epilogue's
         // atomics and its shallow pipeline.)
         const int64_t last_tile = (p.tile_begin + p.n_row_tiles - 1) * p.tile_stride;
-        if (p.lists_empty && p.tile_skip == 0 && p.Q > 64 && p.n_row_tiles > 0 &&
+        if (p.lists_empty && p.tile_skip == 0 && p.n_row_tiles > 0 &&
             (last_tile + 1) * SCAN_BM <= p.N && p.n_row_tiles * SCAN_BM <= (int64_t)p.cap && p.cap % 2 == 0) {
-            const bool wide = p.Q > 128;
-            if (p.in_dtype == DT_F16)
-                return wide ? launch_dma_variant<true, 2, 4, 4, 2, 64, 2, false, 2, 2, false, true>(p, n_cu, stream)
-                            : launch_dma_variant<true, 2, 4, 4, 1, 64, 3, false, 3, 2, false, true>(p, n_cu, stream);
-            return wide ? launch_dma_variant<false, 2, 4, 4, 2, 64, 2, false, 2, 2, false, true>(p, n_cu, stream)
-                        : launch_dma_variant<false, 2, 4, 4, 1, 64, 3, false, 3, 2, false, true>(p, n_cu, stream);
+            const int bn = scan_bn_for(p.Q);
+            if (p.in_dtype == DT_F16) {
+                if (bn == 32) return launch_dma_variant<true, 4, 1, 2, 1, 64, 4, false, 3, 0, false, true>(p, n_cu, stream);
+                if (bn == 64) return launch_dma_variant<true, 4, 2, 2, 1, 64, 3, false, 3, 2, false, true>(p, n_cu, stream);
+                if (bn == 128) return launch_dma_variant<true, 2, 4, 4, 1, 64, 3, false, 3, 2, false, true>(p, n_cu, stream);
+                return launch_dma_variant<true, 2, 4, 4, 2, 64, 2, false, 2, 2, false, true>(p, n_cu, stream);
+            }
+            if (bn == 32) return launch_dma_variant<false, 4, 1, 2, 1, 64, 4, false, 3, 0, false, true>(p, n_cu, stream);
+            if (bn == 64) return launch_dma_variant<false, 4, 2, 2, 1, 64, 3, false, 3, 2, false, true>(p, n_cu, stream);
+            if (bn == 128) return launch_dma_variant<false, 2, 4, 4, 1, 64, 3, false, 3, 2, false, true>(p, n_cu, stream);
+            return launch_dma_variant<false, 2, 4, 4, 2, 64, 2, false, 2, 2, false, true>(p, n_cu, stream);
         }
         return p.in_dtype == DT_F16 ? launch_in<DT_F16>(p, n_cu, stream) : launch_in<DT_BF16>(p, n_cu, stream);
     }
