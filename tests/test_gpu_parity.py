@@ -254,6 +254,29 @@ def test_list_overflow_is_recovered_by_the_exact_pass_and_the_sequential_ladder_
     assert np.array_equal(ids.cpu().numpy(), wi) and np.array_equal(sc.cpu().numpy(), wsc)
 
 
+@pytest.mark.parametrize("N", [16384, 16000, 16484, 32768 + 256, 256, 300])
+@pytest.mark.parametrize("Q", [5, 100, 300])
+def test_first_stage_with_full_and_partial_last_tiles(B, oracle, N, Q):
+    """The first stage of the ladder keeps every score.  When all of its 256-row tiles are full it
+    writes each score to the list slot that the row's place in the stage determines; when the
+    datastore's partial last tile is among them it takes the atomic path.  Datastores of one stage
+    (N <= 16384) and of two, with and without a partial last tile in stage 0."""
+    g = torch.Generator().manual_seed(N + Q)
+    d, k = 64, 7
+    X = torch.randint(-3, 4, (N, d), generator=g).float()
+    Qm = torch.randint(-3, 4, (Q, d), generator=g).float()
+    for dt in (torch.bfloat16, torch.float16):
+        ds = B.Datastore.from_fp32(X.cuda(), dt)
+        ws = B.alloc_workspace(Q, ds, k)
+        ids, sc = B.ralm_retrieve_topk_ex(Qm.cuda(), ds, k, workspace=ws)
+        c = B.ralm_workspace_counters(ws)
+        assert c["unanswered"] == 0 and c["ladder_overflows"] == 0, c
+        wi, wsc = oracle.retrieve_topk(Qm.numpy(), X.numpy(), k)
+        assert np.array_equal(ids.cpu().numpy(), wi) and np.array_equal(sc.cpu().numpy(), wsc)
+        e = B.ralm_workspace_stage_entries(ws)
+        assert e[0] % Q == 0 and e[0] // Q <= 16384
+
+
 def test_list_entries_per_stage_are_reported(B, oracle):
     """The ladder's diagnostic: per stage, the entries the lists held when it ended.  Stage 0 keeps
     every score of the rows it visits, so its sum is exactly rows visited x Q; every later stage holds
