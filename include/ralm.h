@@ -130,7 +130,7 @@ typedef struct {
  * datastore for the scan (N*d*2 bytes, rebuilt on every call; skipped if the
  * device has no room for it).  Batches of up to 768 queries scan the fp32 rows
  * as they are (21M x 768: about 9.3 ms for up to 64 queries, the rate at which
- * HBM delivers the rows; 14.4 ms for 256, 25 ms for 512), and hold no copy.  Calls are serialised.  Meant for convenience; a caller that
+ * HBM delivers the rows; 14 ms for 256, 25 ms for 512), and hold no copy.  Calls are serialised.  Meant for convenience; a caller that
  * retrieves large batches repeatedly keeps a scan copy and uses the full form.
  * A query that the full form would leave unanswered (see
  * ralm_retrieve_topk_ex) makes the call retry through ralm_retrieve_topk_seq;

@@ -22,8 +22,8 @@
 //                       (by choosing which global chunk each lane fetches) so that the MFMA
 //                       operand reads (32 rows, same chunk) are free of bank conflicts.
 //   scan_staged_kernel  global -> registers -> LDS, double buffered: launches that keep every
-//                       score: the first, small stage of a ladder over fp32 rows or with a
-//                       partial last tile, and the blocks of the sequential ladder.  Otherwise
+//                       score: the first, small stage of a ladder with a partial last tile,
+//                       and the blocks of the sequential ladder.  Otherwise
 //                       the first stage runs in scan_dma_kernel<.., ALL>, which writes each
 //                       score to the list slot that its row's place in the launch determines.
 //
@@ -895,7 +895,18 @@ hipError_t launch_scan(const ScanParams &p, int n_cu, hipStream_t stream)
     // Launches whose thresholds admit everything (the first, tiny stage of the ladder) append
     // nearly every score: they take the staged kernel, whose epilogue writes to the global lists
     // with one atomic per lane and block.  fp32 rows always do (they are rounded on the way in).
+    // a launch that keeps every score into empty lists, all of its tiles full: fixed list positions
+    const int64_t last_tile = (p.tile_begin + p.n_row_tiles - 1) * p.tile_stride;
+    const bool all_kept = !p.park_pushes && p.lists_empty && p.tile_skip == 0 && p.n_row_tiles > 0 &&
+                          (last_tile + 1) * SCAN_BM <= p.N && p.n_row_tiles * SCAN_BM <= (int64_t)p.cap && p.cap % 2 == 0;
     if (p.in_dtype == DT_F32) {
+        if (all_kept) {
+            const int bn = scan_bn_for(p.Q);
+            if (bn == 32) return launch_dma_variant<false, 4, 1, 1, 1, 64, 4, false, 3, 0, true, true>(p, n_cu, stream);
+            if (bn == 64) return launch_dma_variant<false, 4, 1, 1, 2, 64, 3, false, 3, 2, true, true>(p, n_cu, stream);
+            if (bn == 128) return launch_dma_variant<false, 2, 4, 4, 1, 32, 3, false, 3, 0, true, true>(p, n_cu, stream);
+            return launch_dma_variant<false, 2, 4, 4, 2, 32, 2, false, 2, 0, true, true>(p, n_cu, stream);
+        }
         // fp32 rows: batches of one query tile stream them as they are and round on the way to the
         // matrix cores (32-element strips for 128 and 256 queries: an fp32 strip row is 128 bytes)
         if (p.park_pushes && p.Q <= 32) return launch_dma_variant<false, 4, 1, 1, 1, 64, 4, true, 3, 0, true>(p, n_cu, stream);
@@ -912,9 +923,7 @@ hipError_t launch_scan(const ScanParams &p, int n_cu, hipStream_t stream)
         // pipelined kernel with stores to fixed list positions; its tiles must all be full and fit
         // the lists.  (One 256 x 256 tile takes the staged kernel 125 us, mostly its epilogue's
         // atomics and its shallow pipeline.)
-        const int64_t last_tile = (p.tile_begin + p.n_row_tiles - 1) * p.tile_stride;
-        if (p.lists_empty && p.tile_skip == 0 && p.n_row_tiles > 0 &&
-            (last_tile + 1) * SCAN_BM <= p.N && p.n_row_tiles * SCAN_BM <= (int64_t)p.cap && p.cap % 2 == 0) {
+        if (all_kept) {
             const int bn = scan_bn_for(p.Q);
             if (p.in_dtype == DT_F16) {
                 if (bn == 32) return launch_dma_variant<true, 4, 1, 2, 1, 64, 4, false, 3, 0, false, true>(p, n_cu, stream);
